@@ -1,0 +1,12 @@
+"""CPU oracle (test infrastructure only): see expm_oracle.c for what it computes and how it is pinned."""
+from .expm_oracle import (  # noqa: F401
+    build_oracle,
+    oracle_expm,
+    oracle_expm_batch,
+    oracle_matmul,
+    oracle_max_threads,
+    oracle_norm1,
+    oracle_select,
+    oracle_select_from_norms,
+    oracle_b16,
+)

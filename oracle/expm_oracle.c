@@ -1,0 +1,356 @@
+/*
+ * CPU oracle for the Taylor scaling-and-squaring matrix exponential of
+ * Sastre et al., "Improving Matrix Exponential for Generative AI Flows: A
+ * Taylor-Based Approach Beyond Paterson-Stockmeyer" (arXiv 2512.20777).
+ *
+ * THIS IS TEST INFRASTRUCTURE.  It is a deliberately plain and slow reference
+ * that the GPU library is checked against; it is not part of the product and
+ * shares no code, header, table or helper with it.  Only the test-suite, the
+ * smoke check and the benchmark's CPU-baseline leg may call it.
+ *
+ * What it computes, per matrix, all in IEEE double (fp32 inputs are widened
+ * exactly by the caller):
+ *   - the order m and scaling s of Algorithm 4 (Sec. 3.3), from ||W||_1 and
+ *     the 1-norm of the explicitly formed W^2, with the bounds of the table
+ *     that follows Algorithm 4;
+ *   - the polynomial the evaluation formulas of Sec. 3.1 equal in exact
+ *     arithmetic, by DIRECT summation of the Taylor series: T_m(A) for
+ *     m in {1,2,4,8} (eq. for T_m(W) in Sec. 2.2) and T_15(A) + b16*A^16 for
+ *     the 15+ approximant (Sec. 3.1, relation y22 = T15 + b16 A^16 with
+ *     b16 = c1^4), A = W/2^s;
+ *   - s repeated squarings (Algorithm 2).
+ * Products are plain triple loops (row i, then k ascending, then column j),
+ * no blocking, no BLAS.  Nothing here uses the evaluation formulas
+ * y02/y12/y22 themselves, so agreement of the GPU path with this file also
+ * checks those formulas against the definition.
+ *
+ * Readings of points the paper leaves open (also listed in the design notes):
+ *   - norm: the 1-norm (max column abs sum), as in the printed algorithms;
+ *   - acceptance test uses E1+E2 <= eps, the scaling uses each E_i separately
+ *     and keeps the larger s (Algorithm 4 as printed);
+ *   - s starts at 0 and is only raised, so a negative ceiling is ignored;
+ *   - a non-finite E_i gives the cap s = 20;
+ *   - m = 0 (zero matrix) returns the identity;
+ *   - inputs are assumed finite (non-finite input is a host-side error path
+ *     of the GPU library, not part of the method).
+ *
+ * Pins (tests/test_oracle_pins.py): the two worked selection examples of the
+ * paper (Remark 1; Sec. 4.2, normal matrix of norm 12.8), closed forms
+ * (diagonal, nilpotent, rotation, Remark-1 matrix), det/trace and inverse
+ * identities, a brute-force long-double series, hand-computed products, and
+ * closed-form switch points of the selection for W = x*I.
+ */
+#include <math.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#define ORACLE_S_CAP 20
+
+/* ||W||_1 = max over columns j of sum_i |w_ij|  (Sec. 1, notation). */
+double oracle_norm1(const double *W, int n)
+{
+    double best = 0.0;
+    for (int j = 0; j < n; ++j) {
+        double sum = 0.0;
+        for (int i = 0; i < n; ++i)
+            sum += fabs(W[(size_t)i * n + j]);
+        if (sum > best)
+            best = sum;
+    }
+    return best;
+}
+
+/* C = A*B, dense row-major n x n, plain triple loop.  Each c_ij is the sum
+ * over k = 0..n-1 in ascending order.  `par` != 0 spreads rows over OpenMP
+ * threads (used for large n only; the arithmetic per element is unchanged). */
+static void matmul_impl(const double *A, const double *B, double *C, int n, int par)
+{
+#pragma omp parallel for schedule(static) if (par)
+    for (int i = 0; i < n; ++i) {
+        double *c = C + (size_t)i * n;
+        for (int j = 0; j < n; ++j)
+            c[j] = 0.0;
+        for (int k = 0; k < n; ++k) {
+            const double a = A[(size_t)i * n + k];
+            const double *b = B + (size_t)k * n;
+            for (int j = 0; j < n; ++j)
+                c[j] += a * b[j];
+        }
+    }
+}
+
+void oracle_matmul(const double *A, const double *B, double *C, int n)
+{
+    matmul_impl(A, B, C, n, 0);
+}
+
+static double factorial(int k)
+{
+    double f = 1.0;
+    for (int i = 2; i <= k; ++i)
+        f *= (double)i;
+    return f;
+}
+
+static double ipow(double x, int k)
+{
+    double p = 1.0;
+    for (int i = 0; i < k; ++i)
+        p *= x;
+    return p;
+}
+
+/* b16 = c1^4 with c1 of the 15+ coefficient table (Sec. 3.1). */
+double oracle_b16(void)
+{
+    const double c1 = 4.018761610201036e-4;
+    return (c1 * c1) * (c1 * c1);
+}
+
+/*
+ * Algorithm 4 on the two norms n1 = ||W||_1 and n2 = ||W^2||_1.
+ * Orders M = [1,2,4,8,15]; bounds per order from the table after Algorithm 4:
+ *   m=1 : E1 = n1^2/2!,            E2 = n1^3/3!
+ *   m=2 : E1 = n2*n1/3!,           E2 = n2*n2/4!
+ *   m=4 : E1 = n2^2*n1/5!,         E2 = n2^2*n2/6!
+ *   m=8 : E1 = n2^4*n1/9!,         E2 = n2^4*n2/10!
+ *   m=15: E1 = |1/16!-b16|*n2^8,   E2 = n2^8*n1/17!
+ * First order with E1+E2 <= eps wins with s=0; otherwise m=15 and
+ * s = max_i ceil(log2(E_i/eps)/(15+i)), i=1,2, capped at 20.
+ * n2 is not looked at when n1 == 0 or the m=1 test passes.
+ */
+void oracle_select_from_norms(double n1, double n2, double eps, int *m_out, int *s_out)
+{
+    int m = 0, s = 0;
+    double E1 = 0.0, E2 = 0.0;
+    int found = 0;
+
+    if (n1 == 0.0) {
+        *m_out = 0;
+        *s_out = 0;
+        return;
+    }
+    /* m = 1 */
+    m = 1;
+    E1 = n1 * n1 / factorial(2);
+    E2 = n1 * n1 * n1 / factorial(3);
+    if (E1 + E2 <= eps)
+        found = 1;
+
+    if (!found) {
+        const int Ms[3] = {2, 4, 8};
+        for (int t = 0; t < 3 && !found; ++t) {
+            m = Ms[t];
+            const int k = m / 2;
+            const double pk = ipow(n2, k);
+            E1 = pk * n1 / factorial(m + 1);
+            E2 = pk * n2 / factorial(m + 2);
+            if (E1 + E2 <= eps)
+                found = 1;
+        }
+    }
+    if (!found) {
+        m = 15;
+        const double p8 = ipow(n2, 8);
+        E1 = fabs(1.0 / factorial(16) - oracle_b16()) * p8;
+        E2 = p8 * n1 / factorial(17);
+        if (E1 + E2 <= eps)
+            found = 1;
+    }
+    if (!found) {
+        const double E[2] = {E1, E2};
+        for (int i = 1; i <= 2; ++i) {
+            int s1;
+            if (!isfinite(E[i - 1])) {
+                s1 = ORACLE_S_CAP;
+            } else if (E[i - 1] <= 0.0) {
+                s1 = 0;
+            } else {
+                const double q = ceil(log2(E[i - 1] / eps) / (double)(m + i));
+                s1 = (q > (double)ORACLE_S_CAP) ? ORACLE_S_CAP : (q < 0.0 ? 0 : (int)q);
+            }
+            if (s1 > s)
+                s = s1;
+        }
+    }
+    if (s > ORACLE_S_CAP)
+        s = ORACLE_S_CAP;
+    *m_out = m;
+    *s_out = s;
+}
+
+/*
+ * Selection for one matrix.  Returns n1, n2 (n2 = -1 when W^2 was not needed)
+ * and `near`: 1 when the choice changes if either norm moves by 1e-6 relative
+ * (the four corners (n1(1+-1e-6), n2(1+-1e-6)) are re-run).  W2 (n*n doubles)
+ * is scratch supplied by the caller.
+ */
+static void select_matrix(const double *W, int n, double eps, double *W2, int par,
+                          int *m, int *s, double *n1_out, double *n2_out, int *near)
+{
+    const double n1 = oracle_norm1(W, n);
+    double n2 = -1.0;
+    int need_w2 = 0;
+    if (n1 != 0.0) {
+        /* W^2 is formed only once the m=1 test has failed (Algorithm 4).  The
+         * corner re-runs below need it as soon as the test fails at the
+         * upper corner, which (the bound is monotone in n1) is the first to
+         * fail. */
+        const double hi = n1 * (1.0 + 1e-6);
+        const double worst = hi * hi / 2.0 + hi * hi * hi / 6.0;
+        need_w2 = !(worst <= eps);
+    }
+    if (need_w2) {
+        matmul_impl(W, W, W2, n, par);
+        n2 = oracle_norm1(W2, n);
+    }
+    oracle_select_from_norms(n1, n2 < 0.0 ? 0.0 : n2, eps, m, s);
+    *near = 0;
+    if (n1 != 0.0) {
+        for (int c = 0; c < 4; ++c) {
+            const double f1 = (c & 1) ? 1.0 + 1e-6 : 1.0 - 1e-6;
+            const double f2 = (c & 2) ? 1.0 + 1e-6 : 1.0 - 1e-6;
+            int mc, sc;
+            oracle_select_from_norms(n1 * f1, (n2 < 0.0 ? 0.0 : n2) * f2, eps, &mc, &sc);
+            if (mc != *m || sc != *s)
+                *near = 1;
+        }
+    }
+    *n1_out = n1;
+    *n2_out = n2;
+}
+
+int oracle_select(const double *W, int n, double eps, int *m, int *s,
+                  double *n1, double *n2, int *near)
+{
+    double *W2 = (double *)malloc(sizeof(double) * (size_t)n * n + 8);
+    if (!W2)
+        return -3;
+    select_matrix(W, n, eps, W2, 0, m, s, n1, n2, near);
+    free(W2);
+    return 0;
+}
+
+/*
+ * Algorithm 2 for one matrix: select (m,s), A = W/2^s, X = polynomial by
+ * direct summation, s squarings.  `work` holds 4*n*n doubles.
+ */
+static void expm_matrix(const double *W, int n, double eps, double *X, double *work, int par,
+                        int *m_out, int *s_out, double *n1, double *n2, int *near)
+{
+    const size_t nn = (size_t)n * n;
+    double *A = work, *term = work + nn, *next = work + 2 * nn, *W2 = work + 3 * nn;
+    int m, s;
+    select_matrix(W, n, eps, W2, par, &m, &s, n1, n2, near);
+    *m_out = m;
+    *s_out = s;
+
+    const double scale = ldexp(1.0, -s); /* exact power of two */
+    for (size_t t = 0; t < nn; ++t)
+        A[t] = W[t] * scale;
+
+    /* X = I, term = I */
+    memset(X, 0, sizeof(double) * nn);
+    memset(term, 0, sizeof(double) * nn);
+    for (int i = 0; i < n; ++i) {
+        X[(size_t)i * n + i] = 1.0;
+        term[(size_t)i * n + i] = 1.0;
+    }
+    /* term_k = term_{k-1} * A / k = A^k / k!,  X += term_k  for k = 1..m */
+    for (int k = 1; k <= m; ++k) {
+        if (k == 1) {
+            memcpy(term, A, sizeof(double) * nn);
+        } else {
+            matmul_impl(term, A, next, n, par);
+            const double inv = (double)k;
+            for (size_t t = 0; t < nn; ++t)
+                term[t] = next[t] / inv;
+        }
+        for (size_t t = 0; t < nn; ++t)
+            X[t] += term[t];
+    }
+    if (m == 15) {
+        /* 15+ : add b16 * A^16 = (b16 * 16!) * (A^16/16!) */
+        matmul_impl(term, A, next, n, par);
+        const double w = oracle_b16() * factorial(16);
+        for (size_t t = 0; t < nn; ++t)
+            X[t] += w * (next[t] / 16.0);
+    }
+    /* squaring phase */
+    for (int q = 0; q < s; ++q) {
+        matmul_impl(X, X, next, n, par);
+        memcpy(X, next, sizeof(double) * nn);
+    }
+}
+
+int oracle_expm(const double *W, int n, double eps, double *X, int *m, int *s,
+                double *n1, double *n2, int *near)
+{
+    double *work = (double *)malloc(sizeof(double) * 4 * (size_t)n * n + 8);
+    if (!work)
+        return -3;
+    expm_matrix(W, n, eps, X, work, 0, m, s, n1, n2, near);
+    free(work);
+    return 0;
+}
+
+/*
+ * Batch driver, also the timed CPU baseline.  threads <= 0 means "all the
+ * OpenMP runtime offers".  Matrices of order < 256 are spread over threads
+ * one matrix each; larger ones run one after another with the rows of every
+ * product spread over the threads.  Returns the thread count used, or a
+ * negative value on allocation failure.
+ */
+int oracle_expm_batch(const double *W, int n, int batch, double eps, double *X,
+                      int *m, int *s, double *n1, double *n2, int *near, int threads)
+{
+    const size_t nn = (size_t)n * n;
+    int used = 1;
+#ifdef _OPENMP
+    if (threads <= 0)
+        threads = omp_get_max_threads();
+    used = threads;
+    omp_set_num_threads(threads);
+#else
+    (void)threads;
+#endif
+    int fail = 0;
+    if (n < 256) {
+#pragma omp parallel
+        {
+            double *work = (double *)malloc(sizeof(double) * 4 * nn + 8);
+            if (!work) {
+#pragma omp atomic write
+                fail = 1;
+            }
+#pragma omp for schedule(dynamic, 1)
+            for (int b = 0; b < batch; ++b) {
+                if (work)
+                    expm_matrix(W + (size_t)b * nn, n, eps, X + (size_t)b * nn, work, 0,
+                                &m[b], &s[b], &n1[b], &n2[b], &near[b]);
+            }
+            free(work);
+        }
+    } else {
+        double *work = (double *)malloc(sizeof(double) * 4 * nn + 8);
+        if (!work)
+            return -3;
+        for (int b = 0; b < batch; ++b)
+            expm_matrix(W + (size_t)b * nn, n, eps, X + (size_t)b * nn, work, 1,
+                        &m[b], &s[b], &n1[b], &n2[b], &near[b]);
+        free(work);
+    }
+    return fail ? -3 : used;
+}
+
+int oracle_max_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}

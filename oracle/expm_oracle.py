@@ -1,0 +1,152 @@
+"""ctypes binding of the plain-C oracle in expm_oracle.c.
+
+TEST INFRASTRUCTURE ONLY.  Imported by tests/, by the smoke check and by the
+benchmark's CPU-baseline leg; never by the GPU package.  It marshals numpy
+arrays into the C routines and does no arithmetic of its own beyond widening
+fp32 inputs to fp64 (exact).
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "expm_oracle.c")
+_LIB = os.path.join(_HERE, "libexpm_oracle.so")
+_lib = None
+
+
+def build_oracle(force: bool = False) -> str:
+    """Compile expm_oracle.c with gcc (generic x86-64, no FMA contraction, OpenMP)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O3", "-ffp-contract=off", "-fno-fast-math", "-fopenmp", "-shared", "-fPIC",
+               "-std=c11", "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB):
+            build_oracle()
+        lib = ctypes.CDLL(_LIB)
+        dp = ctypes.POINTER(ctypes.c_double)
+        ip = ctypes.POINTER(ctypes.c_int)
+        lib.oracle_norm1.restype = ctypes.c_double
+        lib.oracle_norm1.argtypes = [dp, ctypes.c_int]
+        lib.oracle_matmul.restype = None
+        lib.oracle_matmul.argtypes = [dp, dp, dp, ctypes.c_int]
+        lib.oracle_b16.restype = ctypes.c_double
+        lib.oracle_b16.argtypes = []
+        lib.oracle_select_from_norms.restype = None
+        lib.oracle_select_from_norms.argtypes = [ctypes.c_double, ctypes.c_double, ctypes.c_double, ip, ip]
+        lib.oracle_select.restype = ctypes.c_int
+        lib.oracle_select.argtypes = [dp, ctypes.c_int, ctypes.c_double, ip, ip, dp, dp, ip]
+        lib.oracle_expm.restype = ctypes.c_int
+        lib.oracle_expm.argtypes = [dp, ctypes.c_int, ctypes.c_double, dp, ip, ip, dp, dp, ip]
+        lib.oracle_expm_batch.restype = ctypes.c_int
+        lib.oracle_expm_batch.argtypes = [dp, ctypes.c_int, ctypes.c_int, ctypes.c_double, dp,
+                                          ip, ip, dp, dp, ip, ctypes.c_int]
+        lib.oracle_max_threads.restype = ctypes.c_int
+        lib.oracle_max_threads.argtypes = []
+        _lib = lib
+    return _lib
+
+
+def _dptr(a: np.ndarray):
+    return a.ctypes.data_as(ctypes.POINTER(ctypes.c_double))
+
+
+def _iptr(a: np.ndarray):
+    return a.ctypes.data_as(ctypes.POINTER(ctypes.c_int))
+
+
+def _as_f64(W) -> np.ndarray:
+    a = np.ascontiguousarray(np.asarray(W), dtype=np.float64)
+    return a
+
+
+def unit_roundoff(dtype) -> float:
+    """u of the working precision the tolerance defaults to (Sec. 3.2: eps >= u)."""
+    return 2.0 ** -24 if np.dtype(dtype) == np.float32 else 2.0 ** -53
+
+
+def oracle_norm1(W) -> float:
+    a = _as_f64(W)
+    assert a.ndim == 2 and a.shape[0] == a.shape[1]
+    return float(_load().oracle_norm1(_dptr(a), a.shape[0]))
+
+
+def oracle_matmul(A, B) -> np.ndarray:
+    a, b = _as_f64(A), _as_f64(B)
+    n = a.shape[0]
+    assert a.shape == (n, n) and b.shape == (n, n)
+    c = np.empty((n, n), dtype=np.float64)
+    _load().oracle_matmul(_dptr(a), _dptr(b), _dptr(c), n)
+    return c
+
+
+def oracle_b16() -> float:
+    return float(_load().oracle_b16())
+
+
+def oracle_select_from_norms(n1: float, n2: float, tol: float) -> Tuple[int, int]:
+    m, s = ctypes.c_int(0), ctypes.c_int(0)
+    _load().oracle_select_from_norms(float(n1), float(n2), float(tol), ctypes.byref(m), ctypes.byref(s))
+    return m.value, s.value
+
+
+def oracle_select(W, tol: float):
+    """Algorithm 4 for one matrix -> dict(m, s, n1, n2, near)."""
+    a = _as_f64(W)
+    n = a.shape[0]
+    m, s, near = ctypes.c_int(0), ctypes.c_int(0), ctypes.c_int(0)
+    n1, n2 = ctypes.c_double(0), ctypes.c_double(0)
+    rc = _load().oracle_select(_dptr(a), n, float(tol), ctypes.byref(m), ctypes.byref(s),
+                               ctypes.byref(n1), ctypes.byref(n2), ctypes.byref(near))
+    if rc != 0:
+        raise MemoryError("oracle_select")
+    return dict(m=m.value, s=s.value, n1=n1.value, n2=n2.value, near=bool(near.value))
+
+
+def oracle_expm(W, tol: float):
+    """Algorithm 2 for one matrix -> (X fp64, dict(m, s, n1, n2, near))."""
+    a = _as_f64(W)
+    n = a.shape[0]
+    X = np.empty((n, n), dtype=np.float64)
+    m, s, near = ctypes.c_int(0), ctypes.c_int(0), ctypes.c_int(0)
+    n1, n2 = ctypes.c_double(0), ctypes.c_double(0)
+    rc = _load().oracle_expm(_dptr(a), n, float(tol), _dptr(X), ctypes.byref(m), ctypes.byref(s),
+                             ctypes.byref(n1), ctypes.byref(n2), ctypes.byref(near))
+    if rc != 0:
+        raise MemoryError("oracle_expm")
+    return X, dict(m=m.value, s=s.value, n1=n1.value, n2=n2.value, near=bool(near.value))
+
+
+def oracle_expm_batch(W, tol: float, threads: int = 0):
+    """Batch [b][n][n] -> (X fp64 [b][n][n], dict of arrays m, s, n1, n2, near, threads)."""
+    a = _as_f64(W)
+    assert a.ndim == 3 and a.shape[1] == a.shape[2]
+    b, n = a.shape[0], a.shape[1]
+    X = np.empty_like(a)
+    m = np.zeros(b, dtype=np.int32)
+    s = np.zeros(b, dtype=np.int32)
+    near = np.zeros(b, dtype=np.int32)
+    n1 = np.zeros(b, dtype=np.float64)
+    n2 = np.zeros(b, dtype=np.float64)
+    used = 0
+    if b > 0 and n > 0:
+        used = _load().oracle_expm_batch(_dptr(a), n, b, float(tol), _dptr(X), _iptr(m), _iptr(s),
+                                         _dptr(n1), _dptr(n2), _iptr(near), int(threads))
+        if used < 0:
+            raise MemoryError("oracle_expm_batch")
+    return X, dict(m=m, s=s, n1=n1, n2=n2, near=near.astype(bool), threads=used)
+
+
+def oracle_max_threads() -> int:
+    return int(_load().oracle_max_threads())
