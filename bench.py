@@ -1,0 +1,192 @@
+#!/usr/bin/env python3
+"""Benchmark of the batched matrix exponential on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C2] [--no-others] [--no-cpu]
+
+A step is one expm() call over one synthetic batch that is already resident in HBM: norms,
+selection of (m, s), polynomial evaluation, squarings and the store of the result.  Prints one
+JSON line: the headline workload plus, under "per_config", the same figures for all workloads.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK = {"hbm": 8000.0, "mfma_f32": 157.3, "mfma_f64": 78.6}  # GB/s, TFLOP/s (MI355X published)
+DEFAULT_STEPS = {"C1": 200, "C2": 200, "C3": 50, "C4": 20, "C5f64": 4, "C5f32": 6}
+DEFAULT_WARMUP = {"C1": 20, "C2": 20, "C3": 10, "C4": 4, "C5f64": 2, "C5f32": 2}
+
+
+def time_steps(ex, torch, d, out, tol, steps, warmup):
+    for _ in range(warmup):
+        ex.expm(d, tol, out=out)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(steps):
+        ex.expm(d, tol, out=out)
+    e1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    return wall_ms / steps, e0.elapsed_time(e1) / steps
+
+
+def kernel_profile(ex, torch, d, out, tol, steps):
+    """Per-kernel-class time from HIP events recorded around every launch on the launch stream."""
+    ex.expm_profile_reset()
+    ex.expm_profile_enable(True)
+    for _ in range(steps):
+        ex.expm(d, tol, out=out)
+    torch.cuda.synchronize()
+    prof = ex.expm_profile_read()
+    ex.expm_profile_enable(False)
+    ex.expm_profile_reset()
+    return prof
+
+
+def time_select(ex, torch, d, tol, steps):
+    ex.expm_select(d, tol)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        ex.expm_select(d, tol)
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3 / steps
+
+
+def cpu_baseline(name, a, tol, workloads):
+    """The oracle, as it stands, on the host cores: whole batch when that takes seconds, else recorded."""
+    import numpy as np
+    from oracle import oracle_expm_batch, oracle_max_threads
+    w = workloads.WORKLOADS[name]
+    if name.startswith("C5"):
+        path = os.path.join(ROOT, "tests", "golden", "c5_samples_%s.npz" % w.dtype)
+        if not os.path.exists(path):
+            return None
+        g = np.load(path)
+        sec = float(g["oracle_seconds"][0])
+        return {"value": w.batch / sec, "unit": "matrices/s", "cores": int(g["oracle_threads"][0]), "kind": "oracle",
+                "sample": "whole batch, %.0f s, recorded when tests/golden/make_c5_samples.py wrote the stored "
+                          "samples (not re-timed in this run)" % sec}
+    reps = {"C1": 200, "C2": 50, "C3": 5, "C4": 1}[name]
+    oracle_expm_batch(a[: max(1, min(4, a.shape[0]))], tol)  # load the library, warm caches
+    t0 = time.perf_counter()
+    used = 0
+    for _ in range(reps):
+        _, info = oracle_expm_batch(a, tol)
+        used = info["threads"]
+    sec = (time.perf_counter() - t0) / reps
+    return {"value": a.shape[0] / sec, "unit": "matrices/s", "cores": int(used), "kind": "oracle",
+            "sample": "whole batch of %d, mean of %d runs, %.4f s per batch" % (a.shape[0], reps, sec)}
+
+
+def run_workload(name, steps, warmup, with_cpu):
+    import numpy as np
+    import torch
+    import paper_2512_20777_amd as ex
+    from paper_2512_20777_amd import workloads
+
+    w = workloads.WORKLOADS[name]
+    a = workloads.make_workload(name)
+    d = torch.from_numpy(a).cuda()
+    out = torch.empty_like(d)
+    ex.expm_reserve(w.n, w.batch, ex.DTYPE_F64 if w.dtype == "f64" else ex.DTYPE_F32)
+    ex.expm(d, w.tol, out=out)
+    torch.cuda.synchronize()
+    stats = ex.expm_get_stats()
+    wall_ms, ev_ms = time_steps(ex, torch, d, out, w.tol, steps, warmup)
+    prof = kernel_profile(ex, torch, d, out, w.tol, max(2, min(steps, 20)))
+    sel_ms = time_select(ex, torch, d, w.tol, max(2, min(steps, 20)))
+
+    wbytes = 8 if w.dtype == "f64" else 4
+    flops = 2.0 * w.n ** 3 * stats["products"]          # products the selection asked for, W^2 counted once
+    algo_bytes = 2.0 * w.batch * w.n * w.n * wbytes      # read W, write e^W
+    res = {
+        "workload": name, "n": w.n, "batch": w.batch, "dtype": w.dtype, "steps": steps, "warmup": warmup,
+        "ms_per_step": wall_ms, "ms_per_step_events": ev_ms,
+        "matrices_per_s": w.batch / (wall_ms * 1e-3),
+        "tflops": flops / (wall_ms * 1e-3) / 1e12,
+        "products": stats["products"], "rounds": stats["rounds"],
+        "hist_m": {str(k): v for k, v in stats["hist_m"].items() if v},
+        "hist_s": {str(i): v for i, v in enumerate(stats["hist_s"]) if v},
+        "select_ms": sel_ms,
+        "kernel_ms_per_step": {k: v["ms"] / max(2, min(steps, 20)) for k, v in prof.items() if v["launches"]},
+    }
+    if stats["fused_path"]:
+        k = prof["fused"]
+        avg_ms = k["ms"] / k["launches"]
+        ach = algo_bytes / (avg_ms * 1e-3) / 1e9
+        res["roofline"] = {"bound": "hbm", "kernel": "small_expm_kernel", "achieved": ach, "peak": PEAK["hbm"],
+                           "unit": "GB/s", "frac": ach / PEAK["hbm"], "traffic": None,
+                           "avg_launch_ms": avg_ms, "mfma_tflops_in_kernel": flops / (avg_ms * 1e-3) / 1e12}
+    else:
+        k = prof["gemm"]
+        peak = PEAK["mfma_f64" if w.dtype == "f64" else "mfma_f32"]
+        ach = k["flops"] / (k["ms"] * 1e-3) / 1e12       # 2 n^3 per launched product / summed launch time
+        res["roofline"] = {"bound": "mfma", "kernel": "gemm_round_kernel", "achieved": ach, "peak": peak,
+                           "unit": "TFLOP/s", "frac": ach / peak, "traffic": None,
+                           "avg_launch_ms": k["ms"] / k["launches"], "launches_per_step": k["launches"] / max(2, min(steps, 20)),
+                           "whole_call_frac": res["tflops"] / peak}
+    if with_cpu:
+        res["cpu_baseline"] = cpu_baseline(name, a, w.tol, workloads)
+    del d, out
+    torch.cuda.empty_cache()
+    return res
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=0)
+    ap.add_argument("--warmup", type=int, default=-1)
+    ap.add_argument("--workload", default="C2")
+    ap.add_argument("--no-others", action="store_true", help="only the headline workload")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this library runs on one GPU; --gpus %d is not supported (batches shard across GPUs "
+              "with no communication, one process per GPU, each running this same benchmark)" % args.gpus,
+              file=sys.stderr)
+        sys.exit(2)
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    import paper_2512_20777_amd as ex
+    ex.load_library()
+
+    head = args.workload
+    steps = args.steps if args.steps > 0 else DEFAULT_STEPS[head]
+    warmup = args.warmup if args.warmup >= 0 else DEFAULT_WARMUP[head]
+    main_res = run_workload(head, steps, warmup, not args.no_cpu)
+    per = [main_res]
+    if not args.no_others:
+        for name in ("C1", "C2", "C3", "C4", "C5f64", "C5f32"):
+            if name == head:
+                continue
+            per.append(run_workload(name, DEFAULT_STEPS[name], DEFAULT_WARMUP[name], not args.no_cpu))
+        per.sort(key=lambda r: r["workload"])
+    from paper_2512_20777_amd import workloads
+    line = {
+        "metric": "matrix exponentials/sec (+ achieved TFLOP/s and fraction of MFMA/HBM roofline per workload)",
+        "value": main_res["matrices_per_s"], "unit": "matrices/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
+        "ms_per_step": main_res["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": main_res["dtype"], "data": "synthetic",
+        "config": {"workload": "%s: %s" % (head, workloads.WORKLOADS[head].note), "n": main_res["n"],
+                   "batch": main_res["batch"], "tol": "unit roundoff of dtype"},
+        "tflops": main_res["tflops"],
+        "roofline": {k: main_res["roofline"][k] for k in ("bound", "achieved", "peak", "unit", "frac", "traffic")},
+        "cpu_baseline": main_res.get("cpu_baseline"),
+        "per_config": per,
+    }
+    print(json.dumps(line))
+    ex.expm_shutdown()
+
+
+if __name__ == "__main__":
+    main()

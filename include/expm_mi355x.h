@@ -1,0 +1,157 @@
+/*
+ * expm_mi355x.h -- C ABI of the MI355X (gfx950) batched matrix exponential.
+ *
+ * Method: Taylor scaling and squaring with dynamic choice of the order m and
+ * the scaling s, and the evaluation formulas beyond Paterson-Stockmeyer, of
+ * Sastre, Faronbi, Alonso, Traver, Ibanez, Lloret, "Improving Matrix
+ * Exponential for Generative AI Flows: A Taylor-Based Approach Beyond
+ * Paterson-Stockmeyer" (arXiv 2512.20777).  Per matrix W and tolerance eps:
+ *   (m, s) by Algorithm 4 (Sec. 3.3) from ||W||_1 and ||W^2||_1;
+ *   A = W / 2^s;  X = T_m(A) by the formulas of Sec. 3.1 (T_1, T_2, T_4, T_8,
+ *   and y22 = T_15+);  X <- X*X  s times  (Algorithm 2).
+ *
+ * All matrices are real, dense, row-major and contiguous: a batch is
+ * [batch][n][n] with element (b, i, j) at offset (b*n + i)*n + j.
+ * Every pointer is labelled HOST or DEVICE below.  Nothing is thrown across
+ * this boundary; every entry point returns a status code.
+ *
+ * Threading: the library keeps one cached device workspace per process, so
+ * calls must not overlap in time (neither from several host threads nor on
+ * several streams).
+ */
+#ifndef EXPM_MI355X_H
+#define EXPM_MI355X_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* dtype argument */
+#define EXPM_DTYPE_F32 0
+#define EXPM_DTYPE_F64 1
+
+/* status codes: 0 success, > 0 warning (results delivered), < 0 error (nothing delivered) */
+#define EXPM_OK                 0
+#define EXPM_WARN_NONFINITE     1  /* some matrix holds NaN/Inf (or its square overflows): its (m,s) is (-1,-1), its result all NaN */
+#define EXPM_WARN_SCALING_CAP   2  /* some matrix reached the cap s = 20 of Algorithm 4: tolerance not guaranteed for it */
+#define EXPM_ERR_INVALID_ARG   -1  /* null pointer, n < 0, batch < 0, unknown dtype, out overlapping A, size overflow */
+#define EXPM_ERR_TOLERANCE     -2  /* tol negative, NaN, or 0 < tol < unit roundoff of dtype (Sec. 3.2 requires eps >= u) */
+#define EXPM_ERR_ALLOC         -3  /* device or pinned-host allocation failed */
+#define EXPM_ERR_HIP           -4  /* a HIP call failed; expm_last_hip_error() returns its hipError_t */
+
+#define EXPM_S_CAP 20  /* largest scaling Algorithm 4 returns */
+
+/*
+ * expm_select -- order and scaling of Algorithm 4 (Sec. 3.3) for every matrix.
+ *
+ *   A      DEVICE, const, [batch][n][n] of dtype; not modified; caller-owned.
+ *   n      matrix order, >= 0.          batch  number of matrices, >= 0.
+ *   dtype  EXPM_DTYPE_F32 or EXPM_DTYPE_F64.
+ *          Limits: n <= 46340; for n above the fused-path limit (64 in fp32, 48 in fp64)
+ *          batch <= 65535 and batch * ceil(n/128)^2 <= 2e9.
+ *   tol    absolute tolerance eps of Algorithm 4; 0 means "unit roundoff of dtype"
+ *          (2^-24 or 2^-53); otherwise must be >= that unit roundoff.
+ *   m_out, s_out   HOST, int32[batch], written on return.  m is one of 0,1,2,4,8,15
+ *          (15 stands for the 15+ approximant); 0 <= s <= 20; (-1,-1) marks a
+ *          non-finite matrix.
+ *
+ * Runs on the null stream and is synchronous: the outputs are valid on return.
+ * Uses the same kernels as expm(), so both always agree on (m, s).
+ * Returns 0, a warning (> 0) or an error (< 0).  n == 0 or batch == 0: success, no work.
+ */
+int expm_select(const void *A, int n, int batch, int dtype, double tol,
+                int32_t *m_out, int32_t *s_out);
+
+/*
+ * expm -- e^W for every matrix of the batch (Algorithm 2 with Algorithm 4, Sec. 3.3,
+ * evaluation formulas of Sec. 3.1).
+ *
+ *   A      DEVICE, const, [batch][n][n] of dtype; not modified.
+ *   out    DEVICE, [batch][n][n] of dtype, must not overlap A; fully overwritten
+ *          (it also serves as scratch while the call is in flight).
+ *   stream hipStream_t as void* (NULL = null stream).  All device work is ordered
+ *          on this stream.
+ *   other arguments as for expm_select.
+ *
+ * Ordering / blocking: for small matrices (n <= 64 in fp32, n <= 48 in fp64) the
+ * whole call is one fused kernel and returns without waiting for the device.  For
+ * larger n the number of product rounds depends on the data, so the call waits on
+ * `stream` until the selection stage has finished (one 256-byte read-back), enqueues
+ * the remaining rounds and returns without waiting for them.
+ *
+ * Returns 0 or an error (< 0).  Warnings are returned when they are known at return
+ * time (the larger-n path); after any call expm_get_stats() reports them.
+ * Ownership: caller owns A and out and must keep them alive until `stream` has
+ * finished the call; the library owns its workspace (see expm_workspace_bytes).
+ */
+int expm(const void *A, int n, int batch, int dtype, double tol, void *out, void *stream);
+
+/*
+ * Bytes of device workspace the library holds for a call of this shape (the fused
+ * small-matrix path needs only the per-matrix records).  The workspace is allocated
+ * on first use, grown when a larger shape arrives, reused otherwise, and released by
+ * expm_shutdown().  Returns 0 for invalid arguments.
+ */
+size_t expm_workspace_bytes(int n, int batch, int dtype);
+
+/* Grow the workspace now (so that later calls of this shape do not allocate). */
+int expm_reserve(int n, int batch, int dtype);
+
+/*
+ * Statistics of the most recent expm()/expm_select() call.  Synchronises with the
+ * stream of that call.  products = sum over matrices of pi(m)+s with pi = 0,0,1,2,3,4
+ * for m = 0,1,2,4,8,15 (cost of the formulas of Sec. 3.1 plus one per squaring).
+ */
+struct expm_stats {
+    int64_t matrices;      /* batch of the call                                   */
+    int64_t products;      /* matrix products the method asked for                */
+    int32_t n;             /* matrix order                                        */
+    int32_t dtype;
+    int32_t rounds;        /* product rounds launched after the W^2 round (0 on the fused path) */
+    int32_t warning;       /* 0, EXPM_WARN_NONFINITE, EXPM_WARN_SCALING_CAP (larger wins) */
+    int32_t fused_path;    /* 1 if the single-kernel small-matrix path ran        */
+    int32_t reserved;
+    int64_t hist_m[6];     /* matrices with m = 0,1,2,4,8,15                      */
+    int64_t hist_s[21];    /* matrices with s = 0..20                             */
+    int64_t nonfinite;     /* matrices flagged (-1,-1)                            */
+};
+int expm_get_stats(struct expm_stats *st /* HOST */);
+
+/*
+ * Kernel timing hooks for benchmarks.  With profiling enabled, expm() brackets every
+ * kernel launch with HIP events on the caller's stream (this adds launch gaps: do not
+ * time throughput with it on).  expm_profile_read() synchronises and returns, per
+ * kernel class, the launch count, the summed event time in milliseconds and the summed
+ * algorithmic FLOPs (2 n^3 per product actually launched) since the last reset.
+ */
+#define EXPM_KCLASS_NORM   0   /* column abs-sum passes and norm reductions */
+#define EXPM_KCLASS_SELECT 1   /* selection / plan / operand preparation    */
+#define EXPM_KCLASS_GEMM   2   /* grouped MFMA product rounds               */
+#define EXPM_KCLASS_FUSED  3   /* single-kernel small-matrix path           */
+#define EXPM_KCLASS_COUNT  4
+struct expm_profile {
+    int64_t launches[EXPM_KCLASS_COUNT];
+    double  ms[EXPM_KCLASS_COUNT];
+    double  flops[EXPM_KCLASS_COUNT];
+    double  bytes[EXPM_KCLASS_COUNT];   /* algorithmic HBM bytes (compulsory reads + writes) */
+};
+int expm_profile_enable(int on);
+int expm_profile_reset(void);
+int expm_profile_read(struct expm_profile *p /* HOST */);
+
+/* Release the workspace and cached events.  Safe to call repeatedly. */
+int expm_shutdown(void);
+
+/* hipError_t of the last failing HIP call (0 if none). */
+int expm_last_hip_error(void);
+
+/* Static, human-readable text for a status code. */
+const char *expm_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* EXPM_MI355X_H */

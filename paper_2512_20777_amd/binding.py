@@ -1,0 +1,185 @@
+"""Thin ctypes binding of the C ABI in include/expm_mi355x.h.
+
+Argument marshalling only: every step of the method runs in the library's HIP kernels.  torch is
+used for device memory and the current stream.  There is no CPU fallback: if the shared library
+has not been built, or no GPU is present, calls raise.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Tuple
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libexpm_mi355x.so")
+_lib = None
+
+DTYPE_F32 = 0
+DTYPE_F64 = 1
+
+EXPM_KCLASS = {"norm": 0, "select": 1, "gemm": 2, "fused": 3}
+
+
+class ExpmError(RuntimeError):
+    def __init__(self, status: int, text: str):
+        super().__init__("expm status %d: %s" % (status, text))
+        self.status = status
+
+
+class _Stats(ctypes.Structure):
+    _fields_ = [
+        ("matrices", ctypes.c_int64), ("products", ctypes.c_int64), ("n", ctypes.c_int32), ("dtype", ctypes.c_int32),
+        ("rounds", ctypes.c_int32), ("warning", ctypes.c_int32), ("fused_path", ctypes.c_int32),
+        ("reserved", ctypes.c_int32), ("hist_m", ctypes.c_int64 * 6), ("hist_s", ctypes.c_int64 * 21),
+        ("nonfinite", ctypes.c_int64),
+    ]
+
+
+class _Profile(ctypes.Structure):
+    _fields_ = [
+        ("launches", ctypes.c_int64 * 4), ("ms", ctypes.c_double * 4), ("flops", ctypes.c_double * 4),
+        ("bytes", ctypes.c_double * 4),
+    ]
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Load the shared library (built in-tree by paper_2512_20777_amd.build); raise if it is missing."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    # torch ships its own HIP runtime; it must be in the process first so that this library binds to
+    # the same runtime instance (two runtimes in one process do not share device allocations)
+    import torch  # noqa: F401
+    if not os.path.exists(_LIB_PATH):
+        raise ExpmError(-100, "shared library %s not built (run `python -m paper_2512_20777_amd.build`); "
+                              "there is no CPU fallback" % _LIB_PATH)
+    lib = ctypes.CDLL(_LIB_PATH)
+    vp, ci, cd = ctypes.c_void_p, ctypes.c_int, ctypes.c_double
+    i32p = ctypes.POINTER(ctypes.c_int32)
+    lib.expm_select.restype = ci
+    lib.expm_select.argtypes = [vp, ci, ci, ci, cd, i32p, i32p]
+    lib.expm.restype = ci
+    lib.expm.argtypes = [vp, ci, ci, ci, cd, vp, vp]
+    lib.expm_workspace_bytes.restype = ctypes.c_size_t
+    lib.expm_workspace_bytes.argtypes = [ci, ci, ci]
+    lib.expm_reserve.restype = ci
+    lib.expm_reserve.argtypes = [ci, ci, ci]
+    lib.expm_get_stats.restype = ci
+    lib.expm_get_stats.argtypes = [ctypes.POINTER(_Stats)]
+    lib.expm_profile_enable.restype = ci
+    lib.expm_profile_enable.argtypes = [ci]
+    lib.expm_profile_reset.restype = ci
+    lib.expm_profile_reset.argtypes = []
+    lib.expm_profile_read.restype = ci
+    lib.expm_profile_read.argtypes = [ctypes.POINTER(_Profile)]
+    lib.expm_shutdown.restype = ci
+    lib.expm_shutdown.argtypes = []
+    lib.expm_last_hip_error.restype = ci
+    lib.expm_last_hip_error.argtypes = []
+    lib.expm_status_string.restype = ctypes.c_char_p
+    lib.expm_status_string.argtypes = [ci]
+    _lib = lib
+    return lib
+
+
+def expm_status_string(status: int) -> str:
+    return load_library().expm_status_string(int(status)).decode()
+
+
+def _check(status: int) -> int:
+    if status < 0:
+        lib = load_library()
+        text = expm_status_string(status)
+        if status in (-3, -4):
+            text += " [hipError %d]" % lib.expm_last_hip_error()
+        raise ExpmError(status, text)
+    return status
+
+
+def _describe(A) -> Tuple[int, int, int]:
+    import torch
+    if not isinstance(A, torch.Tensor) or not A.is_cuda:
+        raise ExpmError(-1, "input must be a torch tensor in device memory")
+    if A.dim() != 3 or A.shape[1] != A.shape[2]:
+        raise ExpmError(-1, "input must have shape [batch][n][n]")
+    if not A.is_contiguous():
+        raise ExpmError(-1, "input must be contiguous (row-major [batch][n][n])")
+    if A.dtype == torch.float32:
+        dt = DTYPE_F32
+    elif A.dtype == torch.float64:
+        dt = DTYPE_F64
+    else:
+        raise ExpmError(-1, "dtype must be float32 or float64")
+    return int(A.shape[1]), int(A.shape[0]), dt
+
+
+def expm_select(A, tol: float = 0.0):
+    """(m, s) per matrix as two int32 numpy arrays, plus the status (0 or a warning code)."""
+    import numpy as np
+    import torch
+    n, batch, dt = _describe(A)
+    m = np.zeros(batch, dtype=np.int32)
+    s = np.zeros(batch, dtype=np.int32)
+    i32p = ctypes.POINTER(ctypes.c_int32)
+    with torch.cuda.device(A.device):
+        torch.cuda.current_stream().synchronize()  # the C entry point runs on the null stream
+        st = load_library().expm_select(ctypes.c_void_p(A.data_ptr()), n, batch, dt, float(tol),
+                                        m.ctypes.data_as(i32p), s.ctypes.data_as(i32p))
+    return m, s, _check(st)
+
+
+def expm(A, tol: float = 0.0, out=None, stream=None):
+    """e^A for a [batch][n][n] device tensor; returns (out, status).  Runs on torch's current stream."""
+    import torch
+    n, batch, dt = _describe(A)
+    if out is None:
+        out = torch.empty_like(A)
+    else:
+        on, ob, odt = _describe(out)
+        if (on, ob, odt) != (n, batch, dt) or out.device != A.device:
+            raise ExpmError(-1, "out must match the input's shape, dtype and device")
+    with torch.cuda.device(A.device):
+        sp = (torch.cuda.current_stream() if stream is None else stream).cuda_stream
+        st = load_library().expm(ctypes.c_void_p(A.data_ptr()), n, batch, dt, float(tol),
+                                 ctypes.c_void_p(out.data_ptr()), ctypes.c_void_p(sp))
+    return out, _check(st)
+
+
+def expm_workspace_bytes(n: int, batch: int, dtype: int) -> int:
+    return int(load_library().expm_workspace_bytes(int(n), int(batch), int(dtype)))
+
+
+def expm_reserve(n: int, batch: int, dtype: int) -> int:
+    return _check(load_library().expm_reserve(int(n), int(batch), int(dtype)))
+
+
+def expm_get_stats() -> dict:
+    st = _Stats()
+    _check(load_library().expm_get_stats(ctypes.byref(st)))
+    return dict(matrices=st.matrices, products=st.products, n=st.n, dtype=st.dtype, rounds=st.rounds,
+                warning=st.warning, fused_path=st.fused_path, nonfinite=st.nonfinite,
+                hist_m=dict(zip((0, 1, 2, 4, 8, 15), list(st.hist_m))), hist_s=list(st.hist_s))
+
+
+def expm_profile_enable(on: bool) -> None:
+    _check(load_library().expm_profile_enable(1 if on else 0))
+
+
+def expm_profile_reset() -> None:
+    _check(load_library().expm_profile_reset())
+
+
+def expm_profile_read() -> dict:
+    p = _Profile()
+    _check(load_library().expm_profile_read(ctypes.byref(p)))
+    return {name: dict(launches=p.launches[i], ms=p.ms[i], flops=p.flops[i], bytes=p.bytes[i])
+            for name, i in EXPM_KCLASS.items()}
+
+
+def expm_shutdown() -> None:
+    if _lib is not None:
+        _lib.expm_shutdown()

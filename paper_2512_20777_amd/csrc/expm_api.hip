@@ -1,0 +1,443 @@
+// C ABI, workspace management and round dispatcher of the gfx950 expm library.
+// Interface contract: include/expm_mi355x.h.
+#include "../../include/expm_mi355x.h"
+#include "expm_internal.h"
+
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <vector>
+
+namespace {
+
+using namespace expmk;
+
+struct Workspace {
+    void *dev = nullptr;      // one device block
+    size_t bytes = 0;
+    int *host_summary = nullptr;  // pinned, 64 ints
+    MatInfo *host_info = nullptr; // pageable mirror for stats / select
+    size_t host_info_cap = 0;
+};
+
+struct LastCall {
+    bool valid = false;
+    int n = 0, batch = 0, dtype = 0;
+    int rounds = 0;
+    int fused = 0;
+    hipStream_t stream = nullptr;
+    MatInfo *info_dev = nullptr;
+    int *summary_dev = nullptr;
+};
+
+struct ProfEvent {
+    hipEvent_t start, stop;
+    int kclass;
+    double flops, bytes;
+};
+
+Workspace g_ws;
+LastCall g_last;
+int g_last_hip_error = 0;
+bool g_profile = false;
+std::vector<ProfEvent> g_events;
+std::vector<hipEvent_t> g_event_pool;
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+int hip_fail(hipError_t e)
+{
+    g_last_hip_error = (int)e;
+    (void)hipGetLastError();
+    return EXPM_ERR_HIP;
+}
+#define EXPM_TRY(expr)                                  \
+    do {                                                \
+        hipError_t e__ = (expr);                        \
+        if (e__ != hipSuccess) return hip_fail(e__);    \
+    } while (0)
+
+struct Layout {
+    size_t info, order, summary, n1, n2, colpart, mats, total;
+    size_t mat_bytes;
+};
+
+// Device workspace layout: control block first, then 7 matrix-stack buffers (W2, T0..T5) for the
+// round-based path.  The fused path only needs the control block.
+Layout make_layout(int n, int batch, int dtype)
+{
+    Layout L{};
+    const size_t w = dtype == EXPM_DTYPE_F64 ? 8 : 4;
+    size_t off = 0;
+    L.summary = off; off = align_up(off + 64 * sizeof(int), 256);
+    L.info = off;    off = align_up(off + (size_t)batch * sizeof(MatInfo), 256);
+    L.order = off;   off = align_up(off + (size_t)batch * sizeof(int), 256);
+    L.n1 = off;      off = align_up(off + (size_t)batch * sizeof(double), 256);
+    L.n2 = off;      off = align_up(off + (size_t)batch * sizeof(double), 256);
+    L.mat_bytes = 0;
+    L.colpart = off;
+    L.mats = off;
+    if (!small_path_supported(n, dtype)) {
+        off = align_up(off + (size_t)batch * general_tiles(n) * n * sizeof(double), 256);
+        L.mats = off;
+        L.mat_bytes = align_up((size_t)batch * n * n * w, 256);
+        off += 7 * L.mat_bytes;
+    }
+    L.total = off;
+    return L;
+}
+
+int ensure_workspace(size_t bytes, int batch)
+{
+    if (!g_ws.host_summary) {
+        hipError_t e = hipHostMalloc(reinterpret_cast<void **>(&g_ws.host_summary), 64 * sizeof(int), hipHostMallocDefault);
+        if (e != hipSuccess) { g_last_hip_error = (int)e; (void)hipGetLastError(); return EXPM_ERR_ALLOC; }
+    }
+    if ((size_t)batch > g_ws.host_info_cap) {
+        MatInfo *p = static_cast<MatInfo *>(realloc(g_ws.host_info, (size_t)batch * sizeof(MatInfo)));
+        if (!p) return EXPM_ERR_ALLOC;
+        g_ws.host_info = p;
+        g_ws.host_info_cap = (size_t)batch;
+    }
+    if (bytes <= g_ws.bytes) return EXPM_OK;
+    if (g_ws.dev) {
+        // earlier calls may still be using the old block
+        hipError_t e = hipDeviceSynchronize();
+        if (e != hipSuccess) return hip_fail(e);
+        (void)hipFree(g_ws.dev);
+        g_ws.dev = nullptr;
+        g_ws.bytes = 0;
+        g_last.valid = false;
+    }
+    void *p = nullptr;
+    hipError_t e = hipMalloc(&p, bytes);
+    if (e != hipSuccess) { g_last_hip_error = (int)e; (void)hipGetLastError(); return EXPM_ERR_ALLOC; }
+    g_ws.dev = p;
+    g_ws.bytes = bytes;
+    return EXPM_OK;
+}
+
+int check_args(const void *A, int n, int batch, int dtype, double &tol)
+{
+    if (n < 0 || batch < 0) return EXPM_ERR_INVALID_ARG;
+    if (dtype != EXPM_DTYPE_F32 && dtype != EXPM_DTYPE_F64) return EXPM_ERR_INVALID_ARG;
+    if ((n > 0 && batch > 0) && A == nullptr) return EXPM_ERR_INVALID_ARG;
+    if (n > 46340) return EXPM_ERR_INVALID_ARG;  // n*n must fit the kernels' int tile arithmetic
+    if ((double)batch * (double)n * (double)n > 9.0e15) return EXPM_ERR_INVALID_ARG;
+    if (!small_path_supported(n, dtype)) {
+        // round-based path: the batch is a grid dimension and (matrices x tiles) must fit an int
+        const double tiles = (double)general_tiles(n);
+        if (batch > 65535 || (double)batch * tiles * tiles > 2.0e9) return EXPM_ERR_INVALID_ARG;
+    }
+    const double u = dtype == EXPM_DTYPE_F64 ? ldexp(1.0, -53) : ldexp(1.0, -24);
+    if (!(tol == tol) || tol < 0.0) return EXPM_ERR_TOLERANCE;
+    if (tol == 0.0) tol = u;
+    if (tol < u) return EXPM_ERR_TOLERANCE;
+    return EXPM_OK;
+}
+
+// ---- profiling brackets ---------------------------------------------------------------------------
+hipEvent_t get_event()
+{
+    if (!g_event_pool.empty()) {
+        hipEvent_t e = g_event_pool.back();
+        g_event_pool.pop_back();
+        return e;
+    }
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+}
+
+struct Bracket {
+    hipStream_t stream;
+    ProfEvent ev{};
+    bool on;
+    Bracket(hipStream_t s, int kclass, double flops, double bytes) : stream(s), on(g_profile)
+    {
+        if (!on) return;
+        ev.start = get_event();
+        ev.stop = get_event();
+        ev.kclass = kclass;
+        ev.flops = flops;
+        ev.bytes = bytes;
+        if (!ev.start || !ev.stop) { on = false; return; }
+        (void)hipEventRecord(ev.start, stream);
+    }
+    ~Bracket()
+    {
+        if (!on) return;
+        (void)hipEventRecord(ev.stop, stream);
+        g_events.push_back(ev);
+    }
+};
+
+int warning_from_flags(int flags)
+{
+    if (flags & 2) return EXPM_WARN_SCALING_CAP;
+    if (flags & 1) return EXPM_WARN_NONFINITE;
+    return EXPM_OK;
+}
+
+struct Bound {
+    GeneralBuffers gb;
+    Layout L;
+};
+
+Bound bind(const void *A, void *out, int n, int batch, int dtype)
+{
+    Bound B;
+    B.L = make_layout(n, batch, dtype);
+    unsigned char *base = static_cast<unsigned char *>(g_ws.dev);
+    B.gb.summary = reinterpret_cast<int *>(base + B.L.summary);
+    B.gb.info = reinterpret_cast<MatInfo *>(base + B.L.info);
+    B.gb.order = reinterpret_cast<int *>(base + B.L.order);
+    B.gb.n1 = reinterpret_cast<double *>(base + B.L.n1);
+    B.gb.n2 = reinterpret_cast<double *>(base + B.L.n2);
+    B.gb.colpart = reinterpret_cast<double *>(base + B.L.colpart);
+    B.gb.base[BUF_W] = const_cast<void *>(A);
+    for (int i = 0; i < 7; ++i) B.gb.base[BUF_W2 + i] = base + B.L.mats + (size_t)i * B.L.mat_bytes;
+    B.gb.base[BUF_OUT] = out;
+    B.gb.ptr_align16 = (((uintptr_t)A | (uintptr_t)out) % 16) == 0;
+    return B;
+}
+
+// Selection stage of the round-based path: norms, W2, (m,s), plan; leaves the summary in pinned memory.
+int run_selection_general(const Bound &B, int n, int batch, int dtype, double tol, hipStream_t stream)
+{
+    const double w = dtype == EXPM_DTYPE_F64 ? 8.0 : 4.0;
+    const double nn = (double)n * n;
+    {
+        Bracket br(stream, EXPM_KCLASS_NORM, 0.0, batch * nn * w);
+        EXPM_TRY(launch_colabs(B.gb, n, batch, dtype, stream));
+        EXPM_TRY(launch_norm_finalize(B.gb, n, batch, 1, stream));
+    }
+    {
+        Bracket br(stream, EXPM_KCLASS_GEMM, 2.0 * nn * n * batch, 2.0 * batch * nn * w);
+        EXPM_TRY(launch_square_round(B.gb, n, batch, dtype, stream));
+    }
+    {
+        Bracket br(stream, EXPM_KCLASS_NORM, 0.0, 0.0);
+        EXPM_TRY(launch_norm_finalize(B.gb, n, batch, 2, stream));
+    }
+    {
+        Bracket br(stream, EXPM_KCLASS_SELECT, 0.0, 0.0);
+        EXPM_TRY(launch_select_plan(B.gb, n, batch, tol, stream));
+    }
+    EXPM_TRY(hipMemcpyAsync(g_ws.host_summary, B.gb.summary, 64 * sizeof(int), hipMemcpyDeviceToHost, stream));
+    EXPM_TRY(hipStreamSynchronize(stream));
+    return EXPM_OK;
+}
+
+void remember(int n, int batch, int dtype, int rounds, int fused, hipStream_t stream, const Bound &B)
+{
+    g_last.valid = true;
+    g_last.n = n; g_last.batch = batch; g_last.dtype = dtype;
+    g_last.rounds = rounds; g_last.fused = fused; g_last.stream = stream;
+    g_last.info_dev = B.gb.info;
+    g_last.summary_dev = B.gb.summary;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t expm_workspace_bytes(int n, int batch, int dtype)
+{
+    double tol = 0.0;
+    int dummy = 0;
+    if (check_args(&dummy, n, batch, dtype, tol) != EXPM_OK) return 0;
+    if (n == 0 || batch == 0) return 0;
+    return make_layout(n, batch, dtype).total;
+}
+
+int expm_reserve(int n, int batch, int dtype)
+{
+    double tol = 0.0;
+    int dummy = 0;
+    int rc = check_args(&dummy, n, batch, dtype, tol);
+    if (rc != EXPM_OK) return rc;
+    if (n == 0 || batch == 0) return EXPM_OK;
+    return ensure_workspace(make_layout(n, batch, dtype).total, batch);
+}
+
+int expm_select(const void *A, int n, int batch, int dtype, double tol, int32_t *m_out, int32_t *s_out)
+{
+    int rc = check_args(A, n, batch, dtype, tol);
+    if (rc != EXPM_OK) return rc;
+    if (batch > 0 && (m_out == nullptr || s_out == nullptr)) return EXPM_ERR_INVALID_ARG;
+    if (batch == 0) return EXPM_OK;
+    if (n == 0) {
+        for (int b = 0; b < batch; ++b) { m_out[b] = 0; s_out[b] = 0; }
+        return EXPM_OK;
+    }
+    rc = ensure_workspace(make_layout(n, batch, dtype).total, batch);
+    if (rc != EXPM_OK) return rc;
+    hipStream_t stream = nullptr;
+    const Bound B = bind(A, nullptr, n, batch, dtype);
+    int flags = 0;
+    if (small_path_supported(n, dtype)) {
+        EXPM_TRY(launch_small(A, nullptr, n, batch, dtype, tol, 1, B.gb.info, stream));
+        remember(n, batch, dtype, 0, 1, stream, B);
+    } else {
+        rc = run_selection_general(B, n, batch, dtype, tol, stream);
+        if (rc != EXPM_OK) return rc;
+        remember(n, batch, dtype, 0, 0, stream, B);
+    }
+    EXPM_TRY(hipMemcpyAsync(g_ws.host_info, B.gb.info, (size_t)batch * sizeof(MatInfo), hipMemcpyDeviceToHost, stream));
+    EXPM_TRY(hipStreamSynchronize(stream));
+    for (int b = 0; b < batch; ++b) {
+        m_out[b] = g_ws.host_info[b].m;
+        s_out[b] = g_ws.host_info[b].s;
+        flags |= g_ws.host_info[b].flags;
+    }
+    return warning_from_flags(flags);
+}
+
+int expm(const void *A, int n, int batch, int dtype, double tol, void *out, void *stream_v)
+{
+    int rc = check_args(A, n, batch, dtype, tol);
+    if (rc != EXPM_OK) return rc;
+    if (n == 0 || batch == 0) return EXPM_OK;
+    if (out == nullptr) return EXPM_ERR_INVALID_ARG;
+    {
+        const size_t bytes = (size_t)batch * n * n * (dtype == EXPM_DTYPE_F64 ? 8 : 4);
+        const uintptr_t a0 = (uintptr_t)A, o0 = (uintptr_t)out;
+        if (a0 < o0 + bytes && o0 < a0 + bytes) return EXPM_ERR_INVALID_ARG;  // overlap
+        if ((a0 | o0) % (dtype == EXPM_DTYPE_F64 ? 8 : 4)) return EXPM_ERR_INVALID_ARG;
+    }
+    hipStream_t stream = static_cast<hipStream_t>(stream_v);
+    rc = ensure_workspace(make_layout(n, batch, dtype).total, batch);
+    if (rc != EXPM_OK) return rc;
+    const Bound B = bind(A, out, n, batch, dtype);
+    const double w = dtype == EXPM_DTYPE_F64 ? 8.0 : 4.0;
+    const double nn = (double)n * n;
+
+    if (small_path_supported(n, dtype)) {
+        // one kernel, nothing read back: warnings of this path surface through expm_get_stats()
+        {
+            Bracket br(stream, EXPM_KCLASS_FUSED, 0.0, 2.0 * batch * nn * w);
+            EXPM_TRY(launch_small(A, out, n, batch, dtype, tol, 0, B.gb.info, stream));
+        }
+        remember(n, batch, dtype, 0, 1, stream, B);
+        return EXPM_OK;
+    }
+
+    rc = run_selection_general(B, n, batch, dtype, tol, stream);
+    if (rc != EXPM_OK) return rc;
+    const int longest = g_ws.host_summary[0];
+    const int flags = g_ws.host_summary[1];
+    {
+        Bracket br(stream, EXPM_KCLASS_SELECT, 0.0, 0.0);
+        EXPM_TRY(launch_prepare(B.gb, n, batch, dtype, stream));
+    }
+    for (int r = 1; r <= longest && r <= kMaxRounds; ++r) {
+        const int active = g_ws.host_summary[2 + r];
+        if (active <= 0) break;
+        Bracket br(stream, EXPM_KCLASS_GEMM, 2.0 * nn * n * active, 2.0 * active * nn * w);
+        EXPM_TRY(launch_chain_round(B.gb, n, active, r, dtype, stream));
+    }
+    remember(n, batch, dtype, longest, 0, stream, B);
+    return warning_from_flags(flags);
+}
+
+int expm_get_stats(struct expm_stats *st)
+{
+    if (!st) return EXPM_ERR_INVALID_ARG;
+    std::memset(st, 0, sizeof(*st));
+    if (!g_last.valid) return EXPM_OK;
+    EXPM_TRY(hipMemcpyAsync(g_ws.host_info, g_last.info_dev, (size_t)g_last.batch * sizeof(MatInfo),
+                            hipMemcpyDeviceToHost, g_last.stream));
+    EXPM_TRY(hipStreamSynchronize(g_last.stream));
+    st->matrices = g_last.batch;
+    st->n = g_last.n;
+    st->dtype = g_last.dtype;
+    st->rounds = g_last.rounds;
+    st->fused_path = g_last.fused;
+    int flags = 0;
+    for (int b = 0; b < g_last.batch; ++b) {
+        const MatInfo &mi = g_ws.host_info[b];
+        flags |= mi.flags;
+        if (mi.m < 0) { st->nonfinite++; continue; }
+        int slot = 0, pi = 0;
+        switch (mi.m) {
+        case 0: slot = 0; pi = 0; break;
+        case 1: slot = 1; pi = 0; break;
+        case 2: slot = 2; pi = 1; break;
+        case 4: slot = 3; pi = 2; break;
+        case 8: slot = 4; pi = 3; break;
+        default: slot = 5; pi = 4; break;
+        }
+        st->hist_m[slot]++;
+        if (mi.s >= 0 && mi.s <= EXPM_S_CAP) st->hist_s[mi.s]++;
+        st->products += pi + mi.s;
+    }
+    st->warning = warning_from_flags(flags);
+    return EXPM_OK;
+}
+
+int expm_profile_enable(int on)
+{
+    g_profile = on != 0;
+    return EXPM_OK;
+}
+
+int expm_profile_reset(void)
+{
+    for (auto &e : g_events) {
+        g_event_pool.push_back(e.start);
+        g_event_pool.push_back(e.stop);
+    }
+    g_events.clear();
+    return EXPM_OK;
+}
+
+int expm_profile_read(struct expm_profile *p)
+{
+    if (!p) return EXPM_ERR_INVALID_ARG;
+    std::memset(p, 0, sizeof(*p));
+    for (auto &e : g_events) {
+        EXPM_TRY(hipEventSynchronize(e.stop));
+        float ms = 0.f;
+        EXPM_TRY(hipEventElapsedTime(&ms, e.start, e.stop));
+        p->launches[e.kclass]++;
+        p->ms[e.kclass] += ms;
+        p->flops[e.kclass] += e.flops;
+        p->bytes[e.kclass] += e.bytes;
+    }
+    return EXPM_OK;
+}
+
+int expm_shutdown(void)
+{
+    expm_profile_reset();
+    for (auto e : g_event_pool) (void)hipEventDestroy(e);
+    g_event_pool.clear();
+    if (g_ws.dev) {
+        (void)hipDeviceSynchronize();
+        (void)hipFree(g_ws.dev);
+    }
+    if (g_ws.host_summary) (void)hipHostFree(g_ws.host_summary);
+    free(g_ws.host_info);
+    g_ws = Workspace{};
+    g_last = LastCall{};
+    return EXPM_OK;
+}
+
+int expm_last_hip_error(void) { return g_last_hip_error; }
+
+const char *expm_status_string(int status)
+{
+    switch (status) {
+    case EXPM_OK: return "success";
+    case EXPM_WARN_NONFINITE: return "warning: non-finite matrix in the batch (its result is NaN)";
+    case EXPM_WARN_SCALING_CAP: return "warning: scaling parameter reached its cap of 20";
+    case EXPM_ERR_INVALID_ARG: return "error: invalid argument";
+    case EXPM_ERR_TOLERANCE: return "error: tolerance is negative, NaN or below the unit roundoff of dtype";
+    case EXPM_ERR_ALLOC: return "error: allocation failed";
+    case EXPM_ERR_HIP: return "error: a HIP call failed (see expm_last_hip_error)";
+    default: return "unknown status";
+    }
+}
+
+}  // extern "C"

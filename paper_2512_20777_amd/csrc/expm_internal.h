@@ -1,0 +1,271 @@
+// Internal declarations shared by the HIP translation units of the gfx950 expm library.
+// Not part of the public interface (that is include/expm_mi355x.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace expmk {
+
+// ---------------------------------------------------------------------------------------------
+// Coefficients of the evaluation formulas (Sec. 3.1 of arXiv 2512.20777, the two coefficient
+// tables), as printed, in double.  The fp32 path rounds each (scaled) coefficient to float.
+// ---------------------------------------------------------------------------------------------
+// order 8:  y02 = A2 (c1 A2 + c2 A);  T8 = (y02 + c3 A2 + c4 A)(y02 + c5 A2) + c6 y02 + A2/2 + A + I
+#define EXPM_T8_C1 4.980119205559973e-3
+#define EXPM_T8_C2 1.992047682223989e-2
+#define EXPM_T8_C3 7.665265321119147e-2
+#define EXPM_T8_C4 8.765009801785554e-1
+#define EXPM_T8_C5 1.225521150112075e-1
+#define EXPM_T8_C6 2.974307204847627e0
+// order 15+:  y02 = A2 (c1 A2 + c2 A)
+//             y12 = (y02 + c3 A2 + c4 A)(y02 + c5 A2) + c6 y02 + c7 A2
+//             y22 = (y12 + c8 A2 + c9 A)(y12 + c10 y02 + c11 A) + c12 y12 + c13 y02 + c14 A2 + c15 A + c16 I
+#define EXPM_T15_C1 4.018761610201036e-4
+#define EXPM_T15_C2 2.945531440279683e-3
+#define EXPM_T15_C3 -8.709066576837676e-3
+#define EXPM_T15_C4 4.017568440673568e-1
+#define EXPM_T15_C5 3.230762888122312e-2
+#define EXPM_T15_C6 5.768988513026145e0
+#define EXPM_T15_C7 2.338576034271299e-2
+#define EXPM_T15_C8 2.381070373870987e-1
+#define EXPM_T15_C9 2.224209172496374e0
+#define EXPM_T15_C10 -5.792361707073261e0
+#define EXPM_T15_C11 -4.130276365929783e-2
+#define EXPM_T15_C12 1.040801735231354e1
+#define EXPM_T15_C13 -6.331712455883370e1
+#define EXPM_T15_C14 3.484665863364574e-1
+#define EXPM_T15_C15 1.0
+#define EXPM_T15_C16 1.0
+
+constexpr int kSCap = 20;          // cap on s (Algorithm 4, last lines)
+constexpr int kMaxRounds = 3 + kSCap;  // product rounds after the W^2 round: 3 for 15+, one per squaring
+
+// Per-matrix record produced by the selection stage.
+struct MatInfo {
+    int m;      // 0,1,2,4,8,15 ; -1 = non-finite input
+    int s;      // 0..20        ; -1 = non-finite input
+    int len;    // product rounds still to run after the W^2 round
+    int flags;  // bit0 non-finite, bit1 s hit the cap
+};
+
+// ---------------------------------------------------------------------------------------------
+// Algorithm 4 (Sec. 3.3) on the two norms n1 = ||W||_1, n2 = ||W^2||_1, tolerance eps.
+// Bounds per order from the table that follows Algorithm 4.  All in double.
+// ---------------------------------------------------------------------------------------------
+__host__ __device__ inline void select_order_scaling(double n1, double n2, double eps, int &m, int &s, int &flags)
+{
+    flags = 0;
+    if (!(n1 == n1) || !(n2 == n2) || n1 > 1.7976931348623157e308 || n2 > 1.7976931348623157e308) {
+        m = -1; s = -1; flags = 1;
+        return;
+    }
+    m = 0; s = 0;
+    if (n1 == 0.0) return;
+    // 1/(m+1)!, 1/(m+2)! for m = 1, 2, 4, 8 ; for 15+: |1/16! - b16|, 1/17!
+    const double inv2 = 0.5, inv6 = 1.0 / 6.0, inv24 = 1.0 / 24.0, inv120 = 1.0 / 120.0, inv720 = 1.0 / 720.0;
+    const double inv9f = 1.0 / 362880.0, inv10f = 1.0 / 3628800.0;
+    const double c1 = EXPM_T15_C1;
+    const double b16 = (c1 * c1) * (c1 * c1);
+    const double inv16f = 1.0 / 20922789888000.0, inv17f = 1.0 / 355687428096000.0;
+    double e1, e2;
+    m = 1;
+    e1 = inv2 * n1 * n1;
+    e2 = inv6 * n1 * n1 * n1;
+    if (e1 + e2 <= eps) return;
+    m = 2;
+    e1 = inv6 * n2 * n1;
+    e2 = inv24 * n2 * n2;
+    if (e1 + e2 <= eps) return;
+    m = 4;
+    const double p2 = n2 * n2;
+    e1 = inv120 * p2 * n1;
+    e2 = inv720 * p2 * n2;
+    if (e1 + e2 <= eps) return;
+    m = 8;
+    const double p4 = p2 * p2;
+    e1 = inv9f * p4 * n1;
+    e2 = inv10f * p4 * n2;
+    if (e1 + e2 <= eps) return;
+    m = 15;
+    const double p8 = p4 * p4;
+    const double d16 = inv16f > b16 ? inv16f - b16 : b16 - inv16f;
+    e1 = d16 * p8;
+    e2 = inv17f * p8 * n1;
+    if (e1 + e2 <= eps) return;
+    // scaling from each of the two terms alone, the larger wins (Sec. 3.2, last paragraph)
+    const double ee[2] = {e1, e2};
+    for (int i = 0; i < 2; ++i) {
+        int s1;
+        const double e = ee[i];
+        if (!(e <= 1.7976931348623157e308)) {
+            s1 = kSCap;
+        } else if (e <= 0.0) {
+            s1 = 0;
+        } else {
+            const double q = ceil(log2(e / eps) / (double)(16 + i));
+            s1 = q > (double)kSCap ? kSCap : (q < 0.0 ? 0 : (int)q);
+        }
+        if (s1 > s) s = s1;
+    }
+    if (s >= kSCap) { s = kSCap; flags |= 2; }
+}
+
+// Rounds after the W^2 product: T4 needs 1 more product, T8 2, 15+ 3, plus one per squaring.
+__host__ __device__ inline int chain_length(int m, int s)
+{
+    if (m == 4) return 1;
+    if (m == 8) return 2;
+    if (m == 15) return 3 + s;
+    return 0;
+}
+
+// ---------------------------------------------------------------------------------------------
+// MFMA wrappers.  Both dtypes use the 16x16x4 shape.  Operand layouts coincide:
+//   A operand: lane l holds A[i = l%16][k = l/16]
+//   B operand: lane l holds B[k = l/16][j = l%16]
+// The result layouts differ in the row index (checked on the device with a probe):
+//   f32: lane l, register v (0..3) holds C[i = 4*(l/16) + v][j = l%16]
+//   f64: lane l, register v (0..3) holds C[i = 4*v + l/16][j = l%16]
+// ---------------------------------------------------------------------------------------------
+typedef double v4d __attribute__((ext_vector_type(4)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+template <typename T> struct Mfma;
+template <> struct Mfma<double> {
+    using acc_t = v4d;
+    static __device__ __forceinline__ acc_t run(double a, double b, acc_t c)
+    {
+        return __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, c, 0, 0, 0);
+    }
+    // row inside the 16x16 tile held by register v of a lane in 16-lane group g
+    static __device__ __forceinline__ int row(int g, int v) { return 4 * v + g; }
+};
+template <> struct Mfma<float> {
+    using acc_t = v4f;
+    static __device__ __forceinline__ acc_t run(float a, float b, acc_t c)
+    {
+        return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
+    }
+    static __device__ __forceinline__ int row(int g, int v) { return 4 * g + v; }
+};
+
+// ---------------------------------------------------------------------------------------------
+// Buffers of the round-based (larger n) path, one [batch][n][n] array each.
+// ---------------------------------------------------------------------------------------------
+enum Buf : int { BUF_W = 0, BUF_W2 = 1, BUF_T0 = 2, BUF_T1 = 3, BUF_T2 = 4, BUF_T3 = 5, BUF_T4 = 6, BUF_T5 = 7,
+                 BUF_OUT = 8, BUF_COUNT = 9 };
+
+// One product round for one matrix:
+//   t      = acc_scale * (L*R) + sum_i g[i] * S_i
+//   out_j  = a[j] * t + sum_i b[j][i] * S_i + d[j] * I
+// S_i are up to four source matrices read element-wise, out_j up to four outputs.
+template <typename T> struct Step {
+    int L, R;
+    T acc_scale;
+    int nsrc;
+    int src[4];
+    T g[4];
+    int nout;
+    int dst[4];
+    T a[4];
+    T b[4][4];
+    T d[4];
+};
+
+// Build the round `r` (1-based, after the W^2 round) of the chain for order m and scaling s.
+// With sigma = 2^-s:  A = sigma W, A2 = sigma^2 W2.  The power-of-two factors are folded into
+// the coefficients (exact), so W and W2 are never rescaled in memory.
+template <typename T>
+__device__ __forceinline__ Step<T> build_step(int m, int s, int r)
+{
+    Step<T> st;
+    st.L = BUF_T0; st.R = BUF_T1; st.acc_scale = (T)1; st.nsrc = 0; st.nout = 1;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        st.src[i] = BUF_W; st.g[i] = (T)0; st.dst[i] = BUF_OUT; st.a[i] = (T)1; st.d[i] = (T)0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) st.b[i][j] = (T)0;
+    }
+    if (m == 4) {
+        // T4 = L*R + A + I with L = (A2/4 + A)/3 + I, R = A2/2 prepared beforehand (s = 0 here)
+        st.L = BUF_T0; st.R = BUF_T1;
+        st.nsrc = 1; st.src[0] = BUF_W; st.g[0] = (T)1;
+        st.nout = 1; st.dst[0] = BUF_OUT; st.a[0] = (T)1; st.d[0] = (T)1;
+    } else if (m == 8) {
+        if (r == 1) {
+            // y02 = A2 * (c1 A2 + c2 A); emit both factors of T8 and its additive part
+            st.L = BUF_W2; st.R = BUF_T0;
+            st.nsrc = 2; st.src[0] = BUF_W2; st.src[1] = BUF_W;
+            st.nout = 3;
+            st.dst[0] = BUF_T1; st.a[0] = (T)1; st.b[0][0] = (T)EXPM_T8_C3; st.b[0][1] = (T)EXPM_T8_C4;
+            st.dst[1] = BUF_T2; st.a[1] = (T)1; st.b[1][0] = (T)EXPM_T8_C5;
+            st.dst[2] = BUF_T3; st.a[2] = (T)EXPM_T8_C6; st.b[2][0] = (T)0.5; st.b[2][1] = (T)1; st.d[2] = (T)1;
+        } else {
+            st.L = BUF_T1; st.R = BUF_T2;
+            st.nsrc = 1; st.src[0] = BUF_T3; st.g[0] = (T)1;
+            st.nout = 1; st.dst[0] = BUF_OUT; st.a[0] = (T)1;
+        }
+    } else {  // m == 15
+        const double sg = __builtin_ldexp(1.0, -s), sg2 = __builtin_ldexp(1.0, -2 * s);
+        const int poly_dst = (s & 1) ? BUF_T1 : BUF_OUT;  // so that s squarings later end in OUT
+        if (r == 1) {
+            st.L = BUF_W2; st.R = BUF_T0; st.acc_scale = (T)sg2;  // y02 = A2 * (c1 A2 + c2 A)
+            st.nsrc = 2; st.src[0] = BUF_W2; st.src[1] = BUF_W;
+            st.nout = 4;
+            st.dst[0] = BUF_T1; st.b[0][0] = (T)(EXPM_T15_C3 * sg2); st.b[0][1] = (T)(EXPM_T15_C4 * sg);
+            st.dst[1] = BUF_T2; st.b[1][0] = (T)(EXPM_T15_C5 * sg2);
+            st.dst[2] = BUF_T3; st.a[2] = (T)EXPM_T15_C6; st.b[2][0] = (T)(EXPM_T15_C7 * sg2);
+            st.dst[3] = BUF_T4;  // y02 itself
+        } else if (r == 2) {
+            st.L = BUF_T1; st.R = BUF_T2;  // y12 = L*R + (c6 y02 + c7 A2)
+            st.nsrc = 4; st.src[0] = BUF_T3; st.src[1] = BUF_T4; st.src[2] = BUF_W2; st.src[3] = BUF_W;
+            st.g[0] = (T)1;
+            st.nout = 3;
+            st.dst[0] = BUF_T0; st.b[0][2] = (T)(EXPM_T15_C8 * sg2); st.b[0][3] = (T)(EXPM_T15_C9 * sg);
+            st.dst[1] = BUF_T5; st.b[1][1] = (T)EXPM_T15_C10; st.b[1][3] = (T)(EXPM_T15_C11 * sg);
+            st.dst[2] = BUF_T3; st.a[2] = (T)EXPM_T15_C12; st.b[2][1] = (T)EXPM_T15_C13;
+            st.b[2][2] = (T)(EXPM_T15_C14 * sg2); st.b[2][3] = (T)(EXPM_T15_C15 * sg); st.d[2] = (T)EXPM_T15_C16;
+        } else if (r == 3) {
+            st.L = BUF_T0; st.R = BUF_T5;  // y22 = L*R + additive part
+            st.nsrc = 1; st.src[0] = BUF_T3; st.g[0] = (T)1;
+            st.nout = 1; st.dst[0] = poly_dst;
+        } else {
+            // squaring q = r-3 of s: ping-pong between OUT and T1, arranged to finish in OUT
+            const int q = r - 3;
+            const bool cur_is_out = (((s - (q - 1)) & 1) == 0);
+            st.L = st.R = cur_is_out ? BUF_OUT : BUF_T1;
+            st.nsrc = 0; st.nout = 1; st.dst[0] = cur_is_out ? BUF_T1 : BUF_OUT;
+        }
+    }
+    return st;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Host-side launchers implemented by the kernel translation units.
+// ---------------------------------------------------------------------------------------------
+struct GeneralBuffers {
+    void *base[BUF_COUNT];   // device pointers, [batch][n][n] each (BUF_W = input, BUF_OUT = output)
+    double *colpart;         // [batch][tiles][n] column abs-sum partials
+    double *n1, *n2;         // [batch]
+    MatInfo *info;           // [batch]
+    int *order;              // [batch] matrices sorted by chain length, longest first
+    int *summary;            // [64] : [0] longest chain, [1] OR of flags, [2+r] matrices active in round r
+    bool ptr_align16;        // input and output pointers are 16-byte aligned (vector loads allowed)
+};
+
+// small fused path
+bool small_path_supported(int n, int dtype);
+hipError_t launch_small(const void *A, void *out, int n, int batch, int dtype, double eps, int select_only,
+                        MatInfo *info, hipStream_t stream);
+
+// larger-n path
+int general_tiles(int n);
+hipError_t launch_colabs(const GeneralBuffers &gb, int n, int batch, int dtype, hipStream_t stream);
+hipError_t launch_norm_finalize(const GeneralBuffers &gb, int n, int batch, int which, hipStream_t stream);
+hipError_t launch_square_round(const GeneralBuffers &gb, int n, int batch, int dtype, hipStream_t stream);
+hipError_t launch_select_plan(const GeneralBuffers &gb, int n, int batch, double eps, hipStream_t stream);
+hipError_t launch_prepare(const GeneralBuffers &gb, int n, int batch, int dtype, hipStream_t stream);
+hipError_t launch_chain_round(const GeneralBuffers &gb, int n, int active, int round, int dtype, hipStream_t stream);
+
+}  // namespace expmk

@@ -1,0 +1,90 @@
+"""Host-side checks that need no GPU: the shared library loads, exports every symbol the public
+header declares, and rejects bad arguments before touching the device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "expm_mi355x.h")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    import paper_2512_20777_amd as ex
+    if not os.path.exists(ex.library_path()):
+        from paper_2512_20777_amd.build import build_library
+        build_library()
+    return ex.load_library()
+
+
+def _declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = re.findall(r"^\s*(?:int|size_t|const char \*)\s*\*?\s*(expm\w*)\s*\(", text, flags=re.M)
+    return sorted(set(names))
+
+
+def test_header_declares_the_boundary():
+    names = _declared_functions()
+    for must in ("expm", "expm_select", "expm_workspace_bytes", "expm_get_stats", "expm_status_string"):
+        assert must in names
+
+
+def test_library_exports_every_declared_symbol(lib):
+    for name in _declared_functions():
+        assert hasattr(lib, name), name
+
+
+def test_status_strings(lib):
+    for code in (0, 1, 2, -1, -2, -3, -4):
+        s = lib.expm_status_string(code).decode()
+        assert s and s != "unknown status"
+    assert lib.expm_status_string(77).decode() == "unknown status"
+
+
+def test_argument_validation_happens_before_any_device_work(lib):
+    i32p = ctypes.POINTER(ctypes.c_int32)
+    m = (ctypes.c_int32 * 4)()
+    s = (ctypes.c_int32 * 4)()
+    fake = ctypes.c_void_p(0x1000)  # never dereferenced: every call below must fail in validation
+    null = ctypes.c_void_p(0)
+    mp, sp = ctypes.cast(m, i32p), ctypes.cast(s, i32p)
+    assert lib.expm_select(null, 8, 4, 1, 0.0, mp, sp) == -1          # null input
+    assert lib.expm_select(fake, -1, 4, 1, 0.0, mp, sp) == -1         # n < 0
+    assert lib.expm_select(fake, 8, -2, 1, 0.0, mp, sp) == -1         # batch < 0
+    assert lib.expm_select(fake, 8, 4, 7, 0.0, mp, sp) == -1          # unknown dtype
+    assert lib.expm_select(fake, 8, 4, 1, -1e-8, mp, sp) == -2        # negative tolerance
+    assert lib.expm_select(fake, 8, 4, 1, float("nan"), mp, sp) == -2
+    assert lib.expm_select(fake, 8, 4, 1, 1e-17, mp, sp) == -2        # below fp64 unit roundoff
+    assert lib.expm_select(fake, 8, 4, 0, 1e-9, mp, sp) == -2         # below fp32 unit roundoff
+    assert lib.expm_select(fake, 8, 4, 1, 0.0, ctypes.cast(None, i32p), sp) == -1
+    assert lib.expm(fake, 8, 4, 1, 0.0, null, null) == -1             # null output
+    assert lib.expm(fake, 8, 4, 1, 0.0, fake, null) == -1             # output overlaps input
+    assert lib.expm(fake, 8, 4, 1, 0.0, ctypes.c_void_p(0x1000 + 8 * 64), null) == -1  # partial overlap
+    assert lib.expm(fake, 8, 4, 1, 1e-20, ctypes.c_void_p(0x100000), null) == -2
+    # empty problems succeed without work
+    assert lib.expm(null, 0, 4, 1, 0.0, null, null) == 0
+    assert lib.expm(null, 8, 0, 1, 0.0, null, null) == 0
+    assert lib.expm_select(null, 8, 0, 1, 0.0, mp, sp) == 0
+    assert lib.expm_select(null, 0, 4, 1, 0.0, mp, sp) == 0 and list(m) == [0, 0, 0, 0]
+
+
+def test_workspace_size_formula(lib):
+    assert lib.expm_workspace_bytes(0, 4, 1) == 0
+    assert lib.expm_workspace_bytes(16, -1, 0) == 0
+    small = lib.expm_workspace_bytes(16, 4096, 0)
+    assert 0 < small < 1 << 20                       # fused path: control records only
+    big = lib.expm_workspace_bytes(4096, 4, 1)
+    assert big >= 7 * 4 * 4096 * 4096 * 8            # W2 and six temporaries per matrix
+    assert big < 7.2 * 4 * 4096 * 4096 * 8
+
+
+def test_binding_refuses_host_tensors():
+    import torch
+    import paper_2512_20777_amd as ex
+    with pytest.raises(ex.ExpmError):
+        ex.expm(torch.zeros(2, 4, 4, dtype=torch.float64))
+    with pytest.raises(ex.ExpmError):
+        ex.expm_select(torch.zeros(2, 4, 4, dtype=torch.float64))
