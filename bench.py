@@ -85,7 +85,7 @@ def cpu_baseline(name, a, tol, workloads):
             "sample": "whole batch of %d, mean of %d runs, %.4f s per batch" % (a.shape[0], reps, sec)}
 
 
-def run_workload(name, steps, warmup, with_cpu):
+def run_workload(name, steps, warmup, with_cpu, time_sel=False):
     import numpy as np
     import torch
     import paper_2512_20777_amd as ex
@@ -101,7 +101,7 @@ def run_workload(name, steps, warmup, with_cpu):
     stats = ex.expm_get_stats()
     wall_ms, ev_ms = time_steps(ex, torch, d, out, w.tol, steps, warmup)
     prof = kernel_profile(ex, torch, d, out, w.tol, max(2, min(steps, 20)))
-    sel_ms = time_select(ex, torch, d, w.tol, max(2, min(steps, 20)))
+    sel_ms = time_select(ex, torch, d, w.tol, max(2, min(steps, 20))) if time_sel else None
 
     wbytes = 8 if w.dtype == "f64" else 4
     flops = 2.0 * w.n ** 3 * stats["products"]          # products the selection asked for, W^2 counted once
@@ -147,6 +147,8 @@ def main():
     ap.add_argument("--workload", default="C2")
     ap.add_argument("--no-others", action="store_true", help="only the headline workload")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
+    ap.add_argument("--time-select", action="store_true", help="also time expm_select() alone (adds launches "
+                    "of the product kernel that are not expm() steps)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this library runs on one GPU; --gpus %d is not supported (batches shard across GPUs "
@@ -163,13 +165,13 @@ def main():
     head = args.workload
     steps = args.steps if args.steps > 0 else DEFAULT_STEPS[head]
     warmup = args.warmup if args.warmup >= 0 else DEFAULT_WARMUP[head]
-    main_res = run_workload(head, steps, warmup, not args.no_cpu)
+    main_res = run_workload(head, steps, warmup, not args.no_cpu, args.time_select)
     per = [main_res]
     if not args.no_others:
         for name in ("C1", "C2", "C3", "C4", "C5f64", "C5f32"):
             if name == head:
                 continue
-            per.append(run_workload(name, DEFAULT_STEPS[name], DEFAULT_WARMUP[name], not args.no_cpu))
+            per.append(run_workload(name, DEFAULT_STEPS[name], DEFAULT_WARMUP[name], not args.no_cpu, args.time_select))
         per.sort(key=lambda r: r["workload"])
     from paper_2512_20777_amd import workloads
     line = {
