@@ -50,7 +50,7 @@ extern "C" {
  *   A      DEVICE, const, [batch][n][n] of dtype; not modified; caller-owned.
  *   n      matrix order, >= 0.          batch  number of matrices, >= 0.
  *   dtype  EXPM_DTYPE_F32 or EXPM_DTYPE_F64.
- *          Limits: n <= 46340; for n above the fused-path limit (64 in fp32, 48 in fp64)
+ *          Limits: n <= 46340; for n above the fused-path limit (128 in fp32, 96 in fp64)
  *          batch <= 65535 and batch * ceil(n/128)^2 <= 2e9.
  *   tol    absolute tolerance eps of Algorithm 4; 0 means "unit roundoff of dtype"
  *          (2^-24 or 2^-53); otherwise must be >= that unit roundoff.
@@ -76,7 +76,7 @@ int expm_select(const void *A, int n, int batch, int dtype, double tol,
  *          on this stream.
  *   other arguments as for expm_select.
  *
- * Ordering / blocking: for small matrices (n <= 64 in fp32, n <= 48 in fp64) the
+ * Ordering / blocking: for matrices that fit a compute unit's LDS (n <= 128 in fp32, n <= 96 in fp64) the
  * whole call is one fused kernel and returns without waiting for the device.  For
  * larger n the number of product rounds depends on the data, so the call waits on
  * `stream` until the selection stage has finished (one 256-byte read-back), enqueues

@@ -42,6 +42,7 @@ int g_last_hip_error = 0;
 bool g_profile = false;
 std::vector<ProfEvent> g_events;
 std::vector<hipEvent_t> g_event_pool;
+hipEvent_t g_summary_ready = nullptr;
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
@@ -72,13 +73,15 @@ Layout make_layout(int n, int batch, int dtype)
     L.summary = off; off = align_up(off + 64 * sizeof(int), 256);
     L.info = off;    off = align_up(off + (size_t)batch * sizeof(MatInfo), 256);
     L.order = off;   off = align_up(off + (size_t)batch * sizeof(int), 256);
-    L.n1 = off;      off = align_up(off + (size_t)batch * sizeof(double), 256);
-    L.n2 = off;      off = align_up(off + (size_t)batch * sizeof(double), 256);
+    const size_t nblk = (size_t)general_colblocks(n);
+    L.n1 = off;      off = align_up(off + (size_t)batch * nblk * sizeof(double), 256);
+    L.n2 = off;      off = align_up(off + (size_t)batch * nblk * sizeof(double), 256);
     L.mat_bytes = 0;
     L.colpart = off;
     L.mats = off;
     if (!small_path_supported(n, dtype)) {
-        off = align_up(off + (size_t)batch * general_tiles(n) * n * sizeof(double), 256);
+        // column-sum partials: 32-row chunks for W, one per tile row (>= 64 rows) for W2
+        off = align_up(off + (size_t)batch * general_colchunks(n) * n * sizeof(double), 256);
         L.mats = off;
         L.mat_bytes = align_up((size_t)batch * n * n * w, 256);
         off += 7 * L.mat_bytes;
@@ -126,7 +129,7 @@ int check_args(const void *A, int n, int batch, int dtype, double &tol)
     if ((double)batch * (double)n * (double)n > 9.0e15) return EXPM_ERR_INVALID_ARG;
     if (!small_path_supported(n, dtype)) {
         // round-based path: the batch is a grid dimension and (matrices x tiles) must fit an int
-        const double tiles = (double)general_tiles(n);
+        const double tiles = (double)((n + 63) / 64);
         if (batch > 65535 || (double)batch * tiles * tiles > 2.0e9) return EXPM_ERR_INVALID_ARG;
     }
     const double u = dtype == EXPM_DTYPE_F64 ? ldexp(1.0, -53) : ldexp(1.0, -24);
@@ -210,22 +213,26 @@ int run_selection_general(const Bound &B, int n, int batch, int dtype, double to
     {
         Bracket br(stream, EXPM_KCLASS_NORM, 0.0, batch * nn * w);
         EXPM_TRY(launch_colabs(B.gb, n, batch, dtype, stream));
-        EXPM_TRY(launch_norm_finalize(B.gb, n, batch, 1, stream));
+        EXPM_TRY(launch_colmax(B.gb, n, batch, 1, general_colchunks(n), stream));
     }
+    const int wt0 = choose_tile_shape(n, batch);
     {
         Bracket br(stream, EXPM_KCLASS_GEMM, 2.0 * nn * n * batch, 2.0 * batch * nn * w);
-        EXPM_TRY(launch_square_round(B.gb, n, batch, dtype, stream));
+        EXPM_TRY(launch_square_round(B.gb, n, batch, dtype, wt0, stream));
     }
     {
         Bracket br(stream, EXPM_KCLASS_NORM, 0.0, 0.0);
-        EXPM_TRY(launch_norm_finalize(B.gb, n, batch, 2, stream));
+        EXPM_TRY(launch_colmax(B.gb, n, batch, 2, (n + 32 * wt0 - 1) / (32 * wt0), stream));
     }
     {
         Bracket br(stream, EXPM_KCLASS_SELECT, 0.0, 0.0);
         EXPM_TRY(launch_select_plan(B.gb, n, batch, tol, stream));
     }
+    // the plan summary travels to pinned host memory; g_summary_ready marks the copy, so that the
+    // caller can queue more work behind it before waiting
     EXPM_TRY(hipMemcpyAsync(g_ws.host_summary, B.gb.summary, 64 * sizeof(int), hipMemcpyDeviceToHost, stream));
-    EXPM_TRY(hipStreamSynchronize(stream));
+    if (!g_summary_ready) EXPM_TRY(hipEventCreateWithFlags(&g_summary_ready, hipEventDisableTiming));
+    EXPM_TRY(hipEventRecord(g_summary_ready, stream));
     return EXPM_OK;
 }
 
@@ -282,6 +289,7 @@ int expm_select(const void *A, int n, int batch, int dtype, double tol, int32_t 
     } else {
         rc = run_selection_general(B, n, batch, dtype, tol, stream);
         if (rc != EXPM_OK) return rc;
+        EXPM_TRY(hipEventSynchronize(g_summary_ready));
         remember(n, batch, dtype, 0, 0, stream, B);
     }
     EXPM_TRY(hipMemcpyAsync(g_ws.host_info, B.gb.info, (size_t)batch * sizeof(MatInfo), hipMemcpyDeviceToHost, stream));
@@ -325,17 +333,31 @@ int expm(const void *A, int n, int batch, int dtype, double tol, void *out, void
 
     rc = run_selection_general(B, n, batch, dtype, tol, stream);
     if (rc != EXPM_OK) return rc;
-    const int longest = g_ws.host_summary[0];
-    const int flags = g_ws.host_summary[1];
+    // Work that does not need the host's view of the plan is queued before the wait, so the device
+    // stays busy while the summary is read: operand preparation, and the first chain round over the
+    // whole batch (workgroups of matrices that need no product leave at once).
     {
         Bracket br(stream, EXPM_KCLASS_SELECT, 0.0, 0.0);
         EXPM_TRY(launch_prepare(B.gb, n, batch, dtype, stream));
     }
-    for (int r = 1; r <= longest && r <= kMaxRounds; ++r) {
+    {
+        Bracket br(stream, EXPM_KCLASS_GEMM, 0.0, 0.0);  // its work is filled in once the plan is known
+        EXPM_TRY(launch_chain_round(B.gb, n, batch, 1, dtype, choose_tile_shape(n, batch), stream));
+    }
+    const size_t round1_event = g_events.size();
+    EXPM_TRY(hipEventSynchronize(g_summary_ready));
+    const int longest = g_ws.host_summary[0];
+    const int flags = g_ws.host_summary[1];
+    if (g_profile && round1_event > 0) {
+        const int active1 = longest >= 1 ? g_ws.host_summary[3] : 0;
+        g_events[round1_event - 1].flops = 2.0 * nn * n * active1;
+        g_events[round1_event - 1].bytes = 2.0 * active1 * nn * w;
+    }
+    for (int r = 2; r <= longest && r <= kMaxRounds; ++r) {
         const int active = g_ws.host_summary[2 + r];
         if (active <= 0) break;
         Bracket br(stream, EXPM_KCLASS_GEMM, 2.0 * nn * n * active, 2.0 * active * nn * w);
-        EXPM_TRY(launch_chain_round(B.gb, n, active, r, dtype, stream));
+        EXPM_TRY(launch_chain_round(B.gb, n, active, r, dtype, choose_tile_shape(n, active), stream));
     }
     remember(n, batch, dtype, longest, 0, stream, B);
     return warning_from_flags(flags);
@@ -418,6 +440,7 @@ int expm_shutdown(void)
         (void)hipFree(g_ws.dev);
     }
     if (g_ws.host_summary) (void)hipHostFree(g_ws.host_summary);
+    if (g_summary_ready) { (void)hipEventDestroy(g_summary_ready); g_summary_ready = nullptr; }
     free(g_ws.host_info);
     g_ws = Workspace{};
     g_last = LastCall{};

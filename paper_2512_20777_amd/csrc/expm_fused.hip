@@ -1,0 +1,373 @@
+// Fused single-kernel path for matrices that fit one compute unit's LDS, gfx950.
+//
+// One workgroup per matrix.  The matrix is read once, every step of Algorithm 2 and Algorithm 4
+// (Sec. 3.3 of arXiv 2512.20777) runs on chip -- ||W||_1, W^2 and its norm, the choice of (m, s),
+// the evaluation formulas of Sec. 3.1, the s squarings -- and the result is written once.
+// (m, s) is uniform over the workgroup, so no wavefront diverges and nothing has to be bucketed.
+//
+// Layout on chip: two LDS buffers hold the current left and right operand of a product, each with
+// a pitch chosen so that the MFMA fragment reads of that side are bank-conflict free; everything
+// that is only combined element-wise (A, A^2, y02, the additive part) lives in registers of the
+// lane that owns the element in the MFMA result layout.  Products are 16x16 tiles of MFMA 16x16x4
+// in the matrix dtype on the zero-padded matrix; 1 wave for n <= 16, otherwise 2x2 waves, each
+// owning a TH x TH block of tiles.
+#include "expm_internal.h"
+
+namespace expmk {
+
+namespace {
+
+template <typename T, int NT> struct FusedCfg {
+    static constexpr int NP = 16 * NT;
+    static constexpr int WG = NT == 1 ? 1 : 2;          // waves per dimension
+    static constexpr int TH = (NT + WG - 1) / WG;       // tiles per wave per dimension
+    static constexpr int kThreads = 64 * WG * WG;
+    static constexpr bool kF32 = sizeof(T) == 4;
+    // left operand: 16 lanes read 16 consecutive rows at one k -> pitch = 4*odd words (f32) / 2*odd (f64)
+    static constexpr int LPA = NP + (kF32 ? 4 : 2);
+    // right operand: the four 16-lane groups read four k rows -> pitch = 16*odd elements
+    static constexpr int LPB = kF32 ? (NT % 2 == 0 ? NP + 16 : NP + 32) : (NT % 2 == 0 ? NP + 16 : NP);
+    static constexpr int kBytesP = NP * LPA * (int)sizeof(T);
+    static constexpr int kBytesQ = NP * LPB * (int)sizeof(T);
+    static constexpr int kLds = kBytesP + kBytesQ + (kThreads + 16) * (int)sizeof(double);
+    static_assert(kLds <= 163840, "fused path exceeds the LDS of one compute unit");
+};
+
+template <typename T> struct VecOf;
+template <> struct VecOf<float> { using type = float4; };
+template <> struct VecOf<double> { using type = double2; };
+
+__device__ __forceinline__ double pow2neg_f(int e)
+{
+    return __longlong_as_double((long long)(1023 - e) << 52);
+}
+
+template <typename T, int NT>
+__global__ __launch_bounds__(NT == 1 ? 64 : 256) void fused_expm_kernel(const T *__restrict__ Ain, T *__restrict__ Out,
+                                                                        int n, double eps, int select_only,
+                                                                        MatInfo *__restrict__ info)
+{
+    using C = FusedCfg<T, NT>;
+    using acc_t = typename Mfma<T>::acc_t;
+    constexpr int NP = C::NP, LPA = C::LPA, LPB = C::LPB, TH = C::TH, WG = C::WG;
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    T *P = reinterpret_cast<T *>(smem_raw);                         // left operand layout
+    T *Q = reinterpret_cast<T *>(smem_raw + C::kBytesP);            // right operand layout
+    double *red = reinterpret_cast<double *>(smem_raw + C::kBytesP + C::kBytesQ);
+
+    const int b = blockIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform, kept in a scalar register
+    const int wr = wave / WG, wc = wave % WG;
+    constexpr bool kAllTiles = NT % WG == 0;  // every wave owns a full TH x TH block
+    auto row_ok = [&](int ti) -> bool { return kAllTiles || wr * TH + ti < NT; };
+    auto col_ok = [&](int tj) -> bool { return kAllTiles || wc * TH + tj < NT; };
+    const int lj = lane & 15, lg = lane >> 4;
+    const size_t moff = (size_t)b * n * n;
+    const T *W = Ain + moff;
+
+    // ---- load W into both operand layouts, zero padded -------------------------------------------
+    constexpr int VN = 16 / (int)sizeof(T);  // elements per 16-byte vector
+    const bool vec_ok = (n % VN == 0) && ((reinterpret_cast<uintptr_t>(Ain) | reinterpret_cast<uintptr_t>(Out)) % 16 == 0);
+    if (n < NP) {
+        for (int e = tid; e < NP * NP; e += C::kThreads) {
+            const int r = e / NP, c = e - r * NP;
+            if (r >= n || c >= n) {
+                P[r * LPA + c] = (T)0;
+                Q[r * LPB + c] = (T)0;
+            }
+        }
+    }
+    if (vec_ok) {
+        using V = typename VecOf<T>::type;
+        const int vpr = n / VN, total = n * vpr;
+#pragma unroll 4
+        for (int e = tid; e < total; e += C::kThreads) {
+            const int r = e / vpr, c = (e - r * vpr) * VN;
+            const V x = *reinterpret_cast<const V *>(W + (size_t)r * n + c);
+            *reinterpret_cast<V *>(P + r * LPA + c) = x;
+            *reinterpret_cast<V *>(Q + r * LPB + c) = x;
+        }
+    } else {
+#pragma unroll 4
+        for (int e = tid; e < n * n; e += C::kThreads) {
+            const int r = e / n, c = e - r * n;
+            const T x = W[e];
+            P[r * LPA + c] = x;
+            Q[r * LPB + c] = x;
+        }
+    }
+    __syncthreads();
+
+    // ---- 1-norm of the matrix in P: max column abs-sum, double accumulation, NaN if non-finite -------
+    // thread t sums rows t/NP, t/NP + G, ... of column t%NP (G row groups); groups are then added in order.
+    auto norm1_of_P = [&]() -> double {
+        constexpr int G = C::kThreads / NP > 0 ? C::kThreads / NP : 1;
+        const int col = tid % NP, grp = tid / NP;
+        double s = 0.0;
+        if (grp < G) {
+#pragma unroll 8
+            for (int r = grp; r < n; r += G) s += fabs((double)P[r * LPA + col]);
+        }
+        __syncthreads();  // red[] free to overwrite
+        red[tid] = s;
+        __syncthreads();
+        double cs = 0.0;
+        if (tid < NP) {
+#pragma unroll
+            for (int g = 0; g < G; ++g) cs += red[g * NP + tid];
+        }
+        int bad = !(cs <= 1.7976931348623157e308);
+        for (int off = 32; off > 0; off >>= 1) {
+            const double o = __shfl_xor(cs, off);
+            const int ob = __shfl_xor(bad, off);
+            cs = o > cs ? o : cs;
+            bad |= ob;
+        }
+        double *red2 = red + C::kThreads;
+        if (lane == 0) { red2[wave] = cs; red2[8 + wave] = (double)bad; }
+        __syncthreads();
+        double mx = red2[0], anybad = red2[8];
+#pragma unroll
+        for (int w = 1; w < WG * WG; ++w) {
+            mx = red2[w] > mx ? red2[w] : mx;
+            anybad += red2[8 + w];
+        }
+        return anybad != 0.0 ? __longlong_as_double(0x7ff8000000000000LL) : mx;
+    };
+
+    // ---- acc = P * Q on this wave's block of tiles --------------------------------------------------
+    acc_t acc[TH][TH];
+    auto product = [&]() {
+#pragma unroll
+        for (int ti = 0; ti < TH; ++ti)
+#pragma unroll
+            for (int tj = 0; tj < TH; ++tj) acc[ti][tj] = (acc_t)(0);
+        const T *lp = P + (16 * (wr * TH) + lj) * LPA + lg;
+        const T *rp = Q + lg * LPB + 16 * (wc * TH) + lj;
+        constexpr int NK = NP / 4;  // k-steps; even
+        T a0[TH], b0[TH], a1[TH], b1[TH];
+        auto fetch = [&](T *a, T *bq, int kk) {
+#pragma unroll
+            for (int ti = 0; ti < TH; ++ti) a[ti] = row_ok(ti) ? lp[ti * 16 * LPA + 4 * kk] : (T)0;
+#pragma unroll
+            for (int tj = 0; tj < TH; ++tj) bq[tj] = col_ok(tj) ? rp[4 * kk * LPB + tj * 16] : (T)0;
+        };
+        auto fma_step = [&](const T *a, const T *bq) {
+#pragma unroll
+            for (int ti = 0; ti < TH; ++ti)
+#pragma unroll
+                for (int tj = 0; tj < TH; ++tj)
+                    if (row_ok(ti) && col_ok(tj)) acc[ti][tj] = Mfma<T>::run(a[ti], bq[tj], acc[ti][tj]);
+        };
+        // software pipeline: the fragments of the next k-step are in flight while this one multiplies
+        fetch(a0, b0, 0);
+#pragma unroll 1
+        for (int kk = 0; kk < NK; kk += 2) {
+            fetch(a1, b1, kk + 1);
+            fma_step(a0, b0);
+            if (kk + 2 < NK) fetch(a0, b0, kk + 2);
+            fma_step(a1, b1);
+        }
+    };
+    // visit every element this lane owns: f(ti, tj, v, row, col)
+    auto for_owned = [&](auto &&f) {
+#pragma unroll
+        for (int ti = 0; ti < TH; ++ti)
+#pragma unroll
+            for (int tj = 0; tj < TH; ++tj)
+                if (row_ok(ti) && col_ok(tj)) {
+#pragma unroll
+                    for (int v = 0; v < 4; ++v)
+                        f(ti, tj, v, 16 * (wr * TH + ti) + Mfma<T>::row(lg, v), 16 * (wc * TH + tj) + lj);
+                }
+    };
+    auto dg = [&](int r, int c) -> T { return (r == c && r < n) ? (T)1 : (T)0; };
+
+    // element-wise state in registers: A, A^2, y02, additive part
+    T av[TH][TH][4], a2v[TH][TH][4], yv[TH][TH][4], gv[TH][TH][4];
+    for_owned([&](int ti, int tj, int v, int r, int c) {
+        av[ti][tj][v] = P[r * LPA + c];
+        a2v[ti][tj][v] = (T)0;
+    });
+
+    int m = 0, s = 0, flags = 0;
+    const double n1 = norm1_of_P();
+    double n2 = 0.0;
+    {
+        // orders 0 and 1 need no product: Algorithm 4 forms W^2 only once the m = 1 test has failed
+        const bool finite1 = n1 == n1;
+        const bool tiny = finite1 && (n1 == 0.0 || (0.5 * n1 * n1 + (1.0 / 6.0) * n1 * n1 * n1 <= eps));
+        if (finite1 && !tiny) {
+            product();  // W * W
+            __syncthreads();
+            for_owned([&](int ti, int tj, int v, int r, int c) {
+                a2v[ti][tj][v] = acc[ti][tj][v];
+                P[r * LPA + c] = acc[ti][tj][v];
+            });
+            __syncthreads();
+            n2 = norm1_of_P();
+        }
+    }
+    select_order_scaling(n1, n2, eps, m, s, flags);
+    if (tid == 0) {
+        MatInfo mi;
+        mi.m = m; mi.s = s; mi.len = 0; mi.flags = flags;
+        info[b] = mi;
+    }
+    if (select_only) return;
+    T *O = Out + moff;
+    if (m < 0) {
+        const T qnan = (T)__longlong_as_double(0x7ff8000000000000LL);
+        for (int e = tid; e < n * n; e += C::kThreads) O[e] = qnan;
+        return;
+    }
+
+    // ---- scale: A = W / 2^s, A2 = W2 / 4^s (exact).  P holds W2 and becomes A2. ------------------------
+    if (s > 0) {
+        const T sg = (T)pow2neg_f(s), sg2 = (T)pow2neg_f(2 * s);
+        for_owned([&](int ti, int tj, int v, int r, int c) {
+            av[ti][tj][v] *= sg;
+            a2v[ti][tj][v] *= sg2;
+            P[r * LPA + c] = a2v[ti][tj][v];
+        });
+    }
+
+    // The polynomial X ends in registers xv (aliasing acc's storage is left to the compiler).
+    T xv[TH][TH][4];
+    if (m <= 2) {
+        for_owned([&](int ti, int tj, int v, int r, int c) {
+            T x = dg(r, c);
+            if (m >= 1) x += av[ti][tj][v];
+            if (m == 2) x += a2v[ti][tj][v] / (T)2;
+            xv[ti][tj][v] = x;
+        });
+    } else if (m == 4) {
+        // T4 = ((A2/4 + A)/3 + I) * (A2/2) + A + I
+        __syncthreads();  // every wave is done with P (norm) before it is overwritten
+        for_owned([&](int ti, int tj, int v, int r, int c) {
+            const T a = av[ti][tj][v], a2 = a2v[ti][tj][v];
+            P[r * LPA + c] = (a2 / (T)4 + a) / (T)3 + dg(r, c);
+            Q[r * LPB + c] = a2 / (T)2;
+        });
+        __syncthreads();
+        product();
+        for_owned([&](int ti, int tj, int v, int r, int c) { xv[ti][tj][v] = acc[ti][tj][v] + av[ti][tj][v] + dg(r, c); });
+    } else {
+        const bool hi = m == 15;
+        const T c1 = (T)(hi ? EXPM_T15_C1 : EXPM_T8_C1), c2 = (T)(hi ? EXPM_T15_C2 : EXPM_T8_C2);
+        const T c3 = (T)(hi ? EXPM_T15_C3 : EXPM_T8_C3), c4 = (T)(hi ? EXPM_T15_C4 : EXPM_T8_C4);
+        const T c5 = (T)(hi ? EXPM_T15_C5 : EXPM_T8_C5), c6 = (T)(hi ? EXPM_T15_C6 : EXPM_T8_C6);
+        // y02 = A2 * (c1 A2 + c2 A): left operand A2 is already in P
+        for_owned([&](int ti, int tj, int v, int r, int c) { Q[r * LPB + c] = c1 * a2v[ti][tj][v] + c2 * av[ti][tj][v]; });
+        __syncthreads();
+        product();
+        __syncthreads();
+        for_owned([&](int ti, int tj, int v, int r, int c) {
+            const T y = acc[ti][tj][v], a = av[ti][tj][v], a2 = a2v[ti][tj][v];
+            yv[ti][tj][v] = y;
+            P[r * LPA + c] = y + c3 * a2 + c4 * a;
+            Q[r * LPB + c] = y + c5 * a2;
+            gv[ti][tj][v] = hi ? c6 * y + (T)EXPM_T15_C7 * a2 : c6 * y + a2 / (T)2 + a + dg(r, c);
+        });
+        __syncthreads();
+        product();
+        if (!hi) {
+            for_owned([&](int ti, int tj, int v, int, int) { xv[ti][tj][v] = acc[ti][tj][v] + gv[ti][tj][v]; });
+        } else {
+            const T c8 = (T)EXPM_T15_C8, c9 = (T)EXPM_T15_C9, c10 = (T)EXPM_T15_C10, c11 = (T)EXPM_T15_C11,
+                    c12 = (T)EXPM_T15_C12, c13 = (T)EXPM_T15_C13, c14 = (T)EXPM_T15_C14, c15 = (T)EXPM_T15_C15,
+                    c16 = (T)EXPM_T15_C16;
+            __syncthreads();
+            for_owned([&](int ti, int tj, int v, int r, int c) {
+                const T a = av[ti][tj][v], a2 = a2v[ti][tj][v], y0 = yv[ti][tj][v];
+                const T y1 = acc[ti][tj][v] + gv[ti][tj][v];  // y12
+                P[r * LPA + c] = y1 + c8 * a2 + c9 * a;
+                Q[r * LPB + c] = y1 + c10 * y0 + c11 * a;
+                gv[ti][tj][v] = c12 * y1 + c13 * y0 + c14 * a2 + c15 * a + c16 * dg(r, c);
+            });
+            __syncthreads();
+            product();
+            for_owned([&](int ti, int tj, int v, int, int) { xv[ti][tj][v] = acc[ti][tj][v] + gv[ti][tj][v]; });
+        }
+    }
+
+    // ---- squaring phase: X in both operand layouts, product, repeat ------------------------------------
+    for (int q = 0; q < s; ++q) {
+        __syncthreads();
+        for_owned([&](int ti, int tj, int v, int r, int c) {
+            P[r * LPA + c] = xv[ti][tj][v];
+            Q[r * LPB + c] = xv[ti][tj][v];
+        });
+        __syncthreads();
+        product();
+        for_owned([&](int ti, int tj, int v, int, int) { xv[ti][tj][v] = acc[ti][tj][v]; });
+    }
+
+    // ---- store through P so that global writes are whole rows -----------------------------------------
+    __syncthreads();
+    for_owned([&](int ti, int tj, int v, int r, int c) { P[r * LPA + c] = xv[ti][tj][v]; });
+    __syncthreads();
+    if (vec_ok) {
+        using V = typename VecOf<T>::type;
+        const int vpr = n / VN, total = n * vpr;
+#pragma unroll 4
+        for (int e = tid; e < total; e += C::kThreads) {
+            const int r = e / vpr, c = (e - r * vpr) * VN;
+            *reinterpret_cast<V *>(O + (size_t)r * n + c) = *reinterpret_cast<const V *>(P + r * LPA + c);
+        }
+    } else {
+#pragma unroll 4
+        for (int e = tid; e < n * n; e += C::kThreads) {
+            const int r = e / n, c = e - r * n;
+            O[e] = P[r * LPA + c];
+        }
+    }
+}
+
+template <typename T, int NT>
+hipError_t launch_fused_t(const void *A, void *out, int n, int batch, double eps, int select_only, MatInfo *info,
+                          hipStream_t stream)
+{
+    using C = FusedCfg<T, NT>;
+    static bool attr_done = false;
+    if (!attr_done) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(fused_expm_kernel<T, NT>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, C::kLds);
+        if (e != hipSuccess) return e;
+        attr_done = true;
+    }
+    hipLaunchKernelGGL((fused_expm_kernel<T, NT>), dim3(batch), dim3(C::kThreads), C::kLds, stream,
+                       reinterpret_cast<const T *>(A), reinterpret_cast<T *>(out), n, eps, select_only, info);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+bool small_path_supported(int n, int dtype)
+{
+    return dtype == 1 ? n <= 96 : n <= 128;
+}
+
+hipError_t launch_small(const void *A, void *out, int n, int batch, int dtype, double eps, int select_only,
+                        MatInfo *info, hipStream_t stream)
+{
+    const int nt = (n + 15) / 16;
+#define EXPM_FUSED_CASE(TYPE, K) \
+    case K: return launch_fused_t<TYPE, K>(A, out, n, batch, eps, select_only, info, stream);
+    if (dtype == 1) {
+        switch (nt) {
+            EXPM_FUSED_CASE(double, 1) EXPM_FUSED_CASE(double, 2) EXPM_FUSED_CASE(double, 3)
+            EXPM_FUSED_CASE(double, 4) EXPM_FUSED_CASE(double, 5) EXPM_FUSED_CASE(double, 6)
+        default: return hipErrorInvalidValue;
+        }
+    }
+    switch (nt) {
+        EXPM_FUSED_CASE(float, 1) EXPM_FUSED_CASE(float, 2) EXPM_FUSED_CASE(float, 3) EXPM_FUSED_CASE(float, 4)
+        EXPM_FUSED_CASE(float, 5) EXPM_FUSED_CASE(float, 6) EXPM_FUSED_CASE(float, 7) EXPM_FUSED_CASE(float, 8)
+    default: return hipErrorInvalidValue;
+    }
+#undef EXPM_FUSED_CASE
+}
+
+}  // namespace expmk

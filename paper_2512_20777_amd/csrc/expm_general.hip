@@ -1,41 +1,46 @@
 // Round-based path for larger matrices (n above the fused-path limit), gfx950.
 //
 // Pipeline per call (Algorithm 2 with Algorithm 4, Sec. 3.3 of arXiv 2512.20777):
-//   colabs + finalize        ||W||_1 per matrix
+//   colabs + colmax          ||W||_1 per matrix (per-column-block maxima, reduced by the selection)
 //   square round             W2 = W*W for every matrix, column abs-sums of W2 fused in the epilogue
-//   finalize                 ||W2||_1
+//   colmax                   ||W2||_1
 //   select_plan              (m, s) per matrix, chain length, order by chain length, active counts
 //   prepare                  results of orders 0,1,2 ; first operand pair for orders 4, 8, 15+
 //   chain rounds r = 1..R    one grouped MFMA product per still-active matrix, fused epilogue forming
 //                            every linear combination the next round needs (Sec. 3.1 formulas)
 //
-// The product kernel computes 128x128 tiles with 256 threads (2x2 waves of 64x64), MFMA 16x16x4 in
-// the matrix dtype, operands staged through double-buffered LDS in k-blocks of 128 bytes per row.
+// The product kernel computes a (32*WT)x(32*WT) tile per workgroup of 256 threads (2x2 waves, each
+// WT x WT MFMA 16x16x4 tiles in the matrix dtype); WT = 4 is the main shape, WT = 2 serves rounds with
+// too few tiles to fill the chip.  Operands are staged through double-buffered LDS in k-blocks of
+// 128 bytes per row.
 #include "expm_internal.h"
+
+#include <cstdlib>
 
 namespace expmk {
 
 namespace {
 
-constexpr int BM = 128, BN = 128;
 constexpr int kThreads = 256;
-constexpr int kAPitch = 144;  // bytes per A row in LDS: 128 data + 16 pad (conflict-free 16-byte reads)
+constexpr int kAPitch = 144;    // bytes per A row in LDS: 128 data + 16 pad (conflict-free 16-byte reads)
+constexpr int kColChunk = 32;   // rows per column-abs-sum partial of the input matrix
 
 template <typename T> struct Tile;
 template <> struct Tile<double> {
     static constexpr int BK = 16;        // k-block: 128 bytes of a row
     static constexpr int VN = 2;         // elements per 16-byte vector
-    static constexpr int BPitch = 1024 + 128;  // bytes per B row in LDS
     using vec_t = double2;
 };
 template <> struct Tile<float> {
     static constexpr int BK = 32;
     static constexpr int VN = 4;
-    static constexpr int BPitch = 512 + 32;
     using vec_t = float4;
 };
 
-template <typename T> constexpr int stage_bytes() { return BM * kAPitch + Tile<T>::BK * Tile<T>::BPitch; }
+template <typename T, int WT> constexpr int stage_bytes()
+{
+    return 32 * WT * kAPitch + Tile<T>::BK * 32 * WT * (int)sizeof(T);
+}
 
 struct GemmParams {
     void *base[BUF_COUNT];
@@ -86,15 +91,20 @@ __device__ __forceinline__ typename Tile<T>::vec_t load_vec(const T *__restrict_
     return v;
 }
 
-template <typename T, bool ALIGNED>
-__global__ __launch_bounds__(kThreads, 2) void gemm_round_kernel(GemmParams p)
+template <typename T, int WT, bool ALIGNED>
+__global__ __launch_bounds__(kThreads, WT == 4 ? 2 : 4) void gemm_round_kernel(GemmParams p)
 {
     using V = typename Tile<T>::vec_t;
     using acc_t = typename Mfma<T>::acc_t;
-    constexpr int BK = Tile<T>::BK, VN = Tile<T>::VN, BPitch = Tile<T>::BPitch;
-    constexpr int KQ = BK / 4;            // k values each 16-lane group owns per k-block
-    constexpr int VPR = BN / VN;          // 16-byte vectors per B row
-    constexpr int STAGE = stage_bytes<T>();
+    constexpr int BM = 32 * WT, BN = 32 * WT;
+    constexpr int BK = Tile<T>::BK, VN = Tile<T>::VN;
+    constexpr int BPitch = BN * (int)sizeof(T);   // B rows are rotated, not padded
+    constexpr int KQ = BK / 4;                    // k values each 16-lane group owns per k-block
+    constexpr int VPR = BN / VN;                  // 16-byte vectors per B row
+    constexpr int BSTEP = kThreads / VPR;         // B rows covered by one pass of the workgroup
+    constexpr int STAGE = stage_bytes<T, WT>();
+    constexpr int kRot = 16 * (int)sizeof(T);     // rotation of a B row per k-group, in bytes
+    static_assert(BK / BSTEP == WT && BM / 32 == WT, "WT staged vectors per thread and operand");
     extern __shared__ __align__(16) unsigned char smem[];
 
     const int n = p.n;
@@ -107,7 +117,7 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_round_kernel(GemmParams p)
     const int tiles2 = p.tiles * p.tiles;
     const int wid = xcd_remap(blockIdx.x, p.total);
     const int slot = wid / tiles2;
-    int tile = wid - slot * tiles2;
+    const int tile = wid - slot * tiles2;
     int b;
     Step<T> st;
     if (p.round == 0) {
@@ -136,41 +146,50 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_round_kernel(GemmParams p)
     const T *Rp = reinterpret_cast<const T *>(p.base[st.R]) + moff;
 
     // ---- staging maps -----------------------------------------------------------------------
-    // A tile: 128 rows x 8 vectors ; B tile: BK rows x VPR vectors ; 1024 vectors each, 4 per thread.
-    // vector v = tid + 256*i: A row = tid/8 + 32*i, B row = tid/VPR + (256/VPR)*i.
-    constexpr int BSTEP = kThreads / VPR;
+    // A tile: BM rows x 8 vectors ; B tile: BK rows x VPR vectors ; WT vectors per thread each.
+    // vector v = tid + 256*i: A row = tid/8 + 32*i, B row = tid/VPR + BSTEP*i.
+    // B rows are rotated by 16 elements per 16-lane k-group (row / KQ) so that the four groups of a
+    // fragment read hit different banks.
     const int a_row0 = tid >> 3, a_col = (tid & 7) * VN;
     const int b_row0 = tid / VPR, b_col = (tid % VPR) * VN;
     const int a_lds = a_row0 * kAPitch + (tid & 7) * 16;
-    const int b_lds = BM * kAPitch + b_row0 * BPitch + (tid % VPR) * 16;
+    const int b_lds = BM * kAPitch + b_row0 * BPitch;
+    const int b_vcol = (tid % VPR) * 16;  // byte offset of this thread's vector inside an unrotated row
+    int b_wr[WT];
+#pragma unroll
+    for (int i = 0; i < WT; ++i)
+        b_wr[i] = b_lds + BSTEP * i * BPitch + ((b_vcol + kRot * ((b_row0 + BSTEP * i) / KQ)) & (BPitch - 1));
     const int row0 = tm * BM, col0 = tn * BN;
 
-    acc_t acc[4][4];
+    acc_t acc[WT][WT];
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < WT; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) acc[i][j] = (acc_t)(0);
+        for (int j = 0; j < WT; ++j) acc[i][j] = (acc_t)(0);
 
     const int kblocks = (n + BK - 1) / BK;
-    V ra[4], rb[4];
+    V ra[WT], rb[WT];
     // prologue: first k-block into stage 0
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < WT; ++i) {
         ra[i] = load_vec<T, ALIGNED>(Lp, row0 + a_row0 + 32 * i, a_col, n);
         rb[i] = load_vec<T, ALIGNED>(Rp, b_row0 + BSTEP * i, col0 + b_col, n);
     }
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < WT; ++i) {
         *reinterpret_cast<V *>(smem + a_lds + 32 * i * kAPitch) = ra[i];
-        *reinterpret_cast<V *>(smem + b_lds + BSTEP * i * BPitch) = rb[i];
+        *reinterpret_cast<V *>(smem + b_wr[i]) = rb[i];
     }
     __syncthreads();
 
     // per-lane LDS read offsets (bytes) inside a stage
-    //   A: row (wm*64 + 16*ti + lj), k values lg*KQ .. lg*KQ+KQ-1  -> two 16-byte reads
-    //   B: row (lg*KQ + kk), column (wn*64 + 16*tj + lj)
-    const int a_rd = (wm * 64 + lj) * kAPitch + lg * 32;
-    const int b_rd = BM * kAPitch + (lg * KQ) * BPitch + (wn * 64 + lj) * (int)sizeof(T);
+    //   A: row (wm*16*WT + 16*ti + lj), k values lg*KQ .. lg*KQ+KQ-1  -> two 16-byte reads
+    //   B: row (lg*KQ + kk), column (wn*16*WT + 16*tj + lj) rotated by 16*lg elements
+    const int a_rd = (wm * 16 * WT + lj) * kAPitch + lg * 32;
+    const int b_rd = BM * kAPitch + (lg * KQ) * BPitch + lj * (int)sizeof(T);
+    int b_rc[WT];
+#pragma unroll
+    for (int tj = 0; tj < WT; ++tj) b_rc[tj] = ((wn * 16 * WT + 16 * tj + 16 * lg) * (int)sizeof(T)) & (BPitch - 1);
 
     for (int kb = 0; kb < kblocks; ++kb) {
         const unsigned char *cur = smem + (kb & 1) * STAGE;
@@ -179,15 +198,15 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_round_kernel(GemmParams p)
         if (more) {
             const int k0 = (kb + 1) * BK;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
+            for (int i = 0; i < WT; ++i) {
                 ra[i] = load_vec<T, ALIGNED>(Lp, row0 + a_row0 + 32 * i, k0 + a_col, n);
                 rb[i] = load_vec<T, ALIGNED>(Rp, k0 + b_row0 + BSTEP * i, col0 + b_col, n);
             }
         }
         // A fragments of the whole k-block
-        T af[4][KQ];
+        T af[WT][KQ];
 #pragma unroll
-        for (int ti = 0; ti < 4; ++ti) {
+        for (int ti = 0; ti < WT; ++ti) {
             const V lo = *reinterpret_cast<const V *>(cur + a_rd + ti * 16 * kAPitch);
             const V hi = *reinterpret_cast<const V *>(cur + a_rd + ti * 16 * kAPitch + 16);
             const T *l = reinterpret_cast<const T *>(&lo);
@@ -200,38 +219,38 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_round_kernel(GemmParams p)
         }
 #pragma unroll
         for (int kk = 0; kk < KQ; ++kk) {
-            T bf[4];
+            T bf[WT];
 #pragma unroll
-            for (int tj = 0; tj < 4; ++tj)
-                bf[tj] = *reinterpret_cast<const T *>(cur + b_rd + kk * BPitch + tj * 16 * (int)sizeof(T));
+            for (int tj = 0; tj < WT; ++tj)
+                bf[tj] = *reinterpret_cast<const T *>(cur + b_rd + kk * BPitch + b_rc[tj]);
 #pragma unroll
-            for (int ti = 0; ti < 4; ++ti)
+            for (int ti = 0; ti < WT; ++ti)
 #pragma unroll
-                for (int tj = 0; tj < 4; ++tj) acc[ti][tj] = Mfma<T>::run(af[ti][kk], bf[tj], acc[ti][tj]);
+                for (int tj = 0; tj < WT; ++tj) acc[ti][tj] = Mfma<T>::run(af[ti][kk], bf[tj], acc[ti][tj]);
         }
         if (more) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
+            for (int i = 0; i < WT; ++i) {
                 *reinterpret_cast<V *>(nxt + a_lds + 32 * i * kAPitch) = ra[i];
-                *reinterpret_cast<V *>(nxt + b_lds + BSTEP * i * BPitch) = rb[i];
+                *reinterpret_cast<V *>(nxt + b_wr[i]) = rb[i];
             }
         }
         __syncthreads();
     }
 
     // ---- epilogue -----------------------------------------------------------------------------
-    // lane holds C[row0 + wm*64 + 16*ti + Mfma<T>::row(lg, v)][col0 + wn*64 + 16*tj + lj]
-    const int er = row0 + wm * 64;
-    const int ec = col0 + wn * 64 + lj;
+    // lane holds C[row0 + wm*16*WT + 16*ti + Mfma<T>::row(lg, v)][col0 + wn*16*WT + 16*tj + lj]
+    const int er = row0 + wm * 16 * WT;
+    const int ec = col0 + wn * 16 * WT + lj;
     if (st.nsrc == 0 && st.nout == 1) {
         T *D = reinterpret_cast<T *>(p.base[st.dst[0]]) + moff;
 #pragma unroll
-        for (int ti = 0; ti < 4; ++ti)
+        for (int ti = 0; ti < WT; ++ti)
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 const int row = er + 16 * ti + Mfma<T>::row(lg, v);
 #pragma unroll
-                for (int tj = 0; tj < 4; ++tj) {
+                for (int tj = 0; tj < WT; ++tj) {
                     const int col = ec + 16 * tj;
                     if (row < n && col < n) D[(size_t)row * n + col] = acc[ti][tj][v];
                 }
@@ -245,12 +264,12 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_round_kernel(GemmParams p)
             D[i] = reinterpret_cast<T *>(p.base[st.dst[i]]) + moff;
         }
 #pragma unroll
-        for (int ti = 0; ti < 4; ++ti)
+        for (int ti = 0; ti < WT; ++ti)
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 const int row = er + 16 * ti + Mfma<T>::row(lg, v);
 #pragma unroll
-                for (int tj = 0; tj < 4; ++tj) {
+                for (int tj = 0; tj < WT; ++tj) {
                     const int col = ec + 16 * tj;
                     if (row < n && col < n) {
                         const size_t idx = (size_t)row * n + col;
@@ -277,18 +296,18 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_round_kernel(GemmParams p)
     }
 
     if (p.round == 0) {
-        // column abs-sums of this tile of W2, in double: 64 rows per wave, then the two wave rows
-        double *red = reinterpret_cast<double *>(smem);  // [2][128]; the k-loop's last barrier has passed
+        // column abs-sums of this tile of W2, in double: 16*WT rows per wave, then the two wave rows
+        double *red = reinterpret_cast<double *>(smem);  // [2][BN]; the k-loop's last barrier has passed
 #pragma unroll
-        for (int tj = 0; tj < 4; ++tj) {
+        for (int tj = 0; tj < WT; ++tj) {
             double cs = 0.0;
 #pragma unroll
-            for (int ti = 0; ti < 4; ++ti)
+            for (int ti = 0; ti < WT; ++ti)
 #pragma unroll
                 for (int v = 0; v < 4; ++v) cs += fabs((double)acc[ti][tj][v]);
             cs += __shfl_xor(cs, 16);
             cs += __shfl_xor(cs, 32);
-            if (lg == 0) red[wm * BN + wn * 64 + 16 * tj + lj] = cs;
+            if (lg == 0) red[wm * BN + wn * 16 * WT + 16 * tj + lj] = cs;
         }
         __syncthreads();
         if (tid < BN) {
@@ -299,53 +318,62 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_round_kernel(GemmParams p)
 }
 
 // ---- ||.||_1 helpers ----------------------------------------------------------------------------
-// Column abs-sums of W over row chunks of 128: colpart[b][chunk][col], accumulated in double.
+// Column abs-sums of W over row chunks of kColChunk rows: colpart[b][chunk][col], accumulated in double.
 template <typename T>
 __global__ __launch_bounds__(256) void colabs_kernel(const T *__restrict__ W, double *__restrict__ colpart, int n, int chunks)
 {
     const int col = blockIdx.x * 256 + threadIdx.x;
     const int chunk = blockIdx.y, b = blockIdx.z;
     if (col >= n) return;
-    const T *p = W + (size_t)b * n * n;
-    const int r0 = chunk * BM, r1 = min(n, r0 + BM);
+    const T *p = W + (size_t)b * n * n + col;
+    const int r0 = chunk * kColChunk, r1 = min(n, r0 + kColChunk);
     double s = 0.0;
-    for (int r = r0; r < r1; ++r) s += fabs((double)p[(size_t)r * n + col]);
+#pragma unroll 8
+    for (int r = r0; r < r1; ++r) s += fabs((double)p[(size_t)r * n]);
     colpart[((size_t)b * chunks + chunk) * n + col] = s;
 }
 
-// norm[b] = max over columns of (sum over chunks of colpart[b][chunk][col]); NaN if anything is non-finite.
-__global__ __launch_bounds__(256) void norm_finalize_kernel(const double *__restrict__ colpart, double *__restrict__ norm,
-                                                            int n, int chunks)
+// pmax[b][blk] = max over the 256 columns of block blk of (sum over chunks of colpart[b][chunk][col]),
+// chunks added in ascending order; NaN if any column sum is non-finite.
+__global__ __launch_bounds__(256) void colmax_kernel(const double *__restrict__ colpart, double *__restrict__ pmax,
+                                                     int n, int chunks, int nblk)
 {
-    __shared__ double smax[256];
-    __shared__ int sbad[256];
-    const int b = blockIdx.x, tid = threadIdx.x;
-    double mx = 0.0;
-    int bad = 0;
-    for (int col = tid; col < n; col += 256) {
-        double s = 0.0;
-        for (int c = 0; c < chunks; ++c) s += colpart[((size_t)b * chunks + c) * n + col];
-        if (!(s <= 1.7976931348623157e308)) bad = 1;  // NaN or Inf
-        if (s > mx) mx = s;
+    __shared__ double smax[4];
+    __shared__ int sbad[4];
+    const int blk = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
+    const int col = blk * 256 + tid;
+    double s = 0.0;
+    if (col < n) {
+        const double *p = colpart + (size_t)b * chunks * n + col;
+#pragma unroll 4
+        for (int c = 0; c < chunks; ++c) s += p[(size_t)c * n];
     }
-    smax[tid] = mx;
-    sbad[tid] = bad;
+    int bad = !(s <= 1.7976931348623157e308);  // NaN or Inf
+    for (int off = 32; off > 0; off >>= 1) {
+        const double o = __shfl_xor(s, off);
+        const int ob = __shfl_xor(bad, off);
+        s = o > s ? o : s;
+        bad |= ob;
+    }
+    if ((tid & 63) == 0) { smax[tid >> 6] = s; sbad[tid >> 6] = bad; }
     __syncthreads();
-    for (int w = 128; w > 0; w >>= 1) {
-        if (tid < w) {
-            if (smax[tid + w] > smax[tid]) smax[tid] = smax[tid + w];
-            sbad[tid] |= sbad[tid + w];
+    if (tid == 0) {
+        double mx = smax[0];
+        int anybad = sbad[0];
+        for (int w = 1; w < 4; ++w) {
+            mx = smax[w] > mx ? smax[w] : mx;
+            anybad |= sbad[w];
         }
-        __syncthreads();
+        pmax[(size_t)b * nblk + blk] = anybad ? __longlong_as_double(0x7ff8000000000000LL) : mx;
     }
-    if (tid == 0) norm[b] = sbad[0] ? __longlong_as_double(0x7ff8000000000000LL) : smax[0];
 }
 
 // ---- selection and plan ---------------------------------------------------------------------------
-// One workgroup.  Writes info[b], the order (longest chain first) and the summary:
+// One workgroup.  Reduces the per-block maxima to n1, n2, runs Algorithm 4, writes info[b], the order
+// (longest chain first) and the summary:
 //   summary[0] = longest chain, summary[1] = OR of flags, summary[2 + r] = matrices active in round r.
-__global__ __launch_bounds__(1024) void select_plan_kernel(const double *__restrict__ n1, const double *__restrict__ n2,
-                                                           MatInfo *__restrict__ info, int *__restrict__ order,
+__global__ __launch_bounds__(1024) void select_plan_kernel(const double *__restrict__ p1, const double *__restrict__ p2,
+                                                           int nblk, MatInfo *__restrict__ info, int *__restrict__ order,
                                                            int *__restrict__ summary, int batch, double eps)
 {
     __shared__ int hist[kMaxRounds + 1];
@@ -356,8 +384,17 @@ __global__ __launch_bounds__(1024) void select_plan_kernel(const double *__restr
     if (tid == 0) flags_or = 0;
     __syncthreads();
     for (int b = tid; b < batch; b += blockDim.x) {
+        double n1 = 0.0, n2 = 0.0;
+        bool bad = false;
+        for (int k = 0; k < nblk; ++k) {
+            const double x = p1[(size_t)b * nblk + k], y = p2[(size_t)b * nblk + k];
+            if (!(x == x) || !(y == y)) bad = true;
+            n1 = x > n1 ? x : n1;
+            n2 = y > n2 ? y : n2;
+        }
+        if (bad) n1 = __longlong_as_double(0x7ff8000000000000LL);
         MatInfo mi;
-        select_order_scaling(n1[b], n2[b], eps, mi.m, mi.s, mi.flags);
+        select_order_scaling(n1, n2, eps, mi.m, mi.s, mi.flags);
         mi.len = chain_length(mi.m, mi.s);
         info[b] = mi;
         atomicAdd(&hist[mi.len], 1);
@@ -426,22 +463,22 @@ __global__ __launch_bounds__(256) void prepare_kernel(GemmParams p)
     }
 }
 
-template <typename T, bool ALIGNED>
+template <typename T, int WT, bool ALIGNED>
 hipError_t launch_gemm_t(const GemmParams &p, hipStream_t stream)
 {
     static bool attr_done = false;
-    const int lds = 2 * stage_bytes<T>();
+    const int lds = 2 * stage_bytes<T, WT>();
     if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_round_kernel<T, ALIGNED>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_round_kernel<T, WT, ALIGNED>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, lds);
         if (e != hipSuccess) return e;
         attr_done = true;
     }
-    hipLaunchKernelGGL((gemm_round_kernel<T, ALIGNED>), dim3(p.total), dim3(kThreads), lds, stream, p);
+    hipLaunchKernelGGL((gemm_round_kernel<T, WT, ALIGNED>), dim3(p.total), dim3(kThreads), lds, stream, p);
     return hipGetLastError();
 }
 
-GemmParams make_params(const GeneralBuffers &gb, int n, int round, int matrices)
+GemmParams make_params(const GeneralBuffers &gb, int n, int round, int matrices, int wt)
 {
     GemmParams p;
     for (int i = 0; i < BUF_COUNT; ++i) p.base[i] = gb.base[i];
@@ -449,29 +486,62 @@ GemmParams make_params(const GeneralBuffers &gb, int n, int round, int matrices)
     p.order = gb.order;
     p.colpart = gb.colpart;
     p.n = n;
-    p.tiles = general_tiles(n);
+    p.tiles = (n + 32 * wt - 1) / (32 * wt);
     p.round = round;
     p.total = matrices * p.tiles * p.tiles;
     return p;
 }
 
-hipError_t launch_gemm(const GemmParams &p, int dtype, bool ptr_align16, hipStream_t stream)
+template <typename T, int WT>
+hipError_t launch_gemm_a(const GemmParams &p, bool aligned, hipStream_t stream)
+{
+    return aligned ? launch_gemm_t<T, WT, true>(p, stream) : launch_gemm_t<T, WT, false>(p, stream);
+}
+
+hipError_t launch_gemm(const GemmParams &p, int dtype, int wt, bool ptr_align16, hipStream_t stream)
 {
     if (p.total <= 0) return hipSuccess;
     if (dtype == 1) {
-        return (ptr_align16 && p.n % 2 == 0) ? launch_gemm_t<double, true>(p, stream)
-                                             : launch_gemm_t<double, false>(p, stream);
+        const bool al = ptr_align16 && p.n % 2 == 0;
+        return wt == 4 ? launch_gemm_a<double, 4>(p, al, stream) : launch_gemm_a<double, 2>(p, al, stream);
     }
-    return (ptr_align16 && p.n % 4 == 0) ? launch_gemm_t<float, true>(p, stream) : launch_gemm_t<float, false>(p, stream);
+    const bool al = ptr_align16 && p.n % 4 == 0;
+    return wt == 4 ? launch_gemm_a<float, 4>(p, al, stream) : launch_gemm_a<float, 2>(p, al, stream);
 }
 
 }  // namespace
 
-int general_tiles(int n) { return (n + BM - 1) / BM; }
+// Tile shape for a round with `matrices` active matrices of order n: 128x128 tiles (WT = 4) for large
+// matrices unless they would leave compute units idle or poorly balanced, 64x64 tiles (WT = 2) otherwise.
+// Cost model for n >= 1024, in units of one 128x128 tile on one compute unit: a compute unit works
+// through its tiles one after another (co-resident tiles share the matrix pipe); a 64x64 tile costs a
+// quarter of the work at roughly 0.9 of the efficiency.
+int choose_tile_shape(int n, int matrices)
+{
+    // debugging aid: EXPM_FORCE_WT=2|4 pins the shape (read once)
+    static const int forced = [] {
+        const char *e = getenv("EXPM_FORCE_WT");
+        const int v = e ? atoi(e) : 0;
+        return (v == 2 || v == 4) ? v : 0;
+    }();
+    if (forced) return forced;
+    // Measured on MI355X: up to n of several hundred the 64x64 shape is as fast per product and, with
+    // four workgroups per compute unit out of phase, hides the fused epilogues' memory traffic better.
+    if (n < 1024) return 2;
+    const long long cus = 256;
+    const long long t4 = (long long)matrices * ((n + 127) / 128) * ((n + 127) / 128);
+    const long long t2 = (long long)matrices * ((n + 63) / 64) * ((n + 63) / 64);
+    const double cost4 = (double)((t4 + cus - 1) / cus);
+    const double cost2 = (double)((t2 + cus - 1) / cus) * 0.25 / 0.9;
+    return cost2 < cost4 ? 2 : 4;
+}
+
+int general_colchunks(int n) { return (n + kColChunk - 1) / kColChunk; }
+int general_colblocks(int n) { return (n + 255) / 256; }
 
 hipError_t launch_colabs(const GeneralBuffers &gb, int n, int batch, int dtype, hipStream_t stream)
 {
-    const int chunks = general_tiles(n);
+    const int chunks = general_colchunks(n);
     dim3 grid((n + 255) / 256, chunks, batch);
     if (dtype == 1)
         hipLaunchKernelGGL(colabs_kernel<double>, grid, dim3(256), 0, stream,
@@ -482,29 +552,29 @@ hipError_t launch_colabs(const GeneralBuffers &gb, int n, int batch, int dtype, 
     return hipGetLastError();
 }
 
-hipError_t launch_norm_finalize(const GeneralBuffers &gb, int n, int batch, int which, hipStream_t stream)
+hipError_t launch_colmax(const GeneralBuffers &gb, int n, int batch, int which, int chunks, hipStream_t stream)
 {
-    hipLaunchKernelGGL(norm_finalize_kernel, dim3(batch), dim3(256), 0, stream, gb.colpart, which == 1 ? gb.n1 : gb.n2, n,
-                       general_tiles(n));
+    const int nblk = general_colblocks(n);
+    hipLaunchKernelGGL(colmax_kernel, dim3(nblk, batch), dim3(256), 0, stream, gb.colpart, which == 1 ? gb.n1 : gb.n2, n,
+                       chunks, nblk);
     return hipGetLastError();
 }
 
-hipError_t launch_square_round(const GeneralBuffers &gb, int n, int batch, int dtype, hipStream_t stream)
+hipError_t launch_square_round(const GeneralBuffers &gb, int n, int batch, int dtype, int wt, hipStream_t stream)
 {
-    return launch_gemm(make_params(gb, n, 0, batch), dtype, gb.ptr_align16, stream);
+    return launch_gemm(make_params(gb, n, 0, batch, wt), dtype, wt, gb.ptr_align16, stream);
 }
 
 hipError_t launch_select_plan(const GeneralBuffers &gb, int n, int batch, double eps, hipStream_t stream)
 {
-    (void)n;
-    hipLaunchKernelGGL(select_plan_kernel, dim3(1), dim3(1024), 0, stream, gb.n1, gb.n2, gb.info, gb.order, gb.summary,
-                       batch, eps);
+    hipLaunchKernelGGL(select_plan_kernel, dim3(1), dim3(1024), 0, stream, gb.n1, gb.n2, general_colblocks(n), gb.info,
+                       gb.order, gb.summary, batch, eps);
     return hipGetLastError();
 }
 
 hipError_t launch_prepare(const GeneralBuffers &gb, int n, int batch, int dtype, hipStream_t stream)
 {
-    const GemmParams p = make_params(gb, n, 0, batch);
+    const GemmParams p = make_params(gb, n, 0, batch, 4);
     const size_t nn = (size_t)n * n;
     dim3 grid((unsigned)((nn + 1023) / 1024), batch);
     if (dtype == 1)
@@ -514,9 +584,9 @@ hipError_t launch_prepare(const GeneralBuffers &gb, int n, int batch, int dtype,
     return hipGetLastError();
 }
 
-hipError_t launch_chain_round(const GeneralBuffers &gb, int n, int active, int round, int dtype, hipStream_t stream)
+hipError_t launch_chain_round(const GeneralBuffers &gb, int n, int active, int round, int dtype, int wt, hipStream_t stream)
 {
-    return launch_gemm(make_params(gb, n, round, active), dtype, gb.ptr_align16, stream);
+    return launch_gemm(make_params(gb, n, round, active, wt), dtype, wt, gb.ptr_align16, stream);
 }
 
 }  // namespace expmk

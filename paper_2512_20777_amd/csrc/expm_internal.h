@@ -212,20 +212,19 @@ __device__ __forceinline__ Step<T> build_step(int m, int s, int r)
         if (r == 1) {
             st.L = BUF_W2; st.R = BUF_T0; st.acc_scale = (T)sg2;  // y02 = A2 * (c1 A2 + c2 A)
             st.nsrc = 2; st.src[0] = BUF_W2; st.src[1] = BUF_W;
-            st.nout = 4;
+            st.nout = 3;
             st.dst[0] = BUF_T1; st.b[0][0] = (T)(EXPM_T15_C3 * sg2); st.b[0][1] = (T)(EXPM_T15_C4 * sg);
             st.dst[1] = BUF_T2; st.b[1][0] = (T)(EXPM_T15_C5 * sg2);
-            st.dst[2] = BUF_T3; st.a[2] = (T)EXPM_T15_C6; st.b[2][0] = (T)(EXPM_T15_C7 * sg2);
-            st.dst[3] = BUF_T4;  // y02 itself
+            st.dst[2] = BUF_T4;  // y02 itself; the additive part c6 y02 + c7 A2 is re-formed in round 2
         } else if (r == 2) {
             st.L = BUF_T1; st.R = BUF_T2;  // y12 = L*R + (c6 y02 + c7 A2)
-            st.nsrc = 4; st.src[0] = BUF_T3; st.src[1] = BUF_T4; st.src[2] = BUF_W2; st.src[3] = BUF_W;
-            st.g[0] = (T)1;
+            st.nsrc = 3; st.src[0] = BUF_T4; st.src[1] = BUF_W2; st.src[2] = BUF_W;
+            st.g[0] = (T)EXPM_T15_C6; st.g[1] = (T)(EXPM_T15_C7 * sg2);
             st.nout = 3;
-            st.dst[0] = BUF_T0; st.b[0][2] = (T)(EXPM_T15_C8 * sg2); st.b[0][3] = (T)(EXPM_T15_C9 * sg);
-            st.dst[1] = BUF_T5; st.b[1][1] = (T)EXPM_T15_C10; st.b[1][3] = (T)(EXPM_T15_C11 * sg);
-            st.dst[2] = BUF_T3; st.a[2] = (T)EXPM_T15_C12; st.b[2][1] = (T)EXPM_T15_C13;
-            st.b[2][2] = (T)(EXPM_T15_C14 * sg2); st.b[2][3] = (T)(EXPM_T15_C15 * sg); st.d[2] = (T)EXPM_T15_C16;
+            st.dst[0] = BUF_T0; st.b[0][1] = (T)(EXPM_T15_C8 * sg2); st.b[0][2] = (T)(EXPM_T15_C9 * sg);
+            st.dst[1] = BUF_T5; st.b[1][0] = (T)EXPM_T15_C10; st.b[1][2] = (T)(EXPM_T15_C11 * sg);
+            st.dst[2] = BUF_T3; st.a[2] = (T)EXPM_T15_C12; st.b[2][0] = (T)EXPM_T15_C13;
+            st.b[2][1] = (T)(EXPM_T15_C14 * sg2); st.b[2][2] = (T)(EXPM_T15_C15 * sg); st.d[2] = (T)EXPM_T15_C16;
         } else if (r == 3) {
             st.L = BUF_T0; st.R = BUF_T5;  // y22 = L*R + additive part
             st.nsrc = 1; st.src[0] = BUF_T3; st.g[0] = (T)1;
@@ -246,8 +245,8 @@ __device__ __forceinline__ Step<T> build_step(int m, int s, int r)
 // ---------------------------------------------------------------------------------------------
 struct GeneralBuffers {
     void *base[BUF_COUNT];   // device pointers, [batch][n][n] each (BUF_W = input, BUF_OUT = output)
-    double *colpart;         // [batch][tiles][n] column abs-sum partials
-    double *n1, *n2;         // [batch]
+    double *colpart;         // [batch][chunks][n] column abs-sum partials (chunks: see the launchers)
+    double *n1, *n2;         // [batch][colblocks] per-column-block maxima of the column sums of W, W2
     MatInfo *info;           // [batch]
     int *order;              // [batch] matrices sorted by chain length, longest first
     int *summary;            // [64] : [0] longest chain, [1] OR of flags, [2+r] matrices active in round r
@@ -260,12 +259,15 @@ hipError_t launch_small(const void *A, void *out, int n, int batch, int dtype, d
                         MatInfo *info, hipStream_t stream);
 
 // larger-n path
-int general_tiles(int n);
+int general_colchunks(int n);   // row chunks of the column abs-sum pass over the input
+int general_colblocks(int n);   // 256-column blocks: per-block maxima make up n1 / n2
+int choose_tile_shape(int n, int matrices);  // 4 -> 128x128 tiles, 2 -> 64x64 tiles
 hipError_t launch_colabs(const GeneralBuffers &gb, int n, int batch, int dtype, hipStream_t stream);
-hipError_t launch_norm_finalize(const GeneralBuffers &gb, int n, int batch, int which, hipStream_t stream);
-hipError_t launch_square_round(const GeneralBuffers &gb, int n, int batch, int dtype, hipStream_t stream);
+hipError_t launch_colmax(const GeneralBuffers &gb, int n, int batch, int which, int chunks, hipStream_t stream);
+hipError_t launch_square_round(const GeneralBuffers &gb, int n, int batch, int dtype, int wt, hipStream_t stream);
 hipError_t launch_select_plan(const GeneralBuffers &gb, int n, int batch, double eps, hipStream_t stream);
 hipError_t launch_prepare(const GeneralBuffers &gb, int n, int batch, int dtype, hipStream_t stream);
-hipError_t launch_chain_round(const GeneralBuffers &gb, int n, int active, int round, int dtype, hipStream_t stream);
+hipError_t launch_chain_round(const GeneralBuffers &gb, int n, int active, int round, int dtype, int wt,
+                              hipStream_t stream);
 
 }  // namespace expmk

@@ -76,20 +76,22 @@ def _run_and_check(ex, a, tol=None, label="", gate=None):
 
 
 # ------------------------------------------------------------------------------------------------
-# fused single-kernel path (n <= 64 fp32, n <= 48 fp64)
+# fused single-kernel path (n <= 128 fp32, n <= 96 fp64)
 # ------------------------------------------------------------------------------------------------
-@pytest.mark.parametrize("n", [1, 2, 5, 16, 17, 31, 32, 33, 48])
+@pytest.mark.parametrize("n", [1, 2, 5, 16, 17, 31, 32, 33, 48, 63, 70, 81, 96])
 def test_fused_fp64_sizes(ex, n):
     from paper_2512_20777_amd import workloads
     a = workloads.random_stack(100 + n, 37, n, np.float64, 1e-3, 60.0)
-    _run_and_check(ex, a, label="fused64 n=%d" % n)
+    _, m, s, info, stats = _run_and_check(ex, a, label="fused64 n=%d" % n)
+    assert stats["fused_path"] == 1
 
 
-@pytest.mark.parametrize("n", [1, 3, 16, 20, 32, 47, 49, 64])
+@pytest.mark.parametrize("n", [1, 3, 16, 20, 32, 47, 49, 64, 77, 90, 100, 113, 128])
 def test_fused_fp32_sizes(ex, n):
     from paper_2512_20777_amd import workloads
     a = workloads.random_stack(200 + n, 41, n, np.float32, 1e-3, 60.0, kind="skew" if n % 2 else "dense")
-    _run_and_check(ex, a, label="fused32 n=%d" % n)
+    _, m, s, info, stats = _run_and_check(ex, a, label="fused32 n=%d" % n)
+    assert stats["fused_path"] == 1
 
 
 def test_workload_c1_full(ex):
@@ -109,7 +111,7 @@ def test_workload_c2_full(ex):
 # ------------------------------------------------------------------------------------------------
 # round-based path (larger n): several tiles, ragged tails, aligned and unaligned row lengths
 # ------------------------------------------------------------------------------------------------
-@pytest.mark.parametrize("n,batch", [(49, 5), (64, 4), (130, 3), (200, 3), (257, 2), (384, 2)])
+@pytest.mark.parametrize("n,batch", [(97, 5), (128, 4), (130, 3), (200, 3), (257, 2), (384, 2)])
 def test_rounds_fp64_sizes(ex, n, batch):
     from paper_2512_20777_amd import workloads
     a = workloads.random_stack(300 + n, batch, n, np.float64, 0.05, 80.0)
@@ -117,11 +119,12 @@ def test_rounds_fp64_sizes(ex, n, batch):
     assert stats["fused_path"] == 0
 
 
-@pytest.mark.parametrize("n,batch", [(65, 5), (128, 6), (136, 3), (250, 3), (300, 2), (515, 2)])
+@pytest.mark.parametrize("n,batch", [(129, 5), (136, 3), (192, 6), (250, 3), (300, 2), (515, 2)])
 def test_rounds_fp32_sizes(ex, n, batch):
     from paper_2512_20777_amd import workloads
     a = workloads.random_stack(400 + n, batch, n, np.float32, 0.05, 80.0)
-    _run_and_check(ex, a, label="rounds32 n=%d" % n)
+    _, m, s, info, stats = _run_and_check(ex, a, label="rounds32 n=%d" % n)
+    assert stats["fused_path"] == 0
 
 
 @pytest.mark.parametrize("dtype", [np.float64, np.float32])
@@ -150,7 +153,7 @@ def test_rounds_nonnormal_triangular(ex):
 def test_workload_c3_full(ex):
     from paper_2512_20777_amd import workloads
     _, m, s, info, stats = _run_and_check(ex, workloads.make_workload("C3"), label="C3")
-    assert stats["matrices"] == 256 and stats["fused_path"] == 0
+    assert stats["matrices"] == 256 and stats["fused_path"] == 1
 
 
 def test_workload_c4_full(ex):
@@ -208,7 +211,7 @@ def test_zero_matrix_gives_identity_and_m0(ex, n):
     assert torch.equal(out, torch.eye(n, dtype=torch.float64, device="cuda").expand(3, n, n))
 
 
-@pytest.mark.parametrize("n", [12, 90])
+@pytest.mark.parametrize("n", [12, 90, 140])
 def test_index2_nilpotent_is_exact(ex, n):
     import torch
     a = torch.zeros(2, n, n, dtype=torch.float64, device="cuda")
@@ -230,7 +233,7 @@ def test_empty_batch_and_empty_matrix(ex):
     assert len(m) == 0 and st == 0
 
 
-@pytest.mark.parametrize("n", [10, 80])
+@pytest.mark.parametrize("n", [10, 80, 150])
 def test_nonfinite_input_is_flagged_and_isolated(ex, n):
     import torch
     from oracle import oracle_expm
@@ -250,11 +253,12 @@ def test_nonfinite_input_is_flagged_and_isolated(ex, n):
         assert np.linalg.norm(got - X) / np.linalg.norm(X) < 1e-11
 
 
-def test_scaling_cap_warning(ex):
+@pytest.mark.parametrize("n", [70, 130])
+def test_scaling_cap_warning(ex, n):
     import torch
-    a = torch.zeros(2, 70, 70, dtype=torch.float64, device="cuda")
-    a[0] = torch.eye(70, device="cuda", dtype=torch.float64) * 0.5
-    a[1] = torch.eye(70, device="cuda", dtype=torch.float64) * -3.0e7   # needs s > 20: capped
+    a = torch.zeros(2, n, n, dtype=torch.float64, device="cuda")
+    a[0] = torch.eye(n, device="cuda", dtype=torch.float64) * 0.5
+    a[1] = torch.eye(n, device="cuda", dtype=torch.float64) * -3.0e7   # needs s > 20: capped
     m, s, st = ex.expm_select(a)
     assert st == 2 and (m[1], s[1]) == (15, 20) and s[0] < 20
 
@@ -271,7 +275,7 @@ def test_user_tolerance_changes_the_choice_like_the_oracle(ex):
 def test_results_are_bitwise_reproducible(ex):
     import torch
     from paper_2512_20777_amd import workloads
-    for n, dt in ((16, np.float32), (200, np.float64), (136, np.float32)):
+    for n, dt in ((16, np.float32), (128, np.float32), (200, np.float64), (136, np.float32)):
         d = torch.from_numpy(workloads.random_stack(3, 6, n, dt, 0.1, 50.0)).cuda()
         o1, _ = ex.expm(d)
         o1 = o1.clone()
