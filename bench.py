@@ -21,6 +21,32 @@ DEFAULT_STEPS = {"C1": 200, "C2": 200, "C3": 50, "C4": 20, "C5f64": 4, "C5f32": 
 DEFAULT_WARMUP = {"C1": 20, "C2": 20, "C3": 10, "C4": 4, "C5f64": 2, "C5f32": 2}
 
 
+def source_sha1():
+    import glob
+    import hashlib
+    h = hashlib.sha1()
+    for f in sorted(glob.glob(os.path.join(ROOT, "paper_2512_20777_amd", "csrc", "*"))):
+        h.update(open(f, "rb").read())
+    return h.hexdigest()
+
+
+def recorded_traffic(workload, kernel_prefix):
+    """HBM bytes per dispatch of the kernel from the committed counter summary (profiles/hbm_traffic.txt),
+    or None when there is none or the kernel sources have changed since the counters were taken."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
+    if not os.path.exists(path):
+        return None
+    sha, val = None, None
+    for line in open(path):
+        if line.startswith("source_sha1"):
+            sha = line.split()[1]
+        elif not line.startswith("#") and "|" in line:
+            w, k, f, wr, _ = [x.strip() for x in line.split("|")]
+            if w == workload and k.startswith(kernel_prefix):
+                val = (float(f.split()[1]) + float(wr.split()[1])) * 1024.0
+    return val if sha == source_sha1() else None
+
+
 def time_steps(ex, torch, d, out, tol, steps, warmup):
     for _ in range(warmup):
         ex.expm(d, tol, out=out)
@@ -141,11 +167,32 @@ def run_workload(name, steps, warmup, with_cpu, time_sel=False):
                            "unit": "TFLOP/s", "frac": ach / peak, "traffic": None,
                            "avg_launch_ms": k["ms"] / k["launches"], "launches_per_step": k["launches"] / max(2, min(steps, 20)),
                            "whole_call_frac": res["tflops"] / peak}
+    res["roofline"]["traffic"] = recorded_traffic(name, res["roofline"]["kernel"])
     if with_cpu:
         res["cpu_baseline"] = cpu_baseline(name, a, w.tol, workloads)
     del d, out
     torch.cuda.empty_cache()
     return res
+
+
+def pmc_pass(name, steps):
+    """A few steps of one workload and a 256 MiB device-to-device copy (the counter calibration)."""
+    import torch
+    import paper_2512_20777_amd as ex
+    from paper_2512_20777_amd import workloads
+    w = workloads.WORKLOADS[name]
+    d = torch.from_numpy(workloads.make_workload(name)).cuda()
+    out = torch.empty_like(d)
+    for _ in range(steps):
+        ex.expm(d, w.tol, out=out)
+    torch.cuda.synchronize()
+    src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device="cuda")   # 256 MiB
+    dst = torch.empty_like(src)
+    for _ in range(3):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    print(json.dumps({"pmc_pass": name, "steps": steps, "copy_bytes_each_way": src.numel() * 4}))
+    ex.expm_shutdown()
 
 
 def main():
@@ -156,6 +203,8 @@ def main():
     ap.add_argument("--workload", default="C2")
     ap.add_argument("--no-others", action="store_true", help="only the headline workload")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
+    ap.add_argument("--pmc-pass", action="store_true", help="short run for hardware-counter collection: a few "
+                    "steps of the workload plus a plain device copy of 256 MiB as the calibration kernel")
     ap.add_argument("--time-select", action="store_true", help="also time expm_select() alone (adds launches "
                     "of the product kernel that are not expm() steps)")
     args = ap.parse_args()
@@ -172,6 +221,9 @@ def main():
     ex.load_library()
 
     head = args.workload
+    if args.pmc_pass:
+        pmc_pass(head, args.steps if args.steps > 0 else 3)
+        return
     steps = args.steps if args.steps > 0 else DEFAULT_STEPS[head]
     warmup = args.warmup if args.warmup >= 0 else DEFAULT_WARMUP[head]
     main_res = run_workload(head, steps, warmup, not args.no_cpu, args.time_select)

@@ -108,13 +108,13 @@ def _describe(A) -> Tuple[int, int, int]:
         raise ExpmError(-1, "input must have shape [batch][n][n]")
     if not A.is_contiguous():
         raise ExpmError(-1, "input must be contiguous (row-major [batch][n][n])")
-    if A.dtype == torch.float32:
+    if A.dtype is torch.float32:
         dt = DTYPE_F32
-    elif A.dtype == torch.float64:
+    elif A.dtype is torch.float64:
         dt = DTYPE_F64
     else:
         raise ExpmError(-1, "dtype must be float32 or float64")
-    return int(A.shape[1]), int(A.shape[0]), dt
+    return A.shape[1], A.shape[0], dt
 
 
 def expm_select(A, tol: float = 0.0):
@@ -127,26 +127,36 @@ def expm_select(A, tol: float = 0.0):
     i32p = ctypes.POINTER(ctypes.c_int32)
     with torch.cuda.device(A.device):
         torch.cuda.current_stream().synchronize()  # the C entry point runs on the null stream
-        st = load_library().expm_select(ctypes.c_void_p(A.data_ptr()), n, batch, dt, float(tol),
+        st = load_library().expm_select(A.data_ptr(), n, batch, dt, float(tol),
                                         m.ctypes.data_as(i32p), s.ctypes.data_as(i32p))
     return m, s, _check(st)
 
 
 def expm(A, tol: float = 0.0, out=None, stream=None):
-    """e^A for a [batch][n][n] device tensor; returns (out, status).  Runs on torch's current stream."""
+    """e^A for a [batch][n][n] device tensor; returns (out, status).  Runs on torch's current stream.
+
+    Marshalling only, kept short: for small batches the call rate is bounded by this function.
+    """
     import torch
+    lib = _lib if _lib is not None else load_library()
     n, batch, dt = _describe(A)
     if out is None:
         out = torch.empty_like(A)
+    elif out.shape != A.shape or out.dtype is not A.dtype or out.device != A.device or not out.is_contiguous():
+        raise ExpmError(-1, "out must match the input's shape, dtype and device and be contiguous")
+    dev = A.device.index
+    if stream is not None:
+        sp = stream.cuda_stream
     else:
-        on, ob, odt = _describe(out)
-        if (on, ob, odt) != (n, batch, dt) or out.device != A.device:
-            raise ExpmError(-1, "out must match the input's shape, dtype and device")
-    with torch.cuda.device(A.device):
-        sp = (torch.cuda.current_stream() if stream is None else stream).cuda_stream
-        st = load_library().expm(ctypes.c_void_p(A.data_ptr()), n, batch, dt, float(tol),
-                                 ctypes.c_void_p(out.data_ptr()), ctypes.c_void_p(sp))
-    return out, _check(st)
+        sp = torch.cuda.current_stream(dev).cuda_stream
+    if dev == torch.cuda.current_device():
+        st = lib.expm(A.data_ptr(), n, batch, dt, tol, out.data_ptr(), sp)
+    else:
+        with torch.cuda.device(dev):
+            st = lib.expm(A.data_ptr(), n, batch, dt, tol, out.data_ptr(), sp)
+    if st < 0:
+        _check(st)
+    return out, st
 
 
 def expm_workspace_bytes(n: int, batch: int, dtype: int) -> int:
