@@ -88,3 +88,56 @@ def test_binding_refuses_host_tensors():
         ex.expm(torch.zeros(2, 4, 4, dtype=torch.float64))
     with pytest.raises(ex.ExpmError):
         ex.expm_select(torch.zeros(2, 4, 4, dtype=torch.float64))
+
+
+def test_coefficient_tables_in_the_kernel_header_are_the_printed_ones(golden_dir):
+    """The literals compiled into the HIP kernels equal the paper's tables (tests/golden fixture)."""
+    from conftest import read_coefficients
+    co = read_coefficients(os.path.join(golden_dir, "paper_coefficients.txt"))
+    text = open(os.path.join(ROOT, "paper_2512_20777_amd", "csrc", "expm_internal.h")).read()
+    defs = dict(re.findall(r"#define\s+(EXPM_T(?:8|15)_C\d+)\s+(\S+)", text))
+    assert len(defs) == 6 + 16
+    for k, v in co["T8"].items():
+        assert float(defs["EXPM_T8_" + k.upper()]) == v
+    for k, v in co["T15+"].items():
+        assert float(defs["EXPM_T15_" + k.upper()]) == v
+
+
+def test_selection_rule_of_the_library_matches_the_oracle_on_a_grid_of_norms(tmp_path):
+    """The library's scalar selection (host+device inline function) compiled for the host against
+    the oracle's, on a grid of (n1, n2) pairs and three tolerances: identical away from switch points."""
+    import subprocess
+    import numpy as np
+    from oracle import oracle_select_from_norms
+    src = tmp_path / "sel.cpp"
+    src.write_text(
+        '#include <cstdio>\n#include <cstdlib>\n#include <cmath>\n'
+        '#define __host__\n#define __device__\n#define __forceinline__ inline\n'
+        'namespace hipstub {}\n'
+        + _selection_source() +
+        'int main(int argc, char** argv) { double n1 = atof(argv[1]), n2 = atof(argv[2]), eps = atof(argv[3]);'
+        ' int m, s, f; expmk::select_order_scaling(n1, n2, eps, m, s, f); printf("%d %d %d\\n", m, s, f); return 0; }\n')
+    exe = tmp_path / "sel"
+    subprocess.run(["g++", "-O1", "-o", str(exe), str(src)], check=True)
+    rng = np.random.default_rng(17)
+    for eps in (2.0 ** -53, 2.0 ** -24, 1e-8):
+        for _ in range(60):
+            n1 = float(10.0 ** rng.uniform(-9, 4))
+            n2 = float(n1 * n1 * 10.0 ** rng.uniform(-3, 0))
+            exp = oracle_select_from_norms(n1, n2, eps)
+            corners = {oracle_select_from_norms(n1 * a, n2 * b, eps) for a in (1 - 1e-6, 1 + 1e-6) for b in (1 - 1e-6, 1 + 1e-6)}
+            out = subprocess.run([str(exe), repr(n1), repr(n2), repr(eps)], capture_output=True, text=True, check=True)
+            m, s, _f = [int(x) for x in out.stdout.split()]
+            if len(corners) == 1:
+                assert (m, s) == exp, (n1, n2, eps, (m, s), exp)
+            else:
+                assert (m, s) in corners
+
+
+def _selection_source():
+    """The selection function and its constants cut out of the kernel header (plain C++ once the
+    HIP qualifiers are defined away)."""
+    text = open(os.path.join(ROOT, "paper_2512_20777_amd", "csrc", "expm_internal.h")).read()
+    start = text.index("#define EXPM_T8_C1")
+    end = text.index("// Rounds after the W^2 product")
+    return "namespace expmk {\n" + text[start:end] + "}\n"
