@@ -111,7 +111,7 @@ def cpu_baseline(name, a, tol, workloads):
             "sample": "whole batch of %d, mean of %d runs, %.4f s per batch" % (a.shape[0], reps, sec)}
 
 
-def run_workload(name, steps, warmup, with_cpu, time_sel=False):
+def run_workload(name, steps, warmup, with_cpu, time_sel=False, compare_ps=False):
     import numpy as np
     import torch
     import paper_2512_20777_amd as ex
@@ -168,6 +168,25 @@ def run_workload(name, steps, warmup, with_cpu, time_sel=False):
                            "avg_launch_ms": k["ms"] / k["launches"], "launches_per_step": k["launches"] / max(2, min(steps, 20)),
                            "whole_call_frac": res["tflops"] / peak}
     res["roofline"]["traffic"] = recorded_traffic(name, res["roofline"]["kernel"])
+    if compare_ps:
+        # the paper's own comparison (Sec. 4): same tolerance, Paterson-Stockmeyer evaluation + Algorithm 3
+        ps_steps = max(2, steps // 4)
+        for _ in range(2):
+            ex.expm(d, w.tol, out=out, scheme=ex.SCHEME_PS)
+        torch.cuda.synchronize()
+        ps_stats = ex.expm_get_stats()
+        t0 = time.perf_counter()
+        for _ in range(ps_steps):
+            ex.expm(d, w.tol, out=out, scheme=ex.SCHEME_PS)
+        torch.cuda.synchronize()
+        ps_ms = (time.perf_counter() - t0) * 1e3 / ps_steps
+        res["paterson_stockmeyer_variant"] = {
+            "ms_per_step": ps_ms, "products": ps_stats["products"],
+            "product_ratio_vs_main": ps_stats["products"] / max(1, stats["products"]),
+            "time_ratio_vs_main": ps_ms / wall_ms,
+            "hist_m": {str(k): v for k, v in ps_stats["hist_m"].items() if v}}
+        ex.expm(d, w.tol, out=out)  # leave the main scheme as the last call
+        torch.cuda.synchronize()
     if with_cpu:
         res["cpu_baseline"] = cpu_baseline(name, a, w.tol, workloads)
     del d, out
@@ -205,6 +224,8 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
     ap.add_argument("--pmc-pass", action="store_true", help="short run for hardware-counter collection: a few "
                     "steps of the workload plus a plain device copy of 256 MiB as the calibration kernel")
+    ap.add_argument("--compare-ps", action="store_true", help="also run the Paterson-Stockmeyer scheme and report "
+                    "its products and time relative to the main scheme")
     ap.add_argument("--time-select", action="store_true", help="also time expm_select() alone (adds launches "
                     "of the product kernel that are not expm() steps)")
     args = ap.parse_args()
@@ -226,13 +247,14 @@ def main():
         return
     steps = args.steps if args.steps > 0 else DEFAULT_STEPS[head]
     warmup = args.warmup if args.warmup >= 0 else DEFAULT_WARMUP[head]
-    main_res = run_workload(head, steps, warmup, not args.no_cpu, args.time_select)
+    main_res = run_workload(head, steps, warmup, not args.no_cpu, args.time_select, args.compare_ps)
     per = [main_res]
     if not args.no_others:
         for name in ("C1", "C2", "C3", "C4", "C5f64", "C5f32"):
             if name == head:
                 continue
-            per.append(run_workload(name, DEFAULT_STEPS[name], DEFAULT_WARMUP[name], not args.no_cpu, args.time_select))
+            per.append(run_workload(name, DEFAULT_STEPS[name], DEFAULT_WARMUP[name], not args.no_cpu, args.time_select,
+                                    args.compare_ps))
         per.sort(key=lambda r: r["workload"])
     from paper_2512_20777_amd import workloads
     line = {

@@ -90,6 +90,23 @@ int expm_select(const void *A, int n, int batch, int dtype, double tol,
 int expm(const void *A, int n, int batch, int dtype, double tol, void *out, void *stream);
 
 /*
+ * Variants of the two calls above that pick the evaluation scheme (Sec. 3.3, Algorithm 2 with either
+ * selection algorithm):
+ *   EXPM_SCHEME_SASTRE  Algorithm 4 + the evaluation formulas of Sec. 3.1, orders {1,2,4,8,15+}
+ *                       (what expm / expm_select run; the paper's expm_flow_opt15);
+ *   EXPM_SCHEME_PS      Algorithm 3 + Paterson-Stockmeyer evaluation of the Taylor polynomial,
+ *                       orders {1,2,4,6,9,12,16}, powers up to W^4 (the paper's expm_flow_ps).  m_out then
+ *                       holds one of 0,1,2,4,6,9,12,16.  On the round-based path W^2, W^3 = W^2 W and
+ *                       W^4 = W^3 W are formed for the whole batch before the selection.
+ * All other arguments, blocking behaviour, ownership and status codes are as for expm_select / expm.
+ */
+#define EXPM_SCHEME_SASTRE 0
+#define EXPM_SCHEME_PS     1
+int expm_select_scheme(const void *A, int n, int batch, int dtype, double tol, int scheme,
+                       int32_t *m_out, int32_t *s_out);
+int expm_scheme(const void *A, int n, int batch, int dtype, double tol, int scheme, void *out, void *stream);
+
+/*
  * Bytes of device workspace the library holds for a call of this shape (the fused
  * small-matrix path needs only the per-matrix records).  The workspace is allocated
  * on first use, grown when a larger shape arrives, reused otherwise, and released by
@@ -103,7 +120,8 @@ int expm_reserve(int n, int batch, int dtype);
 /*
  * Statistics of the most recent expm()/expm_select() call.  Synchronises with the
  * stream of that call.  products = sum over matrices of pi(m)+s with pi = 0,0,1,2,3,4
- * for m = 0,1,2,4,8,15 (cost of the formulas of Sec. 3.1 plus one per squaring).
+ * for m = 0,1,2,4,8,15 (cost of the formulas of Sec. 3.1 plus one per squaring), resp.
+ * pi = 0,0,1,2,3,4,5,6 for m = 0,1,2,4,6,9,12,16 with the Paterson-Stockmeyer scheme (Table 1).
  */
 struct expm_stats {
     int64_t matrices;      /* batch of the call                                   */
@@ -112,9 +130,9 @@ struct expm_stats {
     int32_t dtype;
     int32_t rounds;        /* product rounds launched after the W^2 round (0 on the fused path) */
     int32_t warning;       /* 0, EXPM_WARN_NONFINITE, EXPM_WARN_SCALING_CAP (larger wins) */
-    int32_t fused_path;    /* 1 if the single-kernel small-matrix path ran        */
-    int32_t reserved;
-    int64_t hist_m[6];     /* matrices with m = 0,1,2,4,8,15                      */
+    int32_t fused_path;    /* 1 if the single-kernel on-chip path ran             */
+    int32_t scheme;        /* EXPM_SCHEME_* of the call                           */
+    int64_t hist_m[17];    /* matrices with order m, indexed by m = 0..16         */
     int64_t hist_s[21];    /* matrices with s = 0..20                             */
     int64_t nonfinite;     /* matrices flagged (-1,-1)                            */
 };

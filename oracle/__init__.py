@@ -9,4 +9,7 @@ from .expm_oracle import (  # noqa: F401
     oracle_select,
     oracle_select_from_norms,
     oracle_b16,
+    oracle_select_ps,
+    oracle_select_ps_from_norms,
+    oracle_expm_ps_batch,
 )

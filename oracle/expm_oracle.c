@@ -34,6 +34,9 @@
  *   - inputs are assumed finite (non-finite input is a host-side error path
  *     of the GPU library, not part of the method).
  *
+ * The file also holds the Paterson-Stockmeyer variant of the paper (Algorithm 3 selection,
+ * plain Taylor polynomial T_m, m in {1,2,4,6,9,12,16}); see further down.
+ *
  * Pins (tests/test_oracle_pins.py): the two worked selection examples of the
  * paper (Remark 1; Sec. 4.2, normal matrix of norm 12.8), closed forms
  * (diagonal, nilpotent, rotation, Remark-1 matrix), det/trace and inverse
@@ -341,6 +344,188 @@ int oracle_expm_batch(const double *W, int n, int batch, double eps, double *X,
         for (int b = 0; b < batch; ++b)
             expm_matrix(W + (size_t)b * nn, n, eps, X + (size_t)b * nn, work, 1,
                         &m[b], &s[b], &n1[b], &n2[b], &near[b]);
+        free(work);
+    }
+    return fail ? -3 : used;
+}
+
+/* ------------------------------------------------------------------------------------------
+ * Paterson-Stockmeyer variant (Algorithm 3 of Sec. 3.3 with Algorithm 2): orders
+ * M = [1,2,4,6,9,12,16], powers W^j, j = ceil(sqrt(m)) in {1,2,2,3,3,4,4}, k = m/j.
+ * Bounds from the table after Algorithm 3:
+ *   m=1      : E1 = n1^2/2!,              E2 = n1^3/3!
+ *   m=j*k>1  : E1 = nj^k * n1 / (m+1)!,   E2 = nj^k * n2 / (m+2)!,   nj = ||W^j||_1
+ * First order with E1+E2 <= eps wins with s = 0; otherwise m = 16 and
+ * s = max_i ceil(log2(E_i/eps)/(16+i)), i = 1,2, capped at 20.
+ * The polynomial is the plain Taylor polynomial T_m (direct summation here; how it is
+ * evaluated -- Paterson-Stockmeyer -- is the GPU side's business).
+ * ------------------------------------------------------------------------------------------ */
+void oracle_select_ps_from_norms(double n1, double n2, double n3, double n4, double eps, int *m_out, int *s_out)
+{
+    static const int M[7] = {1, 2, 4, 6, 9, 12, 16};
+    static const int J[7] = {1, 2, 2, 3, 3, 4, 4};
+    int m = 0, s = 0, found = 0;
+    double E1 = 0.0, E2 = 0.0;
+    if (n1 == 0.0) {
+        *m_out = 0;
+        *s_out = 0;
+        return;
+    }
+    const double nj[5] = {0.0, n1, n2, n3, n4};
+    for (int i = 0; i < 7 && !found; ++i) {
+        m = M[i];
+        const int j = J[i], k = m / j;
+        if (m == 1) {
+            E1 = n1 * n1 / factorial(2);
+            E2 = n1 * n1 * n1 / factorial(3);
+        } else {
+            const double pk = ipow(nj[j], k);
+            E1 = pk * n1 / factorial(m + 1);
+            E2 = pk * n2 / factorial(m + 2);
+        }
+        if (E1 + E2 <= eps)
+            found = 1;
+    }
+    if (!found) {
+        const double E[2] = {E1, E2};
+        for (int i = 1; i <= 2; ++i) {
+            int s1;
+            if (!isfinite(E[i - 1])) {
+                s1 = ORACLE_S_CAP;
+            } else if (E[i - 1] <= 0.0) {
+                s1 = 0;
+            } else {
+                const double q = ceil(log2(E[i - 1] / eps) / (double)(m + i));
+                s1 = (q > (double)ORACLE_S_CAP) ? ORACLE_S_CAP : (q < 0.0 ? 0 : (int)q);
+            }
+            if (s1 > s)
+                s = s1;
+        }
+    }
+    if (s > ORACLE_S_CAP)
+        s = ORACLE_S_CAP;
+    *m_out = m;
+    *s_out = s;
+}
+
+/* Norms of W, W^2, W^3 = W^2*W, W^4 = W^3*W (powers by repeated multiplication, as in Algorithm 3),
+ * the choice, and the near flag over the 16 corners of the four norms.  work: 3*n*n doubles. */
+static void select_ps_matrix(const double *W, int n, double eps, double *work, int par,
+                             int *m, int *s, double norms[4], int *near)
+{
+    const size_t nn = (size_t)n * n;
+    double *W2 = work, *W3 = work + nn, *W4 = work + 2 * nn;
+    norms[0] = oracle_norm1(W, n);
+    norms[1] = norms[2] = norms[3] = 0.0;
+    *near = 0;
+    if (norms[0] == 0.0) {
+        *m = 0;
+        *s = 0;
+        return;
+    }
+    const double hi = norms[0] * (1.0 + 1e-6);
+    if (!(hi * hi / 2.0 + hi * hi * hi / 6.0 <= eps)) {
+        matmul_impl(W, W, W2, n, par);
+        matmul_impl(W2, W, W3, n, par);
+        matmul_impl(W3, W, W4, n, par);
+        norms[1] = oracle_norm1(W2, n);
+        norms[2] = oracle_norm1(W3, n);
+        norms[3] = oracle_norm1(W4, n);
+    }
+    oracle_select_ps_from_norms(norms[0], norms[1], norms[2], norms[3], eps, m, s);
+    for (int c = 0; c < 16; ++c) {
+        double f[4];
+        for (int t = 0; t < 4; ++t)
+            f[t] = (c >> t) & 1 ? 1.0 + 1e-6 : 1.0 - 1e-6;
+        int mc, sc;
+        oracle_select_ps_from_norms(norms[0] * f[0], norms[1] * f[1], norms[2] * f[2], norms[3] * f[3], eps, &mc, &sc);
+        if (mc != *m || sc != *s)
+            *near = 1;
+    }
+}
+
+int oracle_select_ps(const double *W, int n, double eps, int *m, int *s, double *norms4, int *near)
+{
+    double *work = (double *)malloc(sizeof(double) * 3 * (size_t)n * n + 8);
+    if (!work)
+        return -3;
+    select_ps_matrix(W, n, eps, work, 0, m, s, norms4, near);
+    free(work);
+    return 0;
+}
+
+/* Algorithm 2 with Algorithm 3: X = T_m(W/2^s) by direct summation, s squarings.  work: 6*n*n doubles. */
+static void expm_ps_matrix(const double *W, int n, double eps, double *X, double *work, int par,
+                           int *m_out, int *s_out, double norms[4], int *near)
+{
+    const size_t nn = (size_t)n * n;
+    double *A = work, *term = work + nn, *next = work + 2 * nn;
+    int m, s;
+    select_ps_matrix(W, n, eps, work + 3 * nn, par, &m, &s, norms, near);
+    *m_out = m;
+    *s_out = s;
+    const double scale = ldexp(1.0, -s);
+    for (size_t t = 0; t < nn; ++t)
+        A[t] = W[t] * scale;
+    memset(X, 0, sizeof(double) * nn);
+    for (int i = 0; i < n; ++i)
+        X[(size_t)i * n + i] = 1.0;
+    for (int k = 1; k <= m; ++k) {
+        if (k == 1) {
+            memcpy(term, A, sizeof(double) * nn);
+        } else {
+            matmul_impl(term, A, next, n, par);
+            const double inv = (double)k;
+            for (size_t t = 0; t < nn; ++t)
+                term[t] = next[t] / inv;
+        }
+        for (size_t t = 0; t < nn; ++t)
+            X[t] += term[t];
+    }
+    for (int q = 0; q < s; ++q) {
+        matmul_impl(X, X, next, n, par);
+        memcpy(X, next, sizeof(double) * nn);
+    }
+}
+
+/* Batch driver of the Paterson-Stockmeyer variant; norms is [batch][4]. */
+int oracle_expm_ps_batch(const double *W, int n, int batch, double eps, double *X,
+                         int *m, int *s, double *norms, int *near, int threads)
+{
+    const size_t nn = (size_t)n * n;
+    int used = 1;
+#ifdef _OPENMP
+    if (threads <= 0)
+        threads = omp_get_max_threads();
+    used = threads;
+    omp_set_num_threads(threads);
+#else
+    (void)threads;
+#endif
+    int fail = 0;
+    if (n < 256) {
+#pragma omp parallel
+        {
+            double *work = (double *)malloc(sizeof(double) * 6 * nn + 8);
+            if (!work) {
+#pragma omp atomic write
+                fail = 1;
+            }
+#pragma omp for schedule(dynamic, 1)
+            for (int b = 0; b < batch; ++b) {
+                if (work)
+                    expm_ps_matrix(W + (size_t)b * nn, n, eps, X + (size_t)b * nn, work, 0,
+                                   &m[b], &s[b], norms + 4 * (size_t)b, &near[b]);
+            }
+            free(work);
+        }
+    } else {
+        double *work = (double *)malloc(sizeof(double) * 6 * nn + 8);
+        if (!work)
+            return -3;
+        for (int b = 0; b < batch; ++b)
+            expm_ps_matrix(W + (size_t)b * nn, n, eps, X + (size_t)b * nn, work, 1,
+                           &m[b], &s[b], norms + 4 * (size_t)b, &near[b]);
         free(work);
     }
     return fail ? -3 : used;

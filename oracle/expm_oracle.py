@@ -52,6 +52,13 @@ def _load():
         lib.oracle_expm_batch.restype = ctypes.c_int
         lib.oracle_expm_batch.argtypes = [dp, ctypes.c_int, ctypes.c_int, ctypes.c_double, dp,
                                           ip, ip, dp, dp, ip, ctypes.c_int]
+        lib.oracle_select_ps_from_norms.restype = None
+        lib.oracle_select_ps_from_norms.argtypes = [ctypes.c_double] * 5 + [ip, ip]
+        lib.oracle_select_ps.restype = ctypes.c_int
+        lib.oracle_select_ps.argtypes = [dp, ctypes.c_int, ctypes.c_double, ip, ip, dp, ip]
+        lib.oracle_expm_ps_batch.restype = ctypes.c_int
+        lib.oracle_expm_ps_batch.argtypes = [dp, ctypes.c_int, ctypes.c_int, ctypes.c_double, dp,
+                                             ip, ip, dp, ip, ctypes.c_int]
         lib.oracle_max_threads.restype = ctypes.c_int
         lib.oracle_max_threads.argtypes = []
         _lib = lib
@@ -146,6 +153,48 @@ def oracle_expm_batch(W, tol: float, threads: int = 0):
         if used < 0:
             raise MemoryError("oracle_expm_batch")
     return X, dict(m=m, s=s, n1=n1, n2=n2, near=near.astype(bool), threads=used)
+
+
+def oracle_select_ps_from_norms(n1: float, n2: float, n3: float, n4: float, tol: float) -> Tuple[int, int]:
+    """Algorithm 3 on the norms of W, W^2, W^3, W^4."""
+    m, s = ctypes.c_int(0), ctypes.c_int(0)
+    _load().oracle_select_ps_from_norms(float(n1), float(n2), float(n3), float(n4), float(tol),
+                                        ctypes.byref(m), ctypes.byref(s))
+    return m.value, s.value
+
+
+def oracle_select_ps(W, tol: float):
+    """Algorithm 3 for one matrix -> dict(m, s, norms[4], near)."""
+    a = _as_f64(W)
+    n = a.shape[0]
+    m, s, near = ctypes.c_int(0), ctypes.c_int(0), ctypes.c_int(0)
+    norms = np.zeros(4, dtype=np.float64)
+    rc = _load().oracle_select_ps(_dptr(a), n, float(tol), ctypes.byref(m), ctypes.byref(s), _dptr(norms),
+                                  ctypes.byref(near))
+    if rc != 0:
+        raise MemoryError("oracle_select_ps")
+    return dict(m=m.value, s=s.value, norms=norms, near=bool(near.value))
+
+
+def oracle_expm_ps_batch(W, tol: float, threads: int = 0):
+    """Paterson-Stockmeyer variant on a batch -> (X fp64, dict of arrays m, s, norms[b][4], near, threads)."""
+    a = _as_f64(W)
+    if a.ndim == 2:
+        a = a[None]
+    assert a.ndim == 3 and a.shape[1] == a.shape[2]
+    b, n = a.shape[0], a.shape[1]
+    X = np.empty_like(a)
+    m = np.zeros(b, dtype=np.int32)
+    s = np.zeros(b, dtype=np.int32)
+    near = np.zeros(b, dtype=np.int32)
+    norms = np.zeros((b, 4), dtype=np.float64)
+    used = 0
+    if b > 0 and n > 0:
+        used = _load().oracle_expm_ps_batch(_dptr(a), n, b, float(tol), _dptr(X), _iptr(m), _iptr(s),
+                                            _dptr(norms), _iptr(near), int(threads))
+        if used < 0:
+            raise MemoryError("oracle_expm_ps_batch")
+    return X, dict(m=m, s=s, norms=norms, near=near.astype(bool), threads=used)
 
 
 def oracle_max_threads() -> int:

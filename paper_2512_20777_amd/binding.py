@@ -16,6 +16,8 @@ _lib = None
 
 DTYPE_F32 = 0
 DTYPE_F64 = 1
+SCHEME_SASTRE = 0   # Algorithm 4 + evaluation formulas of Sec. 3.1 (orders 1,2,4,8,15+)
+SCHEME_PS = 1       # Algorithm 3 + Paterson-Stockmeyer (orders 1,2,4,6,9,12,16)
 
 EXPM_KCLASS = {"norm": 0, "select": 1, "gemm": 2, "fused": 3}
 
@@ -30,7 +32,7 @@ class _Stats(ctypes.Structure):
     _fields_ = [
         ("matrices", ctypes.c_int64), ("products", ctypes.c_int64), ("n", ctypes.c_int32), ("dtype", ctypes.c_int32),
         ("rounds", ctypes.c_int32), ("warning", ctypes.c_int32), ("fused_path", ctypes.c_int32),
-        ("reserved", ctypes.c_int32), ("hist_m", ctypes.c_int64 * 6), ("hist_s", ctypes.c_int64 * 21),
+        ("scheme", ctypes.c_int32), ("hist_m", ctypes.c_int64 * 17), ("hist_s", ctypes.c_int64 * 21),
         ("nonfinite", ctypes.c_int64),
     ]
 
@@ -64,6 +66,10 @@ def load_library():
     lib.expm_select.argtypes = [vp, ci, ci, ci, cd, i32p, i32p]
     lib.expm.restype = ci
     lib.expm.argtypes = [vp, ci, ci, ci, cd, vp, vp]
+    lib.expm_select_scheme.restype = ci
+    lib.expm_select_scheme.argtypes = [vp, ci, ci, ci, cd, ci, i32p, i32p]
+    lib.expm_scheme.restype = ci
+    lib.expm_scheme.argtypes = [vp, ci, ci, ci, cd, ci, vp, vp]
     lib.expm_workspace_bytes.restype = ctypes.c_size_t
     lib.expm_workspace_bytes.argtypes = [ci, ci, ci]
     lib.expm_reserve.restype = ci
@@ -117,7 +123,7 @@ def _describe(A) -> Tuple[int, int, int]:
     return A.shape[1], A.shape[0], dt
 
 
-def expm_select(A, tol: float = 0.0):
+def expm_select(A, tol: float = 0.0, scheme: int = SCHEME_SASTRE):
     """(m, s) per matrix as two int32 numpy arrays, plus the status (0 or a warning code)."""
     import numpy as np
     import torch
@@ -127,12 +133,12 @@ def expm_select(A, tol: float = 0.0):
     i32p = ctypes.POINTER(ctypes.c_int32)
     with torch.cuda.device(A.device):
         torch.cuda.current_stream().synchronize()  # the C entry point runs on the null stream
-        st = load_library().expm_select(A.data_ptr(), n, batch, dt, float(tol),
-                                        m.ctypes.data_as(i32p), s.ctypes.data_as(i32p))
+        st = load_library().expm_select_scheme(A.data_ptr(), n, batch, dt, float(tol), int(scheme),
+                                               m.ctypes.data_as(i32p), s.ctypes.data_as(i32p))
     return m, s, _check(st)
 
 
-def expm(A, tol: float = 0.0, out=None, stream=None):
+def expm(A, tol: float = 0.0, out=None, stream=None, scheme: int = SCHEME_SASTRE):
     """e^A for a [batch][n][n] device tensor; returns (out, status).  Runs on torch's current stream.
 
     Marshalling only, kept short: for small batches the call rate is bounded by this function.
@@ -150,10 +156,10 @@ def expm(A, tol: float = 0.0, out=None, stream=None):
     else:
         sp = torch.cuda.current_stream(dev).cuda_stream
     if dev == torch.cuda.current_device():
-        st = lib.expm(A.data_ptr(), n, batch, dt, tol, out.data_ptr(), sp)
+        st = lib.expm_scheme(A.data_ptr(), n, batch, dt, tol, scheme, out.data_ptr(), sp)
     else:
         with torch.cuda.device(dev):
-            st = lib.expm(A.data_ptr(), n, batch, dt, tol, out.data_ptr(), sp)
+            st = lib.expm_scheme(A.data_ptr(), n, batch, dt, tol, scheme, out.data_ptr(), sp)
     if st < 0:
         _check(st)
     return out, st
@@ -171,8 +177,8 @@ def expm_get_stats() -> dict:
     st = _Stats()
     _check(load_library().expm_get_stats(ctypes.byref(st)))
     return dict(matrices=st.matrices, products=st.products, n=st.n, dtype=st.dtype, rounds=st.rounds,
-                warning=st.warning, fused_path=st.fused_path, nonfinite=st.nonfinite,
-                hist_m=dict(zip((0, 1, 2, 4, 8, 15), list(st.hist_m))), hist_s=list(st.hist_s))
+                warning=st.warning, fused_path=st.fused_path, scheme=st.scheme, nonfinite=st.nonfinite,
+                hist_m={m: int(c) for m, c in enumerate(st.hist_m)}, hist_s=list(st.hist_s))
 
 
 def expm_profile_enable(on: bool) -> None:

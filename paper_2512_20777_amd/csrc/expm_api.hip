@@ -25,6 +25,7 @@ struct LastCall {
     int n = 0, batch = 0, dtype = 0;
     int rounds = 0;
     int fused = 0;
+    int scheme = 0;
     hipStream_t stream = nullptr;
     MatInfo *info_dev = nullptr;
     int *summary_dev = nullptr;
@@ -59,7 +60,7 @@ int hip_fail(hipError_t e)
     } while (0)
 
 struct Layout {
-    size_t info, order, summary, n1, n2, colpart, mats, total;
+    size_t info, order, summary, n1, n2, n3, n4, colpart, mats, total;
     size_t mat_bytes;
 };
 
@@ -76,6 +77,8 @@ Layout make_layout(int n, int batch, int dtype)
     const size_t nblk = (size_t)general_colblocks(n);
     L.n1 = off;      off = align_up(off + (size_t)batch * nblk * sizeof(double), 256);
     L.n2 = off;      off = align_up(off + (size_t)batch * nblk * sizeof(double), 256);
+    L.n3 = off;      off = align_up(off + (size_t)batch * nblk * sizeof(double), 256);
+    L.n4 = off;      off = align_up(off + (size_t)batch * nblk * sizeof(double), 256);
     L.mat_bytes = 0;
     L.colpart = off;
     L.mats = off;
@@ -197,6 +200,8 @@ Bound bind(const void *A, void *out, int n, int batch, int dtype)
     B.gb.order = reinterpret_cast<int *>(base + B.L.order);
     B.gb.n1 = reinterpret_cast<double *>(base + B.L.n1);
     B.gb.n2 = reinterpret_cast<double *>(base + B.L.n2);
+    B.gb.n3 = reinterpret_cast<double *>(base + B.L.n3);
+    B.gb.n4 = reinterpret_cast<double *>(base + B.L.n4);
     B.gb.colpart = reinterpret_cast<double *>(base + B.L.colpart);
     B.gb.base[BUF_W] = const_cast<void *>(A);
     for (int i = 0; i < 7; ++i) B.gb.base[BUF_W2 + i] = base + B.L.mats + (size_t)i * B.L.mat_bytes;
@@ -206,7 +211,7 @@ Bound bind(const void *A, void *out, int n, int batch, int dtype)
 }
 
 // Selection stage of the round-based path: norms, W2, (m,s), plan; leaves the summary in pinned memory.
-int run_selection_general(const Bound &B, int n, int batch, int dtype, double tol, hipStream_t stream)
+int run_selection_general(const Bound &B, int n, int batch, int dtype, double tol, int scheme, hipStream_t stream)
 {
     const double w = dtype == EXPM_DTYPE_F64 ? 8.0 : 4.0;
     const double nn = (double)n * n;
@@ -218,15 +223,26 @@ int run_selection_general(const Bound &B, int n, int batch, int dtype, double to
     const int wt0 = choose_tile_shape(n, batch);
     {
         Bracket br(stream, EXPM_KCLASS_GEMM, 2.0 * nn * n * batch, 2.0 * batch * nn * w);
-        EXPM_TRY(launch_square_round(B.gb, n, batch, dtype, wt0, stream));
+        EXPM_TRY(launch_power_round(B.gb, n, batch, dtype, wt0, 2, stream));
     }
     {
         Bracket br(stream, EXPM_KCLASS_NORM, 0.0, 0.0);
         EXPM_TRY(launch_colmax(B.gb, n, batch, 2, (n + 32 * wt0 - 1) / (32 * wt0), stream));
     }
+    if (scheme == kSchemePS) {
+        // Algorithm 3 looks at ||W^3|| and ||W^4|| as well: W^3 = W^2 W, W^4 = W^3 W for the whole batch
+        for (int which = 3; which <= 4; ++which) {
+            {
+                Bracket br(stream, EXPM_KCLASS_GEMM, 2.0 * nn * n * batch, 2.0 * batch * nn * w);
+                EXPM_TRY(launch_power_round(B.gb, n, batch, dtype, wt0, which, stream));
+            }
+            Bracket br(stream, EXPM_KCLASS_NORM, 0.0, 0.0);
+            EXPM_TRY(launch_colmax(B.gb, n, batch, which, (n + 32 * wt0 - 1) / (32 * wt0), stream));
+        }
+    }
     {
         Bracket br(stream, EXPM_KCLASS_SELECT, 0.0, 0.0);
-        EXPM_TRY(launch_select_plan(B.gb, n, batch, tol, stream));
+        EXPM_TRY(launch_select_plan(B.gb, n, batch, tol, scheme, stream));
     }
     // the plan summary travels to pinned host memory; g_summary_ready marks the copy, so that the
     // caller can queue more work behind it before waiting
@@ -236,9 +252,10 @@ int run_selection_general(const Bound &B, int n, int batch, int dtype, double to
     return EXPM_OK;
 }
 
-void remember(int n, int batch, int dtype, int rounds, int fused, hipStream_t stream, const Bound &B)
+void remember(int n, int batch, int dtype, int rounds, int fused, int scheme, hipStream_t stream, const Bound &B)
 {
     g_last.valid = true;
+    g_last.scheme = scheme;
     g_last.n = n; g_last.batch = batch; g_last.dtype = dtype;
     g_last.rounds = rounds; g_last.fused = fused; g_last.stream = stream;
     g_last.info_dev = B.gb.info;
@@ -270,6 +287,12 @@ int expm_reserve(int n, int batch, int dtype)
 
 int expm_select(const void *A, int n, int batch, int dtype, double tol, int32_t *m_out, int32_t *s_out)
 {
+    return expm_select_scheme(A, n, batch, dtype, tol, EXPM_SCHEME_SASTRE, m_out, s_out);
+}
+
+int expm_select_scheme(const void *A, int n, int batch, int dtype, double tol, int scheme, int32_t *m_out, int32_t *s_out)
+{
+    if (scheme != EXPM_SCHEME_SASTRE && scheme != EXPM_SCHEME_PS) return EXPM_ERR_INVALID_ARG;
     int rc = check_args(A, n, batch, dtype, tol);
     if (rc != EXPM_OK) return rc;
     if (batch > 0 && (m_out == nullptr || s_out == nullptr)) return EXPM_ERR_INVALID_ARG;
@@ -284,13 +307,13 @@ int expm_select(const void *A, int n, int batch, int dtype, double tol, int32_t 
     const Bound B = bind(A, nullptr, n, batch, dtype);
     int flags = 0;
     if (small_path_supported(n, dtype)) {
-        EXPM_TRY(launch_small(A, nullptr, n, batch, dtype, tol, 1, B.gb.info, stream));
-        remember(n, batch, dtype, 0, 1, stream, B);
+        EXPM_TRY(launch_small(A, nullptr, n, batch, dtype, tol, 1, scheme, B.gb.info, stream));
+        remember(n, batch, dtype, 0, 1, scheme, stream, B);
     } else {
-        rc = run_selection_general(B, n, batch, dtype, tol, stream);
+        rc = run_selection_general(B, n, batch, dtype, tol, scheme, stream);
         if (rc != EXPM_OK) return rc;
         EXPM_TRY(hipEventSynchronize(g_summary_ready));
-        remember(n, batch, dtype, 0, 0, stream, B);
+        remember(n, batch, dtype, 0, 0, scheme, stream, B);
     }
     EXPM_TRY(hipMemcpyAsync(g_ws.host_info, B.gb.info, (size_t)batch * sizeof(MatInfo), hipMemcpyDeviceToHost, stream));
     EXPM_TRY(hipStreamSynchronize(stream));
@@ -304,6 +327,12 @@ int expm_select(const void *A, int n, int batch, int dtype, double tol, int32_t 
 
 int expm(const void *A, int n, int batch, int dtype, double tol, void *out, void *stream_v)
 {
+    return expm_scheme(A, n, batch, dtype, tol, EXPM_SCHEME_SASTRE, out, stream_v);
+}
+
+int expm_scheme(const void *A, int n, int batch, int dtype, double tol, int scheme, void *out, void *stream_v)
+{
+    if (scheme != EXPM_SCHEME_SASTRE && scheme != EXPM_SCHEME_PS) return EXPM_ERR_INVALID_ARG;
     int rc = check_args(A, n, batch, dtype, tol);
     if (rc != EXPM_OK) return rc;
     if (n == 0 || batch == 0) return EXPM_OK;
@@ -325,24 +354,24 @@ int expm(const void *A, int n, int batch, int dtype, double tol, void *out, void
         // one kernel, nothing read back: warnings of this path surface through expm_get_stats()
         {
             Bracket br(stream, EXPM_KCLASS_FUSED, 0.0, 2.0 * batch * nn * w);
-            EXPM_TRY(launch_small(A, out, n, batch, dtype, tol, 0, B.gb.info, stream));
+            EXPM_TRY(launch_small(A, out, n, batch, dtype, tol, 0, scheme, B.gb.info, stream));
         }
-        remember(n, batch, dtype, 0, 1, stream, B);
+        remember(n, batch, dtype, 0, 1, scheme, stream, B);
         return EXPM_OK;
     }
 
-    rc = run_selection_general(B, n, batch, dtype, tol, stream);
+    rc = run_selection_general(B, n, batch, dtype, tol, scheme, stream);
     if (rc != EXPM_OK) return rc;
     // Work that does not need the host's view of the plan is queued before the wait, so the device
     // stays busy while the summary is read: operand preparation, and the first chain round over the
     // whole batch (workgroups of matrices that need no product leave at once).
     {
         Bracket br(stream, EXPM_KCLASS_SELECT, 0.0, 0.0);
-        EXPM_TRY(launch_prepare(B.gb, n, batch, dtype, stream));
+        EXPM_TRY(launch_prepare(B.gb, n, batch, dtype, scheme, stream));
     }
     {
         Bracket br(stream, EXPM_KCLASS_GEMM, 0.0, 0.0);  // its work is filled in once the plan is known
-        EXPM_TRY(launch_chain_round(B.gb, n, batch, 1, dtype, choose_tile_shape(n, batch), stream));
+        EXPM_TRY(launch_chain_round(B.gb, n, batch, 1, dtype, choose_tile_shape(n, batch), scheme, stream));
     }
     const size_t round1_event = g_events.size();
     EXPM_TRY(hipEventSynchronize(g_summary_ready));
@@ -357,9 +386,9 @@ int expm(const void *A, int n, int batch, int dtype, double tol, void *out, void
         const int active = g_ws.host_summary[2 + r];
         if (active <= 0) break;
         Bracket br(stream, EXPM_KCLASS_GEMM, 2.0 * nn * n * active, 2.0 * active * nn * w);
-        EXPM_TRY(launch_chain_round(B.gb, n, active, r, dtype, choose_tile_shape(n, active), stream));
+        EXPM_TRY(launch_chain_round(B.gb, n, active, r, dtype, choose_tile_shape(n, active), scheme, stream));
     }
-    remember(n, batch, dtype, longest, 0, stream, B);
+    remember(n, batch, dtype, longest, 0, scheme, stream, B);
     return warning_from_flags(flags);
 }
 
@@ -376,21 +405,21 @@ int expm_get_stats(struct expm_stats *st)
     st->dtype = g_last.dtype;
     st->rounds = g_last.rounds;
     st->fused_path = g_last.fused;
+    st->scheme = g_last.scheme;
     int flags = 0;
     for (int b = 0; b < g_last.batch; ++b) {
         const MatInfo &mi = g_ws.host_info[b];
         flags |= mi.flags;
         if (mi.m < 0) { st->nonfinite++; continue; }
-        int slot = 0, pi = 0;
-        switch (mi.m) {
-        case 0: slot = 0; pi = 0; break;
-        case 1: slot = 1; pi = 0; break;
-        case 2: slot = 2; pi = 1; break;
-        case 4: slot = 3; pi = 2; break;
-        case 8: slot = 4; pi = 3; break;
-        default: slot = 5; pi = 4; break;
+        // products the method spends: Sec. 3.1 formulas 0,0,1,2,3,4 for m = 0,1,2,4,8,15; Paterson-Stockmeyer
+        // (powers up to W^j plus k-1 Horner steps) 0,0,1,2,3,4,5,6 for m = 0,1,2,4,6,9,12,16
+        int pi = 0;
+        if (g_last.scheme == kSchemePS) {
+            pi = mi.m < 2 ? 0 : ps_j(mi.m) - 1 + ps_k(mi.m) - 1;
+        } else {
+            pi = mi.m < 2 ? 0 : (mi.m == 2 ? 1 : (mi.m == 4 ? 2 : (mi.m == 8 ? 3 : 4)));
         }
-        st->hist_m[slot]++;
+        if (mi.m >= 0 && mi.m <= 16) st->hist_m[mi.m]++;
         if (mi.s >= 0 && mi.s <= EXPM_S_CAP) st->hist_s[mi.s]++;
         st->products += pi + mi.s;
     }

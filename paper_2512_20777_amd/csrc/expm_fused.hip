@@ -42,7 +42,7 @@ __device__ __forceinline__ double pow2neg_f(int e)
     return __longlong_as_double((long long)(1023 - e) << 52);
 }
 
-template <typename T, int NT>
+template <typename T, int NT, int SCHEME>
 __global__ __launch_bounds__(NT == 1 ? 64 : 256) void fused_expm_kernel(const T *__restrict__ Ain, T *__restrict__ Out,
                                                                         int n, double eps, int select_only,
                                                                         MatInfo *__restrict__ info)
@@ -193,8 +193,48 @@ __global__ __launch_bounds__(NT == 1 ? 64 : 256) void fused_expm_kernel(const T 
 
     int m = 0, s = 0, flags = 0;
     const double n1 = norm1_of_P();
-    double n2 = 0.0;
-    {
+    T a3v[TH][TH][4], a4v[TH][TH][4];  // W^3, W^4 of the Paterson-Stockmeyer variant
+    if constexpr (SCHEME == kSchemePS) {
+        // Algorithm 3: powers are formed one by one, only as far as the orders tried need them.
+        // P holds the newest power (left operand), Q keeps W (right operand): W^j = W^(j-1) * W.
+        double nrm[4] = {n1, 0.0, 0.0, 0.0};
+        bool need_more = false;
+        select_ps_order_scaling(nrm, 1, eps, m, s, flags, need_more);
+        if (need_more) {
+            product();  // W * W
+            __syncthreads();
+            for_owned([&](int ti, int tj, int v, int r, int c) {
+                a2v[ti][tj][v] = acc[ti][tj][v];
+                P[r * LPA + c] = acc[ti][tj][v];
+            });
+            __syncthreads();
+            nrm[1] = norm1_of_P();
+            select_ps_order_scaling(nrm, 2, eps, m, s, flags, need_more);
+        }
+        if (need_more) {
+            product();  // W^2 * W
+            __syncthreads();
+            for_owned([&](int ti, int tj, int v, int r, int c) {
+                a3v[ti][tj][v] = acc[ti][tj][v];
+                P[r * LPA + c] = acc[ti][tj][v];
+            });
+            __syncthreads();
+            nrm[2] = norm1_of_P();
+            select_ps_order_scaling(nrm, 3, eps, m, s, flags, need_more);
+        }
+        if (need_more) {
+            product();  // W^3 * W
+            __syncthreads();
+            for_owned([&](int ti, int tj, int v, int r, int c) {
+                a4v[ti][tj][v] = acc[ti][tj][v];
+                P[r * LPA + c] = acc[ti][tj][v];
+            });
+            __syncthreads();
+            nrm[3] = norm1_of_P();
+            select_ps_order_scaling(nrm, 4, eps, m, s, flags, need_more);
+        }
+    } else {
+        double n2 = 0.0;
         // orders 0 and 1 need no product: Algorithm 4 forms W^2 only once the m = 1 test has failed
         const bool finite1 = n1 == n1;
         const bool tiny = finite1 && (n1 == 0.0 || (0.5 * n1 * n1 + (1.0 / 6.0) * n1 * n1 * n1 <= eps));
@@ -208,8 +248,8 @@ __global__ __launch_bounds__(NT == 1 ? 64 : 256) void fused_expm_kernel(const T 
             __syncthreads();
             n2 = norm1_of_P();
         }
+        select_order_scaling(n1, n2, eps, m, s, flags);
     }
-    select_order_scaling(n1, n2, eps, m, s, flags);
     if (tid == 0) {
         MatInfo mi;
         mi.m = m; mi.s = s; mi.len = 0; mi.flags = flags;
@@ -223,6 +263,60 @@ __global__ __launch_bounds__(NT == 1 ? 64 : 256) void fused_expm_kernel(const T 
         return;
     }
 
+    // The polynomial X ends in registers xv (aliasing acc's storage is left to the compiler).
+    T xv[TH][TH][4];
+    if constexpr (SCHEME == kSchemePS) {
+        // ---- Paterson-Stockmeyer: T_m(A) = Horner in A^j with blocks of degree < j, m = j*k -----------------
+        const int j = ps_j(m), k = ps_k(m);
+        if (s > 0) {
+            const T sg = (T)pow2neg_f(s), sg2 = (T)pow2neg_f(2 * s), sg3 = (T)pow2neg_f(3 * s), sg4 = (T)pow2neg_f(4 * s);
+            for_owned([&](int ti, int tj, int v, int, int) {
+                av[ti][tj][v] *= sg;
+                if (j >= 2 || m == 2) a2v[ti][tj][v] *= sg2;
+                if (j >= 3) a3v[ti][tj][v] *= sg3;
+                if (j >= 4) a4v[ti][tj][v] *= sg4;
+            });
+        }
+        auto pw = [&](int r, int ti, int tj, int v) -> T {
+            return r == 1 ? av[ti][tj][v] : (r == 2 ? a2v[ti][tj][v] : (r == 3 ? a3v[ti][tj][v] : a4v[ti][tj][v]));
+        };
+        if (k == 1) {  // orders 0, 1, 2: no further product
+            for_owned([&](int ti, int tj, int v, int r, int c) {
+                T x = dg(r, c);
+                if (m >= 1) x += av[ti][tj][v];
+                if (m == 2) x += a2v[ti][tj][v] / (T)2;
+                xv[ti][tj][v] = x;
+            });
+        } else {
+            T cf[5];
+#pragma unroll
+            for (int r = 0; r <= 4; ++r) cf[r] = r <= j ? (T)inv_factorial((k - 1) * j + r) : (T)0;
+            __syncthreads();  // every wave is done with P (norm) before it is overwritten
+            for_owned([&](int ti, int tj, int v, int r, int c) {
+                Q[r * LPB + c] = pw(j, ti, tj, v);  // right operand of every Horner step: A^j
+                T h = cf[0] * dg(r, c) + cf[1] * av[ti][tj][v] + cf[2] * a2v[ti][tj][v];
+                if (j >= 3) h += cf[3] * a3v[ti][tj][v];
+                if (j >= 4) h += cf[4] * a4v[ti][tj][v];
+                P[r * LPA + c] = h;              // top block c_{(k-1)j} I + ... + c_m A^j
+            });
+            for (int q = k - 2; q >= 0; --q) {
+#pragma unroll
+                for (int r = 0; r <= 3; ++r) cf[r] = r < j ? (T)inv_factorial(q * j + r) : (T)0;
+                __syncthreads();
+                product();
+                for_owned([&](int ti, int tj, int v, int r, int c) {
+                    T h = acc[ti][tj][v] + cf[0] * dg(r, c) + cf[1] * av[ti][tj][v];
+                    if (j >= 3) h += cf[2] * a2v[ti][tj][v];
+                    if (j >= 4) h += cf[3] * a3v[ti][tj][v];
+                    xv[ti][tj][v] = h;
+                });
+                if (q > 0) {
+                    __syncthreads();
+                    for_owned([&](int ti, int tj, int v, int r, int c) { P[r * LPA + c] = xv[ti][tj][v]; });
+                }
+            }
+        }
+    } else {
     // ---- scale: A = W / 2^s, A2 = W2 / 4^s (exact).  P holds W2 and becomes A2. ------------------------
     if (s > 0) {
         const T sg = (T)pow2neg_f(s), sg2 = (T)pow2neg_f(2 * s);
@@ -233,8 +327,6 @@ __global__ __launch_bounds__(NT == 1 ? 64 : 256) void fused_expm_kernel(const T 
         });
     }
 
-    // The polynomial X ends in registers xv (aliasing acc's storage is left to the compiler).
-    T xv[TH][TH][4];
     if (m <= 2) {
         for_owned([&](int ti, int tj, int v, int r, int c) {
             T x = dg(r, c);
@@ -292,6 +384,8 @@ __global__ __launch_bounds__(NT == 1 ? 64 : 256) void fused_expm_kernel(const T 
         }
     }
 
+    }
+
     // ---- squaring phase: X in both operand layouts, product, repeat ------------------------------------
     for (int q = 0; q < s; ++q) {
         __syncthreads();
@@ -325,19 +419,19 @@ __global__ __launch_bounds__(NT == 1 ? 64 : 256) void fused_expm_kernel(const T 
     }
 }
 
-template <typename T, int NT>
+template <typename T, int NT, int SCHEME>
 hipError_t launch_fused_t(const void *A, void *out, int n, int batch, double eps, int select_only, MatInfo *info,
                           hipStream_t stream)
 {
     using C = FusedCfg<T, NT>;
     static bool attr_done = false;
     if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(fused_expm_kernel<T, NT>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(fused_expm_kernel<T, NT, SCHEME>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, C::kLds);
         if (e != hipSuccess) return e;
         attr_done = true;
     }
-    hipLaunchKernelGGL((fused_expm_kernel<T, NT>), dim3(batch), dim3(C::kThreads), C::kLds, stream,
+    hipLaunchKernelGGL((fused_expm_kernel<T, NT, SCHEME>), dim3(batch), dim3(C::kThreads), C::kLds, stream,
                        reinterpret_cast<const T *>(A), reinterpret_cast<T *>(out), n, eps, select_only, info);
     return hipGetLastError();
 }
@@ -350,11 +444,14 @@ bool small_path_supported(int n, int dtype)
 }
 
 hipError_t launch_small(const void *A, void *out, int n, int batch, int dtype, double eps, int select_only,
-                        MatInfo *info, hipStream_t stream)
+                        int scheme, MatInfo *info, hipStream_t stream)
 {
     const int nt = (n + 15) / 16;
-#define EXPM_FUSED_CASE(TYPE, K) \
-    case K: return launch_fused_t<TYPE, K>(A, out, n, batch, eps, select_only, info, stream);
+#define EXPM_FUSED_CASE(TYPE, K)                                                                              \
+    case K:                                                                                                   \
+        return scheme == kSchemePS                                                                            \
+                   ? launch_fused_t<TYPE, K, kSchemePS>(A, out, n, batch, eps, select_only, info, stream)     \
+                   : launch_fused_t<TYPE, K, kSchemeSastre>(A, out, n, batch, eps, select_only, info, stream);
     if (dtype == 1) {
         switch (nt) {
             EXPM_FUSED_CASE(double, 1) EXPM_FUSED_CASE(double, 2) EXPM_FUSED_CASE(double, 3)

@@ -49,8 +49,9 @@ struct GemmParams {
     double *colpart;
     int n;
     int tiles;   // tiles per dimension
-    int round;   // 0 = square round (W2 = W*W), >= 1 chain round
+    int round;   // <= 0 power round (0: W2 = W*W, -1: W3 = W2*W, -2: W4 = W3*W), >= 1 chain round
     int total;   // workgroups in the grid
+    int scheme;  // kSchemeSastre or kSchemePS
 };
 
 __device__ __forceinline__ double pow2neg(int e)
@@ -120,14 +121,17 @@ __global__ __launch_bounds__(kThreads, WT == 4 ? 2 : 4) void gemm_round_kernel(G
     const int tile = wid - slot * tiles2;
     int b;
     Step<T> st;
-    if (p.round == 0) {
+    if (p.round <= 0) {
         b = slot;
-        st.L = BUF_W; st.R = BUF_W; st.acc_scale = (T)1; st.nsrc = 0; st.nout = 1; st.dst[0] = BUF_W2;
+        st.L = p.round == 0 ? BUF_W : (p.round == -1 ? BUF_W2 : BUF_W3);
+        st.R = BUF_W;
+        st.acc_scale = (T)1; st.nsrc = 0; st.nout = 1;
+        st.dst[0] = p.round == 0 ? BUF_W2 : (p.round == -1 ? BUF_W3 : BUF_W4);
     } else {
         b = p.order[slot];
         const MatInfo mi = p.info[b];
         if (p.round > mi.len) return;
-        st = build_step<T>(mi.m, mi.s, p.round);
+        st = p.scheme == kSchemePS ? build_step_ps<T>(mi.m, mi.s, p.round) : build_step<T>(mi.m, mi.s, p.round);
     }
     // grouped tile order: 8 tile-rows at a time, column by column
     int tm, tn;
@@ -295,8 +299,8 @@ __global__ __launch_bounds__(kThreads, WT == 4 ? 2 : 4) void gemm_round_kernel(G
             }
     }
 
-    if (p.round == 0) {
-        // column abs-sums of this tile of W2, in double: 16*WT rows per wave, then the two wave rows
+    if (p.round <= 0) {
+        // column abs-sums of this tile of the new power, in double: 16*WT rows per wave, then the two wave rows
         double *red = reinterpret_cast<double *>(smem);  // [2][BN]; the k-loop's last barrier has passed
 #pragma unroll
         for (int tj = 0; tj < WT; ++tj) {
@@ -373,8 +377,9 @@ __global__ __launch_bounds__(256) void colmax_kernel(const double *__restrict__ 
 // (longest chain first) and the summary:
 //   summary[0] = longest chain, summary[1] = OR of flags, summary[2 + r] = matrices active in round r.
 __global__ __launch_bounds__(1024) void select_plan_kernel(const double *__restrict__ p1, const double *__restrict__ p2,
+                                                           const double *__restrict__ p3, const double *__restrict__ p4,
                                                            int nblk, MatInfo *__restrict__ info, int *__restrict__ order,
-                                                           int *__restrict__ summary, int batch, double eps)
+                                                           int *__restrict__ summary, int batch, double eps, int scheme)
 {
     __shared__ int hist[kMaxRounds + 1];
     __shared__ int cursor[kMaxRounds + 1];
@@ -384,18 +389,27 @@ __global__ __launch_bounds__(1024) void select_plan_kernel(const double *__restr
     if (tid == 0) flags_or = 0;
     __syncthreads();
     for (int b = tid; b < batch; b += blockDim.x) {
-        double n1 = 0.0, n2 = 0.0;
+        double nrm[4] = {0.0, 0.0, 0.0, 0.0};
         bool bad = false;
-        for (int k = 0; k < nblk; ++k) {
-            const double x = p1[(size_t)b * nblk + k], y = p2[(size_t)b * nblk + k];
-            if (!(x == x) || !(y == y)) bad = true;
-            n1 = x > n1 ? x : n1;
-            n2 = y > n2 ? y : n2;
+        const int used = scheme == kSchemePS ? 4 : 2;
+        for (int q = 0; q < used; ++q) {
+            const double *pq = q == 0 ? p1 : (q == 1 ? p2 : (q == 2 ? p3 : p4));
+            for (int k = 0; k < nblk; ++k) {
+                const double x = pq[(size_t)b * nblk + k];
+                if (!(x == x)) bad = true;
+                nrm[q] = x > nrm[q] ? x : nrm[q];
+            }
         }
-        if (bad) n1 = __longlong_as_double(0x7ff8000000000000LL);
+        if (bad) nrm[0] = __longlong_as_double(0x7ff8000000000000LL);
         MatInfo mi;
-        select_order_scaling(n1, n2, eps, mi.m, mi.s, mi.flags);
-        mi.len = chain_length(mi.m, mi.s);
+        if (scheme == kSchemePS) {
+            bool need_more;
+            select_ps_order_scaling(nrm, 4, eps, mi.m, mi.s, mi.flags, need_more);
+            mi.len = chain_length_ps(mi.m, mi.s);
+        } else {
+            select_order_scaling(nrm[0], nrm[1], eps, mi.m, mi.s, mi.flags);
+            mi.len = chain_length(mi.m, mi.s);
+        }
         info[b] = mi;
         atomicAdd(&hist[mi.len], 1);
         if (mi.flags) atomicOr(&flags_or, mi.flags);
@@ -436,6 +450,25 @@ __global__ __launch_bounds__(256) void prepare_kernel(GemmParams p)
     T *T0 = reinterpret_cast<T *>(p.base[BUF_T0]) + moff;
     T *T1 = reinterpret_cast<T *>(p.base[BUF_T1]) + moff;
     const double sg = mi.s > 0 ? pow2neg(mi.s) : 1.0, sg2 = mi.s > 0 ? pow2neg(2 * mi.s) : 1.0;
+    if (p.scheme == kSchemePS && mi.m >= 4) {
+        // top block of the Paterson-Stockmeyer form: H0 = sum_{r=0..j} c_{(k-1)j+r} A^r  ->  T0
+        const T *W3 = reinterpret_cast<const T *>(p.base[BUF_W3]) + moff;
+        const T *W4 = reinterpret_cast<const T *>(p.base[BUF_W4]) + moff;
+        const int j = ps_j(mi.m), base = (ps_k(mi.m) - 1) * j;
+        const T h0 = (T)inv_factorial(base), h1 = (T)(inv_factorial(base + 1) * sg),
+                h2 = (T)(inv_factorial(base + 2) * sg2), h3 = j >= 3 ? (T)(inv_factorial(base + 3) * sg2 * sg) : (T)0,
+                h4 = j >= 4 ? (T)(inv_factorial(base + 4) * sg2 * sg2) : (T)0;
+        for (int e = 0; e < 4; ++e) {
+            const size_t idx = ((size_t)blockIdx.x * 4 + e) * 256 + threadIdx.x;
+            if (idx >= nn) break;
+            const int row = (int)(idx / n), col = (int)(idx - (size_t)row * n);
+            T h = h1 * W[idx] + h2 * W2[idx] + (row == col ? h0 : (T)0);
+            if (j >= 3) h += h3 * W3[idx];
+            if (j >= 4) h += h4 * W4[idx];
+            T0[idx] = h;
+        }
+        return;
+    }
     const T c1_8 = (T)EXPM_T8_C1, c2_8 = (T)EXPM_T8_C2;
     const T c1_15 = (T)(EXPM_T15_C1 * sg2), c2_15 = (T)(EXPM_T15_C2 * sg);
     for (int e = 0; e < 4; ++e) {
@@ -478,9 +511,10 @@ hipError_t launch_gemm_t(const GemmParams &p, hipStream_t stream)
     return hipGetLastError();
 }
 
-GemmParams make_params(const GeneralBuffers &gb, int n, int round, int matrices, int wt)
+GemmParams make_params(const GeneralBuffers &gb, int n, int round, int matrices, int wt, int scheme)
 {
     GemmParams p;
+    p.scheme = scheme;
     for (int i = 0; i < BUF_COUNT; ++i) p.base[i] = gb.base[i];
     p.info = gb.info;
     p.order = gb.order;
@@ -555,26 +589,27 @@ hipError_t launch_colabs(const GeneralBuffers &gb, int n, int batch, int dtype, 
 hipError_t launch_colmax(const GeneralBuffers &gb, int n, int batch, int which, int chunks, hipStream_t stream)
 {
     const int nblk = general_colblocks(n);
-    hipLaunchKernelGGL(colmax_kernel, dim3(nblk, batch), dim3(256), 0, stream, gb.colpart, which == 1 ? gb.n1 : gb.n2, n,
-                       chunks, nblk);
+    double *dst = which == 1 ? gb.n1 : (which == 2 ? gb.n2 : (which == 3 ? gb.n3 : gb.n4));
+    hipLaunchKernelGGL(colmax_kernel, dim3(nblk, batch), dim3(256), 0, stream, gb.colpart, dst, n, chunks, nblk);
     return hipGetLastError();
 }
 
-hipError_t launch_square_round(const GeneralBuffers &gb, int n, int batch, int dtype, int wt, hipStream_t stream)
+// power round `which` = 2, 3, 4: W^which = W^(which-1) * W with the column abs-sums of the result
+hipError_t launch_power_round(const GeneralBuffers &gb, int n, int batch, int dtype, int wt, int which, hipStream_t stream)
 {
-    return launch_gemm(make_params(gb, n, 0, batch, wt), dtype, wt, gb.ptr_align16, stream);
+    return launch_gemm(make_params(gb, n, 2 - which, batch, wt, kSchemeSastre), dtype, wt, gb.ptr_align16, stream);
 }
 
-hipError_t launch_select_plan(const GeneralBuffers &gb, int n, int batch, double eps, hipStream_t stream)
+hipError_t launch_select_plan(const GeneralBuffers &gb, int n, int batch, double eps, int scheme, hipStream_t stream)
 {
-    hipLaunchKernelGGL(select_plan_kernel, dim3(1), dim3(1024), 0, stream, gb.n1, gb.n2, general_colblocks(n), gb.info,
-                       gb.order, gb.summary, batch, eps);
+    hipLaunchKernelGGL(select_plan_kernel, dim3(1), dim3(1024), 0, stream, gb.n1, gb.n2, gb.n3, gb.n4,
+                       general_colblocks(n), gb.info, gb.order, gb.summary, batch, eps, scheme);
     return hipGetLastError();
 }
 
-hipError_t launch_prepare(const GeneralBuffers &gb, int n, int batch, int dtype, hipStream_t stream)
+hipError_t launch_prepare(const GeneralBuffers &gb, int n, int batch, int dtype, int scheme, hipStream_t stream)
 {
-    const GemmParams p = make_params(gb, n, 0, batch, 4);
+    const GemmParams p = make_params(gb, n, 0, batch, 4, scheme);
     const size_t nn = (size_t)n * n;
     dim3 grid((unsigned)((nn + 1023) / 1024), batch);
     if (dtype == 1)
@@ -584,9 +619,10 @@ hipError_t launch_prepare(const GeneralBuffers &gb, int n, int batch, int dtype,
     return hipGetLastError();
 }
 
-hipError_t launch_chain_round(const GeneralBuffers &gb, int n, int active, int round, int dtype, int wt, hipStream_t stream)
+hipError_t launch_chain_round(const GeneralBuffers &gb, int n, int active, int round, int dtype, int wt, int scheme,
+                              hipStream_t stream)
 {
-    return launch_gemm(make_params(gb, n, round, active, wt), dtype, wt, gb.ptr_align16, stream);
+    return launch_gemm(make_params(gb, n, round, active, wt, scheme), dtype, wt, gb.ptr_align16, stream);
 }
 
 }  // namespace expmk

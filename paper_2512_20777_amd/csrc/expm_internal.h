@@ -121,6 +121,83 @@ __host__ __device__ inline int chain_length(int m, int s)
 }
 
 // ---------------------------------------------------------------------------------------------
+// Paterson-Stockmeyer variant (Algorithm 3, Sec. 3.3): orders M = [1,2,4,6,9,12,16], powers W^j with
+// j = ceil(sqrt(m)), k = m/j; bounds of the table after Algorithm 3:
+//   m = 1: E1 = n1^2/2!, E2 = n1^3/3! ;  m = j*k > 1: E1 = nj^k n1/(m+1)!, E2 = nj^k n2/(m+2)!.
+// nrm[r-1] = ||W^r||_1 for r = 1..avail.  Orders that need a power above `avail` are not looked at:
+// if none of the orders that can be judged is accepted, need_more is set and (m, s) are not final.
+// ---------------------------------------------------------------------------------------------
+__host__ __device__ inline int ps_j(int m) { return m <= 1 ? 1 : (m <= 4 ? 2 : (m <= 9 ? 3 : 4)); }
+__host__ __device__ inline int ps_k(int m) { return m <= 0 ? 1 : m / ps_j(m); }
+
+__host__ __device__ inline void select_ps_order_scaling(const double nrm[4], int avail, double eps, int &m, int &s,
+                                                        int &flags, bool &need_more)
+{
+    flags = 0;
+    need_more = false;
+    for (int r = 0; r < avail; ++r)
+        if (!(nrm[r] <= 1.7976931348623157e308)) {  // NaN or Inf
+            m = -1; s = -1; flags = 1;
+            return;
+        }
+    m = 0; s = 0;
+    const double n1 = nrm[0];
+    if (n1 == 0.0) return;
+    // 1/(m+1)! and 1/(m+2)! for m = 1,2,4,6,9,12,16
+    const double c1[7] = {1.0 / 2.0, 1.0 / 6.0, 1.0 / 120.0, 1.0 / 5040.0, 1.0 / 3628800.0, 1.0 / 6227020800.0,
+                          1.0 / 355687428096000.0};
+    const double c2[7] = {1.0 / 6.0, 1.0 / 24.0, 1.0 / 720.0, 1.0 / 40320.0, 1.0 / 39916800.0, 1.0 / 87178291200.0,
+                          1.0 / 6402373705728000.0};
+    const int M[7] = {1, 2, 4, 6, 9, 12, 16};
+    double e1 = 0.0, e2 = 0.0;
+    for (int i = 0; i < 7; ++i) {
+        m = M[i];
+        const int j = ps_j(m), k = m / j;
+        if (j > avail) { need_more = true; return; }
+        if (m == 1) {
+            e1 = c1[0] * n1 * n1;
+            e2 = c2[0] * n1 * n1 * n1;
+        } else {
+            double pk = 1.0;
+            for (int q = 0; q < k; ++q) pk *= nrm[j - 1];
+            e1 = c1[i] * pk * n1;
+            e2 = c2[i] * pk * nrm[1];
+        }
+        if (e1 + e2 <= eps) return;
+    }
+    const double ee[2] = {e1, e2};
+    for (int i = 0; i < 2; ++i) {
+        int s1;
+        const double e = ee[i];
+        if (!(e <= 1.7976931348623157e308)) {
+            s1 = kSCap;
+        } else if (e <= 0.0) {
+            s1 = 0;
+        } else {
+            const double q = ceil(log2(e / eps) / (double)(17 + i));
+            s1 = q > (double)kSCap ? kSCap : (q < 0.0 ? 0 : (int)q);
+        }
+        if (s1 > s) s = s1;
+    }
+    if (s >= kSCap) { s = kSCap; flags |= 2; }
+}
+
+// Products after the powers: k-1 Horner steps, plus one per squaring.
+__host__ __device__ inline int chain_length_ps(int m, int s)
+{
+    if (m < 4) return 0;
+    return ps_k(m) - 1 + s;
+}
+
+// 1/i!, i = 0..16 (i! is exact in double up to 18!, so this is the correctly rounded reciprocal)
+__host__ __device__ inline double inv_factorial(int i)
+{
+    double f = 1.0;
+    for (int q = 2; q <= i; ++q) f *= (double)q;
+    return 1.0 / f;
+}
+
+// ---------------------------------------------------------------------------------------------
 // MFMA wrappers.  Both dtypes use the 16x16x4 shape.  Operand layouts coincide:
 //   A operand: lane l holds A[i = l%16][k = l/16]
 //   B operand: lane l holds B[k = l/16][j = l%16]
@@ -153,8 +230,12 @@ template <> struct Mfma<float> {
 // ---------------------------------------------------------------------------------------------
 // Buffers of the round-based (larger n) path, one [batch][n][n] array each.
 // ---------------------------------------------------------------------------------------------
+constexpr int kSchemeSastre = 0;  // evaluation formulas of Sec. 3.1 with Algorithm 4
+constexpr int kSchemePS = 1;      // Paterson-Stockmeyer with Algorithm 3
+
 enum Buf : int { BUF_W = 0, BUF_W2 = 1, BUF_T0 = 2, BUF_T1 = 3, BUF_T2 = 4, BUF_T3 = 5, BUF_T4 = 6, BUF_T5 = 7,
-                 BUF_OUT = 8, BUF_COUNT = 9 };
+                 BUF_OUT = 8, BUF_COUNT = 9,
+                 BUF_W3 = BUF_T3, BUF_W4 = BUF_T4 };  // the Paterson-Stockmeyer variant keeps W^3, W^4 there
 
 // One product round for one matrix:
 //   t      = acc_scale * (L*R) + sum_i g[i] * S_i
@@ -240,13 +321,56 @@ __device__ __forceinline__ Step<T> build_step(int m, int s, int r)
     return st;
 }
 
+// Round r (1-based, after the power products) of the Paterson-Stockmeyer chain for order m = j*k and
+// scaling s.  Horner in A^j:  H <- H * A^j + sum_{r'<j} c_{qj+r'} A^r',  q = k-2 .. 0, with the top block
+// prepared beforehand in T0; intermediate H ping-pongs between T0 and T2; then the squarings.
+template <typename T>
+__device__ __forceinline__ Step<T> build_step_ps(int m, int s, int r)
+{
+    Step<T> st;
+    st.L = BUF_T0; st.R = BUF_W2; st.acc_scale = (T)1; st.nsrc = 0; st.nout = 1;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        st.src[i] = BUF_W; st.g[i] = (T)0; st.dst[i] = BUF_OUT; st.a[i] = (T)1; st.d[i] = (T)0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) st.b[i][j] = (T)0;
+    }
+    const int j = ps_j(m), k = ps_k(m);
+    const int horner = k - 1;
+    const int poly_dst = (s & 1) ? BUF_T1 : BUF_OUT;
+    if (r <= horner) {
+        const int q = k - 1 - r;  // block whose coefficients are added in this step
+        const double sg = __longlong_as_double((long long)(1023 - s) << 52);
+        st.L = (r & 1) ? BUF_T0 : BUF_T2;
+        st.R = j == 2 ? BUF_W2 : (j == 3 ? BUF_W3 : BUF_W4);
+        double sgj = 1.0;
+        for (int e = 0; e < j; ++e) sgj *= sg;
+        st.acc_scale = (T)sgj;                       // H * A^j = sigma^j (H * W^j)
+        st.nsrc = j - 1;                             // A, A^2, A^3 as far as the block reaches
+        st.src[0] = BUF_W; st.src[1] = BUF_W2; st.src[2] = BUF_W3;
+        st.g[0] = (T)(inv_factorial(q * j + 1) * sg);
+        if (j >= 3) st.g[1] = (T)(inv_factorial(q * j + 2) * sg * sg);
+        if (j >= 4) st.g[2] = (T)(inv_factorial(q * j + 3) * sg * sg * sg);
+        st.nout = 1;
+        st.dst[0] = r == horner ? poly_dst : ((r & 1) ? BUF_T2 : BUF_T0);
+        st.a[0] = (T)1;
+        st.d[0] = (T)inv_factorial(q * j);
+    } else {
+        const int q = r - horner;  // squaring q of s
+        const bool cur_is_out = (((s - (q - 1)) & 1) == 0);
+        st.L = st.R = cur_is_out ? BUF_OUT : BUF_T1;
+        st.nsrc = 0; st.nout = 1; st.dst[0] = cur_is_out ? BUF_T1 : BUF_OUT;
+    }
+    return st;
+}
+
 // ---------------------------------------------------------------------------------------------
 // Host-side launchers implemented by the kernel translation units.
 // ---------------------------------------------------------------------------------------------
 struct GeneralBuffers {
     void *base[BUF_COUNT];   // device pointers, [batch][n][n] each (BUF_W = input, BUF_OUT = output)
     double *colpart;         // [batch][chunks][n] column abs-sum partials (chunks: see the launchers)
-    double *n1, *n2;         // [batch][colblocks] per-column-block maxima of the column sums of W, W2
+    double *n1, *n2, *n3, *n4;  // [batch][colblocks] per-column-block maxima of the column sums of W .. W^4
     MatInfo *info;           // [batch]
     int *order;              // [batch] matrices sorted by chain length, longest first
     int *summary;            // [64] : [0] longest chain, [1] OR of flags, [2+r] matrices active in round r
@@ -256,7 +380,7 @@ struct GeneralBuffers {
 // small fused path
 bool small_path_supported(int n, int dtype);
 hipError_t launch_small(const void *A, void *out, int n, int batch, int dtype, double eps, int select_only,
-                        MatInfo *info, hipStream_t stream);
+                        int scheme, MatInfo *info, hipStream_t stream);
 
 // larger-n path
 int general_colchunks(int n);   // row chunks of the column abs-sum pass over the input
@@ -264,10 +388,11 @@ int general_colblocks(int n);   // 256-column blocks: per-block maxima make up n
 int choose_tile_shape(int n, int matrices);  // 4 -> 128x128 tiles, 2 -> 64x64 tiles
 hipError_t launch_colabs(const GeneralBuffers &gb, int n, int batch, int dtype, hipStream_t stream);
 hipError_t launch_colmax(const GeneralBuffers &gb, int n, int batch, int which, int chunks, hipStream_t stream);
-hipError_t launch_square_round(const GeneralBuffers &gb, int n, int batch, int dtype, int wt, hipStream_t stream);
-hipError_t launch_select_plan(const GeneralBuffers &gb, int n, int batch, double eps, hipStream_t stream);
-hipError_t launch_prepare(const GeneralBuffers &gb, int n, int batch, int dtype, hipStream_t stream);
-hipError_t launch_chain_round(const GeneralBuffers &gb, int n, int active, int round, int dtype, int wt,
+hipError_t launch_power_round(const GeneralBuffers &gb, int n, int batch, int dtype, int wt, int which,
+                              hipStream_t stream);
+hipError_t launch_select_plan(const GeneralBuffers &gb, int n, int batch, double eps, int scheme, hipStream_t stream);
+hipError_t launch_prepare(const GeneralBuffers &gb, int n, int batch, int dtype, int scheme, hipStream_t stream);
+hipError_t launch_chain_round(const GeneralBuffers &gb, int n, int active, int round, int dtype, int wt, int scheme,
                               hipStream_t stream);
 
 }  // namespace expmk

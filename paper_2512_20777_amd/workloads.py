@@ -143,11 +143,13 @@ def random_stack(seed: int, batch: int, n: int, dtype, norm_lo: float, norm_hi: 
     return np.ascontiguousarray(a.astype(dtype))
 
 
-def products_for(m: np.ndarray, s: np.ndarray) -> np.ndarray:
+def products_for(m: np.ndarray, s: np.ndarray, scheme: str = "sastre") -> np.ndarray:
     """Matrix products the method spends on a matrix with order m and scaling s.
 
     Cost of the evaluation formulas (Sec. 3.1): 0 for m in {0,1}, 1 for m=2, 2 for m=4,
     3 for m=8, 4 for 15+; each squaring adds one.  Pure bookkeeping for FLOP accounting.
     """
     table = {0: 0, 1: 0, 2: 1, 4: 2, 8: 3, 15: 4}
+    if scheme == "ps":  # Paterson-Stockmeyer (Table 1 of the paper): order 6 at 3, 9 at 4, 12 at 5, 16 at 6 products
+        table = {0: 0, 1: 0, 2: 1, 4: 2, 6: 3, 9: 4, 12: 5, 16: 6}
     return np.array([table[int(x)] for x in np.asarray(m)], dtype=np.int64) + np.asarray(s, dtype=np.int64)
