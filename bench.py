@@ -17,8 +17,8 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 PEAK = {"hbm": 8000.0, "mfma_f32": 157.3, "mfma_f64": 78.6}  # GB/s, TFLOP/s (MI355X published)
-DEFAULT_STEPS = {"C1": 200, "C2": 200, "C3": 50, "C4": 20, "C5f64": 4, "C5f32": 6}
-DEFAULT_WARMUP = {"C1": 20, "C2": 20, "C3": 10, "C4": 4, "C5f64": 2, "C5f32": 2}
+DEFAULT_STEPS = {"F1": 200, "C1": 200, "C2": 200, "C3": 50, "C4": 20, "C5f64": 4, "C5f32": 6}
+DEFAULT_WARMUP = {"F1": 20, "C1": 20, "C2": 20, "C3": 10, "C4": 4, "C5f64": 2, "C5f32": 2}
 
 
 def source_sha1():
@@ -47,27 +47,27 @@ def recorded_traffic(workload, kernel_prefix):
     return val if sha == source_sha1() else None
 
 
-def time_steps(ex, torch, d, out, tol, steps, warmup):
+def time_steps(ex, torch, d, out, tol, steps, warmup, norm=0):
     for _ in range(warmup):
-        ex.expm(d, tol, out=out)
+        ex.expm(d, tol, out=out, norm=norm)
     torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t0 = time.perf_counter()
     e0.record()
     for _ in range(steps):
-        ex.expm(d, tol, out=out)
+        ex.expm(d, tol, out=out, norm=norm)
     e1.record()
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3
     return wall_ms / steps, e0.elapsed_time(e1) / steps
 
 
-def kernel_profile(ex, torch, d, out, tol, steps):
+def kernel_profile(ex, torch, d, out, tol, steps, norm=0):
     """Per-kernel-class time from HIP events recorded around every launch on the launch stream."""
     ex.expm_profile_reset()
     ex.expm_profile_enable(True)
     for _ in range(steps):
-        ex.expm(d, tol, out=out)
+        ex.expm(d, tol, out=out, norm=norm)
     torch.cuda.synchronize()
     prof = ex.expm_profile_read()
     ex.expm_profile_enable(False)
@@ -99,7 +99,10 @@ def cpu_baseline(name, a, tol, workloads):
         return {"value": w.batch / sec, "unit": "matrices/s", "cores": int(g["oracle_threads"][0]), "kind": "oracle",
                 "sample": "whole batch, %.0f s, recorded when tests/golden/make_c5_samples.py wrote the stored "
                           "samples (not re-timed in this run)" % sec}
-    reps = {"C1": 200, "C2": 50, "C3": 5, "C4": 1}[name]
+    reps = {"F1": 50, "C1": 200, "C2": 50, "C3": 5, "C4": 1}[name]
+    if w.norm == "inf":  # infinity-norm selection of W = 1-norm selection of its transpose (same work for the oracle)
+        import numpy as np
+        a = np.ascontiguousarray(np.swapaxes(a, -1, -2))
     oracle_expm_batch(a[: max(1, min(4, a.shape[0]))], tol)  # load the library, warm caches
     t0 = time.perf_counter()
     used = 0
@@ -122,18 +125,20 @@ def run_workload(name, steps, warmup, with_cpu, time_sel=False, compare_ps=False
     d = torch.from_numpy(a).cuda()
     out = torch.empty_like(d)
     ex.expm_reserve(w.n, w.batch, ex.DTYPE_F64 if w.dtype == "f64" else ex.DTYPE_F32)
-    ex.expm(d, w.tol, out=out)
+    norm = ex.NORM_INF if w.norm == "inf" else ex.NORM_ONE
+    ex.expm(d, w.tol, out=out, norm=norm)
     torch.cuda.synchronize()
     stats = ex.expm_get_stats()
-    wall_ms, ev_ms = time_steps(ex, torch, d, out, w.tol, steps, warmup)
-    prof = kernel_profile(ex, torch, d, out, w.tol, max(2, min(steps, 20)))
+    wall_ms, ev_ms = time_steps(ex, torch, d, out, w.tol, steps, warmup, norm)
+    prof = kernel_profile(ex, torch, d, out, w.tol, max(2, min(steps, 20)), norm)
     sel_ms = time_select(ex, torch, d, w.tol, max(2, min(steps, 20))) if time_sel else None
 
     wbytes = 8 if w.dtype == "f64" else 4
     flops = 2.0 * w.n ** 3 * stats["products"]          # products the selection asked for, W^2 counted once
     algo_bytes = 2.0 * w.batch * w.n * w.n * wbytes      # read W, write e^W
     res = {
-        "workload": name, "n": w.n, "batch": w.batch, "dtype": w.dtype, "steps": steps, "warmup": warmup,
+        "workload": name, "n": w.n, "batch": w.batch, "dtype": w.dtype, "tol": w.tol, "norm": w.norm,
+        "steps": steps, "warmup": warmup,
         "ms_per_step": wall_ms, "ms_per_step_events": ev_ms,
         "matrices_per_s": w.batch / (wall_ms * 1e-3),
         "tflops": flops / (wall_ms * 1e-3) / 1e12,
@@ -172,12 +177,12 @@ def run_workload(name, steps, warmup, with_cpu, time_sel=False, compare_ps=False
         # the paper's own comparison (Sec. 4): same tolerance, Paterson-Stockmeyer evaluation + Algorithm 3
         ps_steps = max(2, steps // 4)
         for _ in range(2):
-            ex.expm(d, w.tol, out=out, scheme=ex.SCHEME_PS)
+            ex.expm(d, w.tol, out=out, scheme=ex.SCHEME_PS, norm=norm)
         torch.cuda.synchronize()
         ps_stats = ex.expm_get_stats()
         t0 = time.perf_counter()
         for _ in range(ps_steps):
-            ex.expm(d, w.tol, out=out, scheme=ex.SCHEME_PS)
+            ex.expm(d, w.tol, out=out, scheme=ex.SCHEME_PS, norm=norm)
         torch.cuda.synchronize()
         ps_ms = (time.perf_counter() - t0) * 1e3 / ps_steps
         res["paterson_stockmeyer_variant"] = {
@@ -185,7 +190,7 @@ def run_workload(name, steps, warmup, with_cpu, time_sel=False, compare_ps=False
             "product_ratio_vs_main": ps_stats["products"] / max(1, stats["products"]),
             "time_ratio_vs_main": ps_ms / wall_ms,
             "hist_m": {str(k): v for k, v in ps_stats["hist_m"].items() if v}}
-        ex.expm(d, w.tol, out=out)  # leave the main scheme as the last call
+        ex.expm(d, w.tol, out=out, norm=norm)  # leave the main scheme as the last call
         torch.cuda.synchronize()
     if with_cpu:
         res["cpu_baseline"] = cpu_baseline(name, a, w.tol, workloads)
@@ -202,8 +207,9 @@ def pmc_pass(name, steps):
     w = workloads.WORKLOADS[name]
     d = torch.from_numpy(workloads.make_workload(name)).cuda()
     out = torch.empty_like(d)
+    norm = ex.NORM_INF if w.norm == "inf" else ex.NORM_ONE
     for _ in range(steps):
-        ex.expm(d, w.tol, out=out)
+        ex.expm(d, w.tol, out=out, norm=norm)
     torch.cuda.synchronize()
     src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device="cuda")   # 256 MiB
     dst = torch.empty_like(src)
@@ -250,7 +256,7 @@ def main():
     main_res = run_workload(head, steps, warmup, not args.no_cpu, args.time_select, args.compare_ps)
     per = [main_res]
     if not args.no_others:
-        for name in ("C1", "C2", "C3", "C4", "C5f64", "C5f32"):
+        for name in ("C1", "C2", "C3", "C4", "C5f64", "C5f32", "F1"):
             if name == head:
                 continue
             per.append(run_workload(name, DEFAULT_STEPS[name], DEFAULT_WARMUP[name], not args.no_cpu, args.time_select,
@@ -263,7 +269,7 @@ def main():
         "ms_per_step": main_res["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": main_res["dtype"], "data": "synthetic",
         "config": {"workload": "%s: %s" % (head, workloads.WORKLOADS[head].note), "n": main_res["n"],
-                   "batch": main_res["batch"], "tol": "unit roundoff of dtype"},
+                   "batch": main_res["batch"], "tol": main_res["tol"], "norm": main_res["norm"]},
         "tflops": main_res["tflops"],
         "roofline": {k: main_res["roofline"][k] for k in ("bound", "achieved", "peak", "unit", "frac", "traffic")},
         "cpu_baseline": main_res.get("cpu_baseline"),

@@ -107,6 +107,20 @@ int expm_select_scheme(const void *A, int n, int batch, int dtype, double tol, i
 int expm_scheme(const void *A, int n, int batch, int dtype, double tol, int scheme, void *out, void *stream);
 
 /*
+ * Same again with the norm of the selection as an argument.  The printed algorithms use the 1-norm
+ * (EXPM_NORM_ONE: largest column abs-sum, what every call above uses); the paper's PyTorch runs use the
+ * infinity-norm "for consistency with the baseline" (Sec. 4.2): EXPM_NORM_INF takes the largest row abs-sum
+ * of W and of its powers instead.  Only the selection changes; with EXPM_NORM_INF the result equals the
+ * transpose of what EXPM_NORM_ONE gives for the transposed batch.
+ */
+#define EXPM_NORM_ONE 0
+#define EXPM_NORM_INF 1
+int expm_select_ex(const void *A, int n, int batch, int dtype, double tol, int scheme, int norm_kind,
+                   int32_t *m_out, int32_t *s_out);
+int expm_ex(const void *A, int n, int batch, int dtype, double tol, int scheme, int norm_kind, void *out,
+            void *stream);
+
+/*
  * Bytes of device workspace the library holds for a call of this shape (the fused
  * small-matrix path needs only the per-matrix records).  The workspace is allocated
  * on first use, grown when a larger shape arrives, reused otherwise, and released by

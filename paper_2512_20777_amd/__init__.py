@@ -6,6 +6,8 @@ Importing it does not load the library; the first call does, and fails loudly if
 from .binding import (  # noqa: F401
     DTYPE_F32,
     DTYPE_F64,
+    NORM_INF,
+    NORM_ONE,
     SCHEME_PS,
     SCHEME_SASTRE,
     ExpmError,

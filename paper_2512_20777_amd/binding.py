@@ -18,6 +18,8 @@ DTYPE_F32 = 0
 DTYPE_F64 = 1
 SCHEME_SASTRE = 0   # Algorithm 4 + evaluation formulas of Sec. 3.1 (orders 1,2,4,8,15+)
 SCHEME_PS = 1       # Algorithm 3 + Paterson-Stockmeyer (orders 1,2,4,6,9,12,16)
+NORM_ONE = 0        # selection on 1-norms (the printed algorithms)
+NORM_INF = 1        # selection on infinity-norms (the paper's PyTorch runs, Sec. 4.2)
 
 EXPM_KCLASS = {"norm": 0, "select": 1, "gemm": 2, "fused": 3}
 
@@ -70,6 +72,10 @@ def load_library():
     lib.expm_select_scheme.argtypes = [vp, ci, ci, ci, cd, ci, i32p, i32p]
     lib.expm_scheme.restype = ci
     lib.expm_scheme.argtypes = [vp, ci, ci, ci, cd, ci, vp, vp]
+    lib.expm_select_ex.restype = ci
+    lib.expm_select_ex.argtypes = [vp, ci, ci, ci, cd, ci, ci, i32p, i32p]
+    lib.expm_ex.restype = ci
+    lib.expm_ex.argtypes = [vp, ci, ci, ci, cd, ci, ci, vp, vp]
     lib.expm_workspace_bytes.restype = ctypes.c_size_t
     lib.expm_workspace_bytes.argtypes = [ci, ci, ci]
     lib.expm_reserve.restype = ci
@@ -123,7 +129,7 @@ def _describe(A) -> Tuple[int, int, int]:
     return A.shape[1], A.shape[0], dt
 
 
-def expm_select(A, tol: float = 0.0, scheme: int = SCHEME_SASTRE):
+def expm_select(A, tol: float = 0.0, scheme: int = SCHEME_SASTRE, norm: int = NORM_ONE):
     """(m, s) per matrix as two int32 numpy arrays, plus the status (0 or a warning code)."""
     import numpy as np
     import torch
@@ -133,12 +139,12 @@ def expm_select(A, tol: float = 0.0, scheme: int = SCHEME_SASTRE):
     i32p = ctypes.POINTER(ctypes.c_int32)
     with torch.cuda.device(A.device):
         torch.cuda.current_stream().synchronize()  # the C entry point runs on the null stream
-        st = load_library().expm_select_scheme(A.data_ptr(), n, batch, dt, float(tol), int(scheme),
-                                               m.ctypes.data_as(i32p), s.ctypes.data_as(i32p))
+        st = load_library().expm_select_ex(A.data_ptr(), n, batch, dt, float(tol), int(scheme), int(norm),
+                                           m.ctypes.data_as(i32p), s.ctypes.data_as(i32p))
     return m, s, _check(st)
 
 
-def expm(A, tol: float = 0.0, out=None, stream=None, scheme: int = SCHEME_SASTRE):
+def expm(A, tol: float = 0.0, out=None, stream=None, scheme: int = SCHEME_SASTRE, norm: int = NORM_ONE):
     """e^A for a [batch][n][n] device tensor; returns (out, status).  Runs on torch's current stream.
 
     Marshalling only, kept short: for small batches the call rate is bounded by this function.
@@ -156,10 +162,10 @@ def expm(A, tol: float = 0.0, out=None, stream=None, scheme: int = SCHEME_SASTRE
     else:
         sp = torch.cuda.current_stream(dev).cuda_stream
     if dev == torch.cuda.current_device():
-        st = lib.expm_scheme(A.data_ptr(), n, batch, dt, tol, scheme, out.data_ptr(), sp)
+        st = lib.expm_ex(A.data_ptr(), n, batch, dt, tol, scheme, norm, out.data_ptr(), sp)
     else:
         with torch.cuda.device(dev):
-            st = lib.expm_scheme(A.data_ptr(), n, batch, dt, tol, scheme, out.data_ptr(), sp)
+            st = lib.expm_ex(A.data_ptr(), n, batch, dt, tol, scheme, norm, out.data_ptr(), sp)
     if st < 0:
         _check(st)
     return out, st

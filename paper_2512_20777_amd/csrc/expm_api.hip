@@ -190,9 +190,10 @@ struct Bound {
     Layout L;
 };
 
-Bound bind(const void *A, void *out, int n, int batch, int dtype)
+Bound bind(const void *A, void *out, int n, int batch, int dtype, int norm_kind)
 {
     Bound B;
+    B.gb.norm_inf = norm_kind == EXPM_NORM_INF ? 1 : 0;
     B.L = make_layout(n, batch, dtype);
     unsigned char *base = static_cast<unsigned char *>(g_ws.dev);
     B.gb.summary = reinterpret_cast<int *>(base + B.L.summary);
@@ -218,7 +219,7 @@ int run_selection_general(const Bound &B, int n, int batch, int dtype, double to
     {
         Bracket br(stream, EXPM_KCLASS_NORM, 0.0, batch * nn * w);
         EXPM_TRY(launch_colabs(B.gb, n, batch, dtype, stream));
-        EXPM_TRY(launch_colmax(B.gb, n, batch, 1, general_colchunks(n), stream));
+        EXPM_TRY(launch_colmax(B.gb, n, batch, 1, B.gb.norm_inf ? 1 : general_colchunks(n), stream));
     }
     const int wt0 = choose_tile_shape(n, batch);
     {
@@ -292,7 +293,14 @@ int expm_select(const void *A, int n, int batch, int dtype, double tol, int32_t 
 
 int expm_select_scheme(const void *A, int n, int batch, int dtype, double tol, int scheme, int32_t *m_out, int32_t *s_out)
 {
+    return expm_select_ex(A, n, batch, dtype, tol, scheme, EXPM_NORM_ONE, m_out, s_out);
+}
+
+int expm_select_ex(const void *A, int n, int batch, int dtype, double tol, int scheme, int norm_kind, int32_t *m_out,
+                   int32_t *s_out)
+{
     if (scheme != EXPM_SCHEME_SASTRE && scheme != EXPM_SCHEME_PS) return EXPM_ERR_INVALID_ARG;
+    if (norm_kind != EXPM_NORM_ONE && norm_kind != EXPM_NORM_INF) return EXPM_ERR_INVALID_ARG;
     int rc = check_args(A, n, batch, dtype, tol);
     if (rc != EXPM_OK) return rc;
     if (batch > 0 && (m_out == nullptr || s_out == nullptr)) return EXPM_ERR_INVALID_ARG;
@@ -304,10 +312,10 @@ int expm_select_scheme(const void *A, int n, int batch, int dtype, double tol, i
     rc = ensure_workspace(make_layout(n, batch, dtype).total, batch);
     if (rc != EXPM_OK) return rc;
     hipStream_t stream = nullptr;
-    const Bound B = bind(A, nullptr, n, batch, dtype);
+    const Bound B = bind(A, nullptr, n, batch, dtype, norm_kind);
     int flags = 0;
     if (small_path_supported(n, dtype)) {
-        EXPM_TRY(launch_small(A, nullptr, n, batch, dtype, tol, 1, scheme, B.gb.info, stream));
+        EXPM_TRY(launch_small(A, nullptr, n, batch, dtype, tol, 1, scheme, B.gb.norm_inf, B.gb.info, stream));
         remember(n, batch, dtype, 0, 1, scheme, stream, B);
     } else {
         rc = run_selection_general(B, n, batch, dtype, tol, scheme, stream);
@@ -332,7 +340,13 @@ int expm(const void *A, int n, int batch, int dtype, double tol, void *out, void
 
 int expm_scheme(const void *A, int n, int batch, int dtype, double tol, int scheme, void *out, void *stream_v)
 {
+    return expm_ex(A, n, batch, dtype, tol, scheme, EXPM_NORM_ONE, out, stream_v);
+}
+
+int expm_ex(const void *A, int n, int batch, int dtype, double tol, int scheme, int norm_kind, void *out, void *stream_v)
+{
     if (scheme != EXPM_SCHEME_SASTRE && scheme != EXPM_SCHEME_PS) return EXPM_ERR_INVALID_ARG;
+    if (norm_kind != EXPM_NORM_ONE && norm_kind != EXPM_NORM_INF) return EXPM_ERR_INVALID_ARG;
     int rc = check_args(A, n, batch, dtype, tol);
     if (rc != EXPM_OK) return rc;
     if (n == 0 || batch == 0) return EXPM_OK;
@@ -346,7 +360,7 @@ int expm_scheme(const void *A, int n, int batch, int dtype, double tol, int sche
     hipStream_t stream = static_cast<hipStream_t>(stream_v);
     rc = ensure_workspace(make_layout(n, batch, dtype).total, batch);
     if (rc != EXPM_OK) return rc;
-    const Bound B = bind(A, out, n, batch, dtype);
+    const Bound B = bind(A, out, n, batch, dtype, norm_kind);
     const double w = dtype == EXPM_DTYPE_F64 ? 8.0 : 4.0;
     const double nn = (double)n * n;
 
@@ -354,7 +368,7 @@ int expm_scheme(const void *A, int n, int batch, int dtype, double tol, int sche
         // one kernel, nothing read back: warnings of this path surface through expm_get_stats()
         {
             Bracket br(stream, EXPM_KCLASS_FUSED, 0.0, 2.0 * batch * nn * w);
-            EXPM_TRY(launch_small(A, out, n, batch, dtype, tol, 0, scheme, B.gb.info, stream));
+            EXPM_TRY(launch_small(A, out, n, batch, dtype, tol, 0, scheme, B.gb.norm_inf, B.gb.info, stream));
         }
         remember(n, batch, dtype, 0, 1, scheme, stream, B);
         return EXPM_OK;

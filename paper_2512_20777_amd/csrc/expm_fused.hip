@@ -45,7 +45,7 @@ __device__ __forceinline__ double pow2neg_f(int e)
 template <typename T, int NT, int SCHEME>
 __global__ __launch_bounds__(NT == 1 ? 64 : 256) void fused_expm_kernel(const T *__restrict__ Ain, T *__restrict__ Out,
                                                                         int n, double eps, int select_only,
-                                                                        MatInfo *__restrict__ info)
+                                                                        int norm_inf, MatInfo *__restrict__ info)
 {
     using C = FusedCfg<T, NT>;
     using acc_t = typename Mfma<T>::acc_t;
@@ -99,15 +99,16 @@ __global__ __launch_bounds__(NT == 1 ? 64 : 256) void fused_expm_kernel(const T 
     }
     __syncthreads();
 
-    // ---- 1-norm of the matrix in P: max column abs-sum, double accumulation, NaN if non-finite -------
-    // thread t sums rows t/NP, t/NP + G, ... of column t%NP (G row groups); groups are then added in order.
+    // ---- norm of the matrix in P: max column abs-sum (1-norm) or, with norm_inf, max row abs-sum -------
+    // double accumulation, NaN if non-finite.  Thread t sums entries t/NP, t/NP + G, ... of column (row)
+    // t%NP (G groups); the groups are then added in order.
     auto norm1_of_P = [&]() -> double {
         constexpr int G = C::kThreads / NP > 0 ? C::kThreads / NP : 1;
         const int col = tid % NP, grp = tid / NP;
         double s = 0.0;
         if (grp < G) {
 #pragma unroll 8
-            for (int r = grp; r < n; r += G) s += fabs((double)P[r * LPA + col]);
+            for (int r = grp; r < n; r += G) s += fabs((double)(norm_inf ? P[col * LPA + r] : P[r * LPA + col]));
         }
         __syncthreads();  // red[] free to overwrite
         red[tid] = s;
@@ -420,8 +421,8 @@ __global__ __launch_bounds__(NT == 1 ? 64 : 256) void fused_expm_kernel(const T 
 }
 
 template <typename T, int NT, int SCHEME>
-hipError_t launch_fused_t(const void *A, void *out, int n, int batch, double eps, int select_only, MatInfo *info,
-                          hipStream_t stream)
+hipError_t launch_fused_t(const void *A, void *out, int n, int batch, double eps, int select_only, int norm_inf,
+                          MatInfo *info, hipStream_t stream)
 {
     using C = FusedCfg<T, NT>;
     static bool attr_done = false;
@@ -432,7 +433,7 @@ hipError_t launch_fused_t(const void *A, void *out, int n, int batch, double eps
         attr_done = true;
     }
     hipLaunchKernelGGL((fused_expm_kernel<T, NT, SCHEME>), dim3(batch), dim3(C::kThreads), C::kLds, stream,
-                       reinterpret_cast<const T *>(A), reinterpret_cast<T *>(out), n, eps, select_only, info);
+                       reinterpret_cast<const T *>(A), reinterpret_cast<T *>(out), n, eps, select_only, norm_inf, info);
     return hipGetLastError();
 }
 
@@ -444,14 +445,16 @@ bool small_path_supported(int n, int dtype)
 }
 
 hipError_t launch_small(const void *A, void *out, int n, int batch, int dtype, double eps, int select_only,
-                        int scheme, MatInfo *info, hipStream_t stream)
+                        int scheme, int norm_inf, MatInfo *info, hipStream_t stream)
 {
     const int nt = (n + 15) / 16;
 #define EXPM_FUSED_CASE(TYPE, K)                                                                              \
     case K:                                                                                                   \
         return scheme == kSchemePS                                                                            \
-                   ? launch_fused_t<TYPE, K, kSchemePS>(A, out, n, batch, eps, select_only, info, stream)     \
-                   : launch_fused_t<TYPE, K, kSchemeSastre>(A, out, n, batch, eps, select_only, info, stream);
+                   ? launch_fused_t<TYPE, K, kSchemePS>(A, out, n, batch, eps, select_only, norm_inf, info,   \
+                                                        stream)                                              \
+                   : launch_fused_t<TYPE, K, kSchemeSastre>(A, out, n, batch, eps, select_only, norm_inf,     \
+                                                            info, stream);
     if (dtype == 1) {
         switch (nt) {
             EXPM_FUSED_CASE(double, 1) EXPM_FUSED_CASE(double, 2) EXPM_FUSED_CASE(double, 3)

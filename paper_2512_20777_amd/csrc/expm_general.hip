@@ -52,6 +52,7 @@ struct GemmParams {
     int round;   // <= 0 power round (0: W2 = W*W, -1: W3 = W2*W, -2: W4 = W3*W), >= 1 chain round
     int total;   // workgroups in the grid
     int scheme;  // kSchemeSastre or kSchemePS
+    int norm_inf;  // power rounds: emit row abs-sums (infinity-norm) instead of column abs-sums
 };
 
 __device__ __forceinline__ double pow2neg(int e)
@@ -299,7 +300,7 @@ __global__ __launch_bounds__(kThreads, WT == 4 ? 2 : 4) void gemm_round_kernel(G
             }
     }
 
-    if (p.round <= 0) {
+    if (p.round <= 0 && !p.norm_inf) {
         // column abs-sums of this tile of the new power, in double: 16*WT rows per wave, then the two wave rows
         double *red = reinterpret_cast<double *>(smem);  // [2][BN]; the k-loop's last barrier has passed
 #pragma unroll
@@ -318,6 +319,28 @@ __global__ __launch_bounds__(kThreads, WT == 4 ? 2 : 4) void gemm_round_kernel(G
             const int col = col0 + tid;
             if (col < n) p.colpart[((size_t)b * p.tiles + tm) * n + col] = red[tid] + red[BN + tid];
         }
+    } else if (p.round <= 0) {
+        // row abs-sums of this tile (infinity-norm): 16*WT columns per wave, then the two wave columns;
+        // partials are indexed by tile column: colpart[b][tn][row]
+        double *red = reinterpret_cast<double *>(smem);  // [2][BM]
+#pragma unroll
+        for (int ti = 0; ti < WT; ++ti)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                double rs = 0.0;
+#pragma unroll
+                for (int tj = 0; tj < WT; ++tj) rs += fabs((double)acc[ti][tj][v]);
+                rs += __shfl_xor(rs, 1);
+                rs += __shfl_xor(rs, 2);
+                rs += __shfl_xor(rs, 4);
+                rs += __shfl_xor(rs, 8);
+                if (lj == 0) red[wn * BM + wm * 16 * WT + 16 * ti + Mfma<T>::row(lg, v)] = rs;
+            }
+        __syncthreads();
+        if (tid < BM) {
+            const int row = row0 + tid;
+            if (row < n) p.colpart[((size_t)b * p.tiles + tn) * n + row] = red[tid] + red[BM + tid];
+        }
     }
 }
 
@@ -335,6 +358,21 @@ __global__ __launch_bounds__(256) void colabs_kernel(const T *__restrict__ W, do
 #pragma unroll 8
     for (int r = r0; r < r1; ++r) s += fabs((double)p[(size_t)r * n]);
     colpart[((size_t)b * chunks + chunk) * n + col] = s;
+}
+
+// Row abs-sums of W (infinity-norm): one wave per row, lanes stride over the columns, fixed-order wave
+// reduction; written as a single chunk colpart[b][0][row].
+template <typename T>
+__global__ __launch_bounds__(256) void rowabs_kernel(const T *__restrict__ W, double *__restrict__ colpart, int n)
+{
+    const int row = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63, b = blockIdx.y;
+    if (row >= n) return;
+    const T *p = W + ((size_t)b * n + row) * n;
+    double s = 0.0;
+#pragma unroll 4
+    for (int c = lane; c < n; c += 64) s += fabs((double)p[c]);
+    for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off);
+    if (lane == 0) colpart[(size_t)b * n + row] = s;
 }
 
 // pmax[b][blk] = max over the 256 columns of block blk of (sum over chunks of colpart[b][chunk][col]),
@@ -515,6 +553,7 @@ GemmParams make_params(const GeneralBuffers &gb, int n, int round, int matrices,
 {
     GemmParams p;
     p.scheme = scheme;
+    p.norm_inf = gb.norm_inf;
     for (int i = 0; i < BUF_COUNT; ++i) p.base[i] = gb.base[i];
     p.info = gb.info;
     p.order = gb.order;
@@ -575,6 +614,16 @@ int general_colblocks(int n) { return (n + 255) / 256; }
 
 hipError_t launch_colabs(const GeneralBuffers &gb, int n, int batch, int dtype, hipStream_t stream)
 {
+    if (gb.norm_inf) {
+        dim3 grid((n + 3) / 4, batch);
+        if (dtype == 1)
+            hipLaunchKernelGGL(rowabs_kernel<double>, grid, dim3(256), 0, stream,
+                               reinterpret_cast<const double *>(gb.base[BUF_W]), gb.colpart, n);
+        else
+            hipLaunchKernelGGL(rowabs_kernel<float>, grid, dim3(256), 0, stream,
+                               reinterpret_cast<const float *>(gb.base[BUF_W]), gb.colpart, n);
+        return hipGetLastError();
+    }
     const int chunks = general_colchunks(n);
     dim3 grid((n + 255) / 256, chunks, batch);
     if (dtype == 1)

@@ -375,12 +375,13 @@ struct GeneralBuffers {
     int *order;              // [batch] matrices sorted by chain length, longest first
     int *summary;            // [64] : [0] longest chain, [1] OR of flags, [2+r] matrices active in round r
     bool ptr_align16;        // input and output pointers are 16-byte aligned (vector loads allowed)
+    int norm_inf;            // 0: 1-norm (column sums), 1: infinity-norm (row sums) in the selection
 };
 
 // small fused path
 bool small_path_supported(int n, int dtype);
 hipError_t launch_small(const void *A, void *out, int n, int batch, int dtype, double eps, int select_only,
-                        int scheme, MatInfo *info, hipStream_t stream);
+                        int scheme, int norm_inf, MatInfo *info, hipStream_t stream);
 
 // larger-n path
 int general_colchunks(int n);   // row chunks of the column abs-sum pass over the input

@@ -29,6 +29,8 @@ class Workload:
     dtype: str  # "f32" | "f64"
     seed: int
     note: str
+    tolerance: float = 0.0   # 0: unit roundoff of the dtype
+    norm: str = "one"        # norm the selection uses: "one" | "inf"
 
     @property
     def np_dtype(self):
@@ -36,7 +38,9 @@ class Workload:
 
     @property
     def tol(self) -> float:
-        """Tolerance of the workload: the unit roundoff of its dtype."""
+        """Tolerance of the workload: the unit roundoff of its dtype unless it states one."""
+        if self.tolerance > 0.0:
+            return self.tolerance
         return 2.0 ** -24 if self.dtype == "f32" else 2.0 ** -53
 
 
@@ -55,6 +59,11 @@ WORKLOADS: Dict[str, Workload] = {
                       "4 x 4096x4096 fp64, iid N(0,1/4096), 1-norms 1, 10, 50, 200"),
     "C5f32": Workload("C5f32", 4096, 4, "f32", SEED_BASE + 5,
                       "4 x 4096x4096 fp32 (the fp64 draw rounded), 1-norms 1, 10, 50, 200"),
+    # The setting of the paper's own flow-model runs (Sec. 4.2): tolerance 1e-8, infinity-norm selection,
+    # norms between 1e-5 and 12.8, so that the low orders are exercised heavily.
+    "F1": Workload("F1", 16, 4096, "f64", SEED_BASE + 6,
+                   "4096 x 16x16 fp64 flow-layer generators, inf-norm log-uniform in [1e-5,12.8], tol 1e-8, "
+                   "inf-norm selection", tolerance=1e-8, norm="inf"),
 }
 
 
@@ -93,6 +102,14 @@ def make_workload(name: str, batch: int | None = None, n: int | None = None) -> 
         idx = np.arange(n)
         a[:, idx, idx] = d
         a = _rescale_to(a, _log_uniform(rng, 0.01, 10.0, b))
+    elif name == "F1":
+        g = rng.standard_normal((b, n, n))
+        up = np.triu(g, 1)
+        a = up - np.swapaxes(up, -1, -2)
+        idx = np.arange(n)
+        a[:, idx, idx] = rng.standard_normal((b, n)) * np.sqrt(0.1)
+        target = _log_uniform(rng, 1e-5, 12.8, b)
+        a = a * (target / np.abs(a).sum(axis=-1).max(axis=-1))[:, None, None]   # rescale the infinity-norm
     elif name == "C3":
         a = rng.standard_normal((b, n, n)) * np.sqrt(1.0 / n)
         a = a * _log_uniform(rng, 0.1, 50.0, b)[:, None, None]

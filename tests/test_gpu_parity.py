@@ -315,3 +315,81 @@ def test_inverse_and_determinant_identities_at_size(ex):
     sign, logdet = torch.linalg.slogdet(x)
     tr = torch.diagonal(d, dim1=-2, dim2=-1).sum(-1)
     assert bool((sign > 0).all()) and float((logdet - tr).abs().max()) < 1e-9
+
+
+# ------------------------------------------------------------------------------------------------
+# infinity-norm selection and the tolerance of the paper's own runs (Sec. 4.2: eps = 1e-8, inf-norm)
+# ------------------------------------------------------------------------------------------------
+def _run_inf_norm(ex, a, tol, label, scheme=0):
+    """Selection on infinity-norms of W equals selection on 1-norms of W^T, and e^(W^T) = (e^W)^T:
+    the oracle runs on the transposed stack and its result is transposed back."""
+    import torch
+    from oracle import oracle_expm_batch, oracle_expm_ps_batch
+    at = np.ascontiguousarray(np.swapaxes(a, -1, -2))
+    X, info = (oracle_expm_ps_batch if scheme else oracle_expm_batch)(at, tol)
+    X = np.swapaxes(X, -1, -2)
+    d = torch.from_numpy(a).cuda()
+    print("case %s shape %s %s" % (label, a.shape, a.dtype), flush=True)
+    out, _ = ex.expm(d, tol, scheme=scheme, norm=ex.NORM_INF)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy().astype(np.float64)
+    m, s, _ = ex.expm_select(d, tol, scheme=scheme, norm=ex.NORM_INF)
+    m1, s1, _ = ex.expm_select(d, tol, scheme=scheme, norm=ex.NORM_ONE)
+    worst = 0.0
+    for b in range(a.shape[0]):
+        if (m[b], s[b]) != (info["m"][b], info["s"][b]):
+            assert info["near"][b], (label, b, (m[b], s[b]), (info["m"][b], info["s"][b]))
+            continue
+        err = np.linalg.norm(got[b] - X[b]) / np.linalg.norm(X[b])
+        worst = max(worst, err)
+        assert err <= GATE[a.dtype], (label, b, err)
+    print("   worst rel Frobenius error %.3e; matrices whose choice differs between the two norms: %d"
+          % (worst, int(((m != m1) | (s != s1)).sum())), flush=True)
+    return m, s, m1, s1
+
+
+@pytest.mark.parametrize("n,batch,dtype", [(16, 64, np.float32), (48, 20, np.float64), (128, 8, np.float32),
+                                           (150, 6, np.float64), (260, 3, np.float32), (515, 2, np.float64)])
+def test_infinity_norm_selection(ex, n, batch, dtype):
+    from paper_2512_20777_amd import workloads
+    a = workloads.random_stack(900 + n, batch, n, dtype, 0.01, 60.0, kind="triu" if n % 2 == 0 else "dense")
+    _run_inf_norm(ex, a, _tol(a), "inf-norm n=%d" % n)
+
+
+@pytest.mark.parametrize("n", [24, 160])
+def test_infinity_norm_really_uses_row_sums(ex, n):
+    """One dense row: the 1-norm is the largest entry, the infinity-norm the sum of the row."""
+    import torch
+    from oracle import oracle_select
+    rng = np.random.default_rng(n)
+    a = np.zeros((2, n, n))
+    a[0, 3, :] = rng.uniform(0.5, 1.0, n) * 0.02      # row sums ~ 0.015 n, column sums <= 0.02
+    a[1, :, 5] = rng.uniform(0.5, 1.0, n) * 0.02      # the transpose situation
+    d = torch.from_numpy(a).cuda()
+    m1, s1, _ = ex.expm_select(d, U64, norm=ex.NORM_ONE)
+    mi, si, _ = ex.expm_select(d, U64, norm=ex.NORM_INF)
+    for b in range(2):
+        o1 = oracle_select(a[b], U64)
+        oi = oracle_select(a[b].T, U64)
+        assert (m1[b], s1[b]) == (o1["m"], o1["s"]) and (mi[b], si[b]) == (oi["m"], oi["s"])
+    assert (m1[0], s1[0]) != (mi[0], si[0]) and (m1[1], s1[1]) != (mi[1], si[1])
+    assert (m1[0], s1[0]) == (mi[1], si[1]) and (m1[1], s1[1]) == (mi[0], si[0])
+
+
+def test_infinity_norm_with_paterson_stockmeyer(ex):
+    from paper_2512_20777_amd import workloads
+    for n, dt in ((40, np.float64), (200, np.float32)):
+        a = workloads.random_stack(950 + n, 6, n, dt, 0.01, 60.0, kind="triu")
+        _run_inf_norm(ex, a, _tol(a), "inf-norm PS n=%d" % n, scheme=1)
+
+
+def test_flow_setting_of_the_paper_tol_1e8_inf_norm(ex):
+    """Workload F1: tolerance 1e-8, infinity-norm, norms 1e-5 .. 12.8: the low orders dominate."""
+    from paper_2512_20777_amd import workloads
+    w = workloads.WORKLOADS["F1"]
+    a = workloads.make_workload("F1")
+    m, s, m1, s1 = _run_inf_norm(ex, a, w.tol, "F1")
+    hist = {int(k): int((m == k).sum()) for k in np.unique(m)}
+    print("   F1 orders:", hist, "max s", int(s.max()), flush=True)
+    assert hist.get(1, 0) > 0 and hist.get(2, 0) > 0 and hist.get(4, 0) > 0 and hist.get(15, 0) > 0
+    assert int(s.max()) <= 3   # norm 12.8 needs s = 3 at this tolerance (the paper's worked example)
