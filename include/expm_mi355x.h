@@ -41,6 +41,7 @@ extern "C" {
 #define EXPM_ERR_TOLERANCE     -2  /* tol negative, NaN, or 0 < tol < unit roundoff of dtype (Sec. 3.2 requires eps >= u) */
 #define EXPM_ERR_ALLOC         -3  /* device or pinned-host allocation failed */
 #define EXPM_ERR_HIP           -4  /* a HIP call failed; expm_last_hip_error() returns its hipError_t */
+#define EXPM_ERR_UNSUPPORTED   -5  /* the scheme asked for is not available for this matrix size */
 
 #define EXPM_S_CAP 20  /* largest scaling Algorithm 4 returns */
 
@@ -98,10 +99,18 @@ int expm(const void *A, int n, int batch, int dtype, double tol, void *out, void
  *                       orders {1,2,4,6,9,12,16}, powers up to W^4 (the paper's expm_flow_ps).  m_out then
  *                       holds one of 0,1,2,4,6,9,12,16.  On the round-based path W^2, W^3 = W^2 W and
  *                       W^4 = W^3 W are formed for the whole batch before the selection.
+ *   EXPM_SCHEME_BASELINE  the comparison baseline of the paper (its Algorithm 1, Sec. 2.2, after Xiao & Liu):
+ *                       smallest s with ||W||/2^s < 1/2, Taylor terms Y <- W Y/k added while ||Y|| > tol,
+ *                       s squarings.  m_out holds the degree reached (it may exceed 16; the paper prices it at
+ *                       (m-1)+s products), no cap on s.  Available on the fused path only (n <= 128 in fp32,
+ *                       n <= 96 in fp64; the paper's flow models use it below 24x24): larger n returns
+ *                       EXPM_ERR_UNSUPPORTED.  expm_select_scheme runs the term loop as well, since the degree
+ *                       is only known at its end.
  * All other arguments, blocking behaviour, ownership and status codes are as for expm_select / expm.
  */
-#define EXPM_SCHEME_SASTRE 0
-#define EXPM_SCHEME_PS     1
+#define EXPM_SCHEME_SASTRE   0
+#define EXPM_SCHEME_PS       1
+#define EXPM_SCHEME_BASELINE 2
 int expm_select_scheme(const void *A, int n, int batch, int dtype, double tol, int scheme,
                        int32_t *m_out, int32_t *s_out);
 int expm_scheme(const void *A, int n, int batch, int dtype, double tol, int scheme, void *out, void *stream);
@@ -146,7 +155,7 @@ struct expm_stats {
     int32_t warning;       /* 0, EXPM_WARN_NONFINITE, EXPM_WARN_SCALING_CAP (larger wins) */
     int32_t fused_path;    /* 1 if the single-kernel on-chip path ran             */
     int32_t scheme;        /* EXPM_SCHEME_* of the call                           */
-    int64_t hist_m[17];    /* matrices with order m, indexed by m = 0..16         */
+    int64_t hist_m[17];    /* matrices with order m, indexed by m = 0..16 (baseline degrees above 16 in the last bin) */
     int64_t hist_s[21];    /* matrices with s = 0..20                             */
     int64_t nonfinite;     /* matrices flagged (-1,-1)                            */
 };

@@ -12,4 +12,5 @@ from .expm_oracle import (  # noqa: F401
     oracle_select_ps,
     oracle_select_ps_from_norms,
     oracle_expm_ps_batch,
+    oracle_expm_baseline_batch,
 )

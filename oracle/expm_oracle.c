@@ -35,7 +35,8 @@
  *     of the GPU library, not part of the method).
  *
  * The file also holds the Paterson-Stockmeyer variant of the paper (Algorithm 3 selection,
- * plain Taylor polynomial T_m, m in {1,2,4,6,9,12,16}); see further down.
+ * plain Taylor polynomial T_m, m in {1,2,4,6,9,12,16}) and the baseline of the paper's
+ * comparison (its Algorithm 1); see further down.
  *
  * Pins (tests/test_oracle_pins.py): the two worked selection examples of the
  * paper (Remark 1; Sec. 4.2, normal matrix of norm 12.8), closed forms
@@ -526,6 +527,99 @@ int oracle_expm_ps_batch(const double *W, int n, int batch, double eps, double *
         for (int b = 0; b < batch; ++b)
             expm_ps_matrix(W + (size_t)b * nn, n, eps, X + (size_t)b * nn, work, 1,
                            &m[b], &s[b], norms + 4 * (size_t)b, &near[b]);
+        free(work);
+    }
+    return fail ? -3 : used;
+}
+
+/* ------------------------------------------------------------------------------------------
+ * Baseline of the paper's comparison (its Algorithm 1, Sec. 2.2, after Xiao & Liu): smallest
+ * s >= 0 with ||W||_1 / 2^s < 1/2; W <- W/2^s; X = I, Y = W, k = 2; while ||Y||_1 > eps:
+ * X += Y, Y = W*Y/k, k++; then s squarings of X (the printed listing squares and returns Y,
+ * which is a slip: Sec. 2.2 describes squaring the computed exponential).
+ * m_out = number of terms added (the degree reached); the paper prices this at (m-1)+s products.
+ * near = 1 if ||W||/2^s lies within 1e-6 relative of 1/2 or some ||Y|| within 1e-6 relative of eps.
+ * work: 3*n*n doubles.
+ * ------------------------------------------------------------------------------------------ */
+static void expm_baseline_matrix(const double *W, int n, double eps, double *X, double *work,
+                                 int *m_out, int *s_out, double *n1_out, int *near)
+{
+    const size_t nn = (size_t)n * n;
+    double *A = work, *Y = work + nn, *next = work + 2 * nn;
+    const double n1 = oracle_norm1(W, n);
+    int s = 0, m = 0;
+    *near = 0;
+    *n1_out = n1;
+    memset(X, 0, sizeof(double) * nn);
+    for (int i = 0; i < n; ++i)
+        X[(size_t)i * n + i] = 1.0;
+    if (n1 == 0.0) {
+        *m_out = 0;
+        *s_out = 0;
+        return;
+    }
+    while (!(ldexp(n1, -s) < 0.5))
+        ++s;
+    {
+        const double r = ldexp(n1, -s) / 0.5, r2 = ldexp(n1, -s + 1) / 0.5;
+        if (fabs(r - 1.0) < 1e-6 || (s > 0 && fabs(r2 - 1.0) < 1e-6))
+            *near = 1;
+    }
+    const double scale = ldexp(1.0, -s);
+    for (size_t t = 0; t < nn; ++t) {
+        A[t] = W[t] * scale;
+        Y[t] = A[t];
+    }
+    int k = 2;
+    for (;;) {
+        const double ny = oracle_norm1(Y, n);
+        if (fabs(ny / eps - 1.0) < 1e-6)
+            *near = 1;
+        if (!(ny > eps))
+            break;
+        for (size_t t = 0; t < nn; ++t)
+            X[t] += Y[t];
+        ++m;
+        matmul_impl(A, Y, next, n, 0);
+        for (size_t t = 0; t < nn; ++t)
+            Y[t] = next[t] / (double)k;
+        ++k;
+    }
+    for (int q = 0; q < s; ++q) {
+        matmul_impl(X, X, next, n, 0);
+        memcpy(X, next, sizeof(double) * nn);
+    }
+    *m_out = m;
+    *s_out = s;
+}
+
+int oracle_expm_baseline_batch(const double *W, int n, int batch, double eps, double *X,
+                               int *m, int *s, double *n1, int *near, int threads)
+{
+    const size_t nn = (size_t)n * n;
+    int used = 1;
+#ifdef _OPENMP
+    if (threads <= 0)
+        threads = omp_get_max_threads();
+    used = threads;
+    omp_set_num_threads(threads);
+#else
+    (void)threads;
+#endif
+    int fail = 0;
+#pragma omp parallel
+    {
+        double *work = (double *)malloc(sizeof(double) * 3 * nn + 8);
+        if (!work) {
+#pragma omp atomic write
+            fail = 1;
+        }
+#pragma omp for schedule(dynamic, 1)
+        for (int b = 0; b < batch; ++b) {
+            if (work)
+                expm_baseline_matrix(W + (size_t)b * nn, n, eps, X + (size_t)b * nn, work,
+                                     &m[b], &s[b], &n1[b], &near[b]);
+        }
         free(work);
     }
     return fail ? -3 : used;

@@ -59,6 +59,9 @@ def _load():
         lib.oracle_expm_ps_batch.restype = ctypes.c_int
         lib.oracle_expm_ps_batch.argtypes = [dp, ctypes.c_int, ctypes.c_int, ctypes.c_double, dp,
                                              ip, ip, dp, ip, ctypes.c_int]
+        lib.oracle_expm_baseline_batch.restype = ctypes.c_int
+        lib.oracle_expm_baseline_batch.argtypes = [dp, ctypes.c_int, ctypes.c_int, ctypes.c_double, dp,
+                                                   ip, ip, dp, ip, ctypes.c_int]
         lib.oracle_max_threads.restype = ctypes.c_int
         lib.oracle_max_threads.argtypes = []
         _lib = lib
@@ -195,6 +198,27 @@ def oracle_expm_ps_batch(W, tol: float, threads: int = 0):
         if used < 0:
             raise MemoryError("oracle_expm_ps_batch")
     return X, dict(m=m, s=s, norms=norms, near=near.astype(bool), threads=used)
+
+
+def oracle_expm_baseline_batch(W, tol: float, threads: int = 0):
+    """The paper's baseline (its Algorithm 1) on a batch -> (X fp64, dict of arrays m, s, n1, near, threads)."""
+    a = _as_f64(W)
+    if a.ndim == 2:
+        a = a[None]
+    assert a.ndim == 3 and a.shape[1] == a.shape[2]
+    b, n = a.shape[0], a.shape[1]
+    X = np.empty_like(a)
+    m = np.zeros(b, dtype=np.int32)
+    s = np.zeros(b, dtype=np.int32)
+    near = np.zeros(b, dtype=np.int32)
+    n1 = np.zeros(b, dtype=np.float64)
+    used = 0
+    if b > 0 and n > 0:
+        used = _load().oracle_expm_baseline_batch(_dptr(a), n, b, float(tol), _dptr(X), _iptr(m), _iptr(s),
+                                                  _dptr(n1), _iptr(near), int(threads))
+        if used < 0:
+            raise MemoryError("oracle_expm_baseline_batch")
+    return X, dict(m=m, s=s, n1=n1, near=near.astype(bool), threads=used)
 
 
 def oracle_max_threads() -> int:

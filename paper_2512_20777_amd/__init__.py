@@ -8,6 +8,7 @@ from .binding import (  # noqa: F401
     DTYPE_F64,
     NORM_INF,
     NORM_ONE,
+    SCHEME_BASELINE,
     SCHEME_PS,
     SCHEME_SASTRE,
     ExpmError,

@@ -18,6 +18,7 @@ DTYPE_F32 = 0
 DTYPE_F64 = 1
 SCHEME_SASTRE = 0   # Algorithm 4 + evaluation formulas of Sec. 3.1 (orders 1,2,4,8,15+)
 SCHEME_PS = 1       # Algorithm 3 + Paterson-Stockmeyer (orders 1,2,4,6,9,12,16)
+SCHEME_BASELINE = 2  # the paper's comparison baseline (its Algorithm 1); small matrices only
 NORM_ONE = 0        # selection on 1-norms (the printed algorithms)
 NORM_INF = 1        # selection on infinity-norms (the paper's PyTorch runs, Sec. 4.2)
 

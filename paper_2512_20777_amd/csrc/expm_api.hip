@@ -299,11 +299,13 @@ int expm_select_scheme(const void *A, int n, int batch, int dtype, double tol, i
 int expm_select_ex(const void *A, int n, int batch, int dtype, double tol, int scheme, int norm_kind, int32_t *m_out,
                    int32_t *s_out)
 {
-    if (scheme != EXPM_SCHEME_SASTRE && scheme != EXPM_SCHEME_PS) return EXPM_ERR_INVALID_ARG;
+    if (scheme != EXPM_SCHEME_SASTRE && scheme != EXPM_SCHEME_PS && scheme != EXPM_SCHEME_BASELINE)
+        return EXPM_ERR_INVALID_ARG;
     if (norm_kind != EXPM_NORM_ONE && norm_kind != EXPM_NORM_INF) return EXPM_ERR_INVALID_ARG;
     int rc = check_args(A, n, batch, dtype, tol);
     if (rc != EXPM_OK) return rc;
     if (batch > 0 && (m_out == nullptr || s_out == nullptr)) return EXPM_ERR_INVALID_ARG;
+    if (scheme == EXPM_SCHEME_BASELINE && !small_path_supported(n, dtype)) return EXPM_ERR_UNSUPPORTED;
     if (batch == 0) return EXPM_OK;
     if (n == 0) {
         for (int b = 0; b < batch; ++b) { m_out[b] = 0; s_out[b] = 0; }
@@ -345,12 +347,14 @@ int expm_scheme(const void *A, int n, int batch, int dtype, double tol, int sche
 
 int expm_ex(const void *A, int n, int batch, int dtype, double tol, int scheme, int norm_kind, void *out, void *stream_v)
 {
-    if (scheme != EXPM_SCHEME_SASTRE && scheme != EXPM_SCHEME_PS) return EXPM_ERR_INVALID_ARG;
+    if (scheme != EXPM_SCHEME_SASTRE && scheme != EXPM_SCHEME_PS && scheme != EXPM_SCHEME_BASELINE)
+        return EXPM_ERR_INVALID_ARG;
     if (norm_kind != EXPM_NORM_ONE && norm_kind != EXPM_NORM_INF) return EXPM_ERR_INVALID_ARG;
     int rc = check_args(A, n, batch, dtype, tol);
     if (rc != EXPM_OK) return rc;
     if (n == 0 || batch == 0) return EXPM_OK;
     if (out == nullptr) return EXPM_ERR_INVALID_ARG;
+    if (scheme == EXPM_SCHEME_BASELINE && !small_path_supported(n, dtype)) return EXPM_ERR_UNSUPPORTED;
     {
         const size_t bytes = (size_t)batch * n * n * (dtype == EXPM_DTYPE_F64 ? 8 : 4);
         const uintptr_t a0 = (uintptr_t)A, o0 = (uintptr_t)out;
@@ -430,10 +434,12 @@ int expm_get_stats(struct expm_stats *st)
         int pi = 0;
         if (g_last.scheme == kSchemePS) {
             pi = mi.m < 2 ? 0 : ps_j(mi.m) - 1 + ps_k(mi.m) - 1;
+        } else if (g_last.scheme == kSchemeBaseline) {
+            pi = mi.m < 1 ? 0 : mi.m - 1;   // the paper prices degree m at (m-1) products (its eq. for C_orig)
         } else {
             pi = mi.m < 2 ? 0 : (mi.m == 2 ? 1 : (mi.m == 4 ? 2 : (mi.m == 8 ? 3 : 4)));
         }
-        if (mi.m >= 0 && mi.m <= 16) st->hist_m[mi.m]++;
+        st->hist_m[mi.m > 16 ? 16 : mi.m]++;   // the baseline may exceed degree 16: counted in the last bin
         if (mi.s >= 0 && mi.s <= EXPM_S_CAP) st->hist_s[mi.s]++;
         st->products += pi + mi.s;
     }
@@ -502,6 +508,7 @@ const char *expm_status_string(int status)
     case EXPM_ERR_TOLERANCE: return "error: tolerance is negative, NaN or below the unit roundoff of dtype";
     case EXPM_ERR_ALLOC: return "error: allocation failed";
     case EXPM_ERR_HIP: return "error: a HIP call failed (see expm_last_hip_error)";
+    case EXPM_ERR_UNSUPPORTED: return "error: this scheme is not available for this matrix size";
     default: return "unknown status";
     }
 }

@@ -102,13 +102,13 @@ __global__ __launch_bounds__(NT == 1 ? 64 : 256) void fused_expm_kernel(const T 
     // ---- norm of the matrix in P: max column abs-sum (1-norm) or, with norm_inf, max row abs-sum -------
     // double accumulation, NaN if non-finite.  Thread t sums entries t/NP, t/NP + G, ... of column (row)
     // t%NP (G groups); the groups are then added in order.
-    auto norm1_of_P = [&]() -> double {
+    auto norm_of = [&](const T *M, int pitch) -> double {
         constexpr int G = C::kThreads / NP > 0 ? C::kThreads / NP : 1;
         const int col = tid % NP, grp = tid / NP;
         double s = 0.0;
         if (grp < G) {
 #pragma unroll 8
-            for (int r = grp; r < n; r += G) s += fabs((double)(norm_inf ? P[col * LPA + r] : P[r * LPA + col]));
+            for (int r = grp; r < n; r += G) s += fabs((double)(norm_inf ? M[col * pitch + r] : M[r * pitch + col]));
         }
         __syncthreads();  // red[] free to overwrite
         red[tid] = s;
@@ -136,6 +136,7 @@ __global__ __launch_bounds__(NT == 1 ? 64 : 256) void fused_expm_kernel(const T 
         }
         return anybad != 0.0 ? __longlong_as_double(0x7ff8000000000000LL) : mx;
     };
+    auto norm1_of_P = [&]() -> double { return norm_of(P, LPA); };
 
     // ---- acc = P * Q on this wave's block of tiles --------------------------------------------------
     acc_t acc[TH][TH];
@@ -193,6 +194,8 @@ __global__ __launch_bounds__(NT == 1 ? 64 : 256) void fused_expm_kernel(const T 
     });
 
     int m = 0, s = 0, flags = 0;
+    // The polynomial X ends in registers xv (aliasing acc's storage is left to the compiler).
+    T xv[TH][TH][4];
     const double n1 = norm1_of_P();
     T a3v[TH][TH][4], a4v[TH][TH][4];  // W^3, W^4 of the Paterson-Stockmeyer variant
     if constexpr (SCHEME == kSchemePS) {
@@ -234,6 +237,40 @@ __global__ __launch_bounds__(NT == 1 ? 64 : 256) void fused_expm_kernel(const T 
             nrm[3] = norm1_of_P();
             select_ps_order_scaling(nrm, 4, eps, m, s, flags, need_more);
         }
+    } else if constexpr (SCHEME == kSchemeBaseline) {
+        // The comparison baseline of the paper (its Algorithm 1): s from ||W|| / 2^s < 1/2, then Taylor terms
+        // Y <- W Y / k are added while ||Y|| > eps.  The whole loop runs here because the degree reached
+        // is only known at its end; xv holds X when it is done.
+        for_owned([&](int ti, int tj, int v, int r, int c) { xv[ti][tj][v] = dg(r, c); });
+        if (!(n1 <= 1.7976931348623157e308)) {
+            m = -1; s = -1; flags = 1;
+        } else if (n1 > 0.0) {
+            double t = n1;
+            while (!(t < 0.5)) { t *= 0.5; ++s; }
+            const T sg = (T)ldexp(1.0, -s);
+            __syncthreads();
+            for_owned([&](int ti, int tj, int v, int r, int c) {
+                av[ti][tj][v] *= sg;
+                yv[ti][tj][v] = av[ti][tj][v];
+                P[r * LPA + c] = av[ti][tj][v];   // left operand: the scaled matrix, fixed
+                Q[r * LPB + c] = av[ti][tj][v];   // right operand: the current term Y
+            });
+            __syncthreads();
+            int k = 2;
+            for (int it = 0; it < 256; ++it) {
+                const double ny = norm_of(Q, LPB);
+                if (!(ny > eps)) break;
+                for_owned([&](int ti, int tj, int v, int, int) { xv[ti][tj][v] += yv[ti][tj][v]; });
+                ++m;
+                product();
+                const T kk = (T)k;
+                for_owned([&](int ti, int tj, int v, int, int) { yv[ti][tj][v] = acc[ti][tj][v] / kk; });
+                ++k;
+                __syncthreads();
+                for_owned([&](int ti, int tj, int v, int r, int c) { Q[r * LPB + c] = yv[ti][tj][v]; });
+                __syncthreads();
+            }
+        }
     } else {
         double n2 = 0.0;
         // orders 0 and 1 need no product: Algorithm 4 forms W^2 only once the m = 1 test has failed
@@ -264,9 +301,9 @@ __global__ __launch_bounds__(NT == 1 ? 64 : 256) void fused_expm_kernel(const T 
         return;
     }
 
-    // The polynomial X ends in registers xv (aliasing acc's storage is left to the compiler).
-    T xv[TH][TH][4];
-    if constexpr (SCHEME == kSchemePS) {
+    if constexpr (SCHEME == kSchemeBaseline) {
+        // nothing left to evaluate: the term loop above produced X
+    } else if constexpr (SCHEME == kSchemePS) {
         // ---- Paterson-Stockmeyer: T_m(A) = Horner in A^j with blocks of degree < j, m = j*k -----------------
         const int j = ps_j(m), k = ps_k(m);
         if (s > 0) {
@@ -453,8 +490,11 @@ hipError_t launch_small(const void *A, void *out, int n, int batch, int dtype, d
         return scheme == kSchemePS                                                                            \
                    ? launch_fused_t<TYPE, K, kSchemePS>(A, out, n, batch, eps, select_only, norm_inf, info,   \
                                                         stream)                                              \
-                   : launch_fused_t<TYPE, K, kSchemeSastre>(A, out, n, batch, eps, select_only, norm_inf,     \
-                                                            info, stream);
+                   : (scheme == kSchemeBaseline                                                               \
+                          ? launch_fused_t<TYPE, K, kSchemeBaseline>(A, out, n, batch, eps, select_only,      \
+                                                                     norm_inf, info, stream)                  \
+                          : launch_fused_t<TYPE, K, kSchemeSastre>(A, out, n, batch, eps, select_only,        \
+                                                                   norm_inf, info, stream));
     if (dtype == 1) {
         switch (nt) {
             EXPM_FUSED_CASE(double, 1) EXPM_FUSED_CASE(double, 2) EXPM_FUSED_CASE(double, 3)

@@ -232,6 +232,7 @@ template <> struct Mfma<float> {
 // ---------------------------------------------------------------------------------------------
 constexpr int kSchemeSastre = 0;  // evaluation formulas of Sec. 3.1 with Algorithm 4
 constexpr int kSchemePS = 1;      // Paterson-Stockmeyer with Algorithm 3
+constexpr int kSchemeBaseline = 2;  // the paper's comparison baseline (its Algorithm 1); fused path only
 
 enum Buf : int { BUF_W = 0, BUF_W2 = 1, BUF_T0 = 2, BUF_T1 = 3, BUF_T2 = 4, BUF_T3 = 5, BUF_T4 = 6, BUF_T5 = 7,
                  BUF_OUT = 8, BUF_COUNT = 9,
