@@ -160,10 +160,10 @@ __global__ __launch_bounds__(kThreads, WT == 4 ? 2 : 4) void gemm_round_kernel(G
     const int a_lds = a_row0 * kAPitch + (tid & 7) * 16;
     const int b_lds = BM * kAPitch + b_row0 * BPitch;
     const int b_vcol = (tid % VPR) * 16;  // byte offset of this thread's vector inside an unrotated row
-    int b_wr[WT];
-#pragma unroll
-    for (int i = 0; i < WT; ++i)
-        b_wr[i] = b_lds + BSTEP * i * BPitch + ((b_vcol + kRot * ((b_row0 + BSTEP * i) / KQ)) & (BPitch - 1));
+    // LDS byte offset of staged B vector i (recomputed where used: two instructions, no register held)
+    auto b_wr = [&](int i) -> int {
+        return b_lds + BSTEP * i * BPitch + ((b_vcol + kRot * ((b_row0 + BSTEP * i) / KQ)) & (BPitch - 1));
+    };
     const int row0 = tm * BM, col0 = tn * BN;
 
     acc_t acc[WT][WT];
@@ -183,7 +183,7 @@ __global__ __launch_bounds__(kThreads, WT == 4 ? 2 : 4) void gemm_round_kernel(G
 #pragma unroll
     for (int i = 0; i < WT; ++i) {
         *reinterpret_cast<V *>(smem + a_lds + 32 * i * kAPitch) = ra[i];
-        *reinterpret_cast<V *>(smem + b_wr[i]) = rb[i];
+        *reinterpret_cast<V *>(smem + b_wr(i)) = rb[i];
     }
     __syncthreads();
 
@@ -192,9 +192,7 @@ __global__ __launch_bounds__(kThreads, WT == 4 ? 2 : 4) void gemm_round_kernel(G
     //   B: row (lg*KQ + kk), column (wn*16*WT + 16*tj + lj) rotated by 16*lg elements
     const int a_rd = (wm * 16 * WT + lj) * kAPitch + lg * 32;
     const int b_rd = BM * kAPitch + (lg * KQ) * BPitch + lj * (int)sizeof(T);
-    int b_rc[WT];
-#pragma unroll
-    for (int tj = 0; tj < WT; ++tj) b_rc[tj] = ((wn * 16 * WT + 16 * tj + 16 * lg) * (int)sizeof(T)) & (BPitch - 1);
+    const int b_rc0 = (wn * 16 * WT + 16 * lg) * (int)sizeof(T);  // rotated column of tile column 0, before wrap
 
     for (int kb = 0; kb < kblocks; ++kb) {
         const unsigned char *cur = smem + (kb & 1) * STAGE;
@@ -208,36 +206,34 @@ __global__ __launch_bounds__(kThreads, WT == 4 ? 2 : 4) void gemm_round_kernel(G
                 rb[i] = load_vec<T, ALIGNED>(Rp, k0 + b_row0 + BSTEP * i, col0 + b_col, n);
             }
         }
-        // A fragments of the whole k-block
-        T af[WT][KQ];
+        // A fragments: each lane's KQ k-values of a row are two 16-byte halves; one half (VN k-steps) at a
+        // time keeps the live registers low, the co-resident waves cover the LDS latency
 #pragma unroll
-        for (int ti = 0; ti < WT; ++ti) {
-            const V lo = *reinterpret_cast<const V *>(cur + a_rd + ti * 16 * kAPitch);
-            const V hi = *reinterpret_cast<const V *>(cur + a_rd + ti * 16 * kAPitch + 16);
-            const T *l = reinterpret_cast<const T *>(&lo);
-            const T *h = reinterpret_cast<const T *>(&hi);
-#pragma unroll
-            for (int q = 0; q < VN; ++q) {
-                af[ti][q] = l[q];
-                af[ti][VN + q] = h[q];
-            }
-        }
-#pragma unroll
-        for (int kk = 0; kk < KQ; ++kk) {
-            T bf[WT];
-#pragma unroll
-            for (int tj = 0; tj < WT; ++tj)
-                bf[tj] = *reinterpret_cast<const T *>(cur + b_rd + kk * BPitch + b_rc[tj]);
+        for (int h = 0; h < 2; ++h) {
+            V af[WT];
 #pragma unroll
             for (int ti = 0; ti < WT; ++ti)
+                af[ti] = *reinterpret_cast<const V *>(cur + a_rd + ti * 16 * kAPitch + 16 * h);
 #pragma unroll
-                for (int tj = 0; tj < WT; ++tj) acc[ti][tj] = Mfma<T>::run(af[ti][kk], bf[tj], acc[ti][tj]);
+            for (int q = 0; q < VN; ++q) {
+                const int kk = h * VN + q;
+                T bf[WT];
+#pragma unroll
+                for (int tj = 0; tj < WT; ++tj)
+                    bf[tj] = *reinterpret_cast<const T *>(cur + b_rd + kk * BPitch + ((b_rc0 + tj * kRot) & (BPitch - 1)));
+#pragma unroll
+                for (int ti = 0; ti < WT; ++ti) {
+                    const T a = reinterpret_cast<const T *>(&af[ti])[q];
+#pragma unroll
+                    for (int tj = 0; tj < WT; ++tj) acc[ti][tj] = Mfma<T>::run(a, bf[tj], acc[ti][tj]);
+                }
+            }
         }
         if (more) {
 #pragma unroll
             for (int i = 0; i < WT; ++i) {
                 *reinterpret_cast<V *>(nxt + a_lds + 32 * i * kAPitch) = ra[i];
-                *reinterpret_cast<V *>(nxt + b_wr[i]) = rb[i];
+                *reinterpret_cast<V *>(nxt + b_wr(i)) = rb[i];
             }
         }
         __syncthreads();
