@@ -5,12 +5,17 @@
 // the evaluation formulas of Sec. 3.1, the s squarings -- and the result is written once.
 // (m, s) is uniform over the workgroup, so no wavefront diverges and nothing has to be bucketed.
 //
-// Layout on chip: two LDS buffers hold the current left and right operand of a product, each with
-// a pitch chosen so that the MFMA fragment reads of that side are bank-conflict free; everything
-// that is only combined element-wise (A, A^2, y02, the additive part) lives in registers of the
-// lane that owns the element in the MFMA result layout.  Products are 16x16 tiles of MFMA 16x16x4
-// in the matrix dtype on the zero-padded matrix; 1 wave for n <= 16, otherwise 2x2 waves, each
-// owning a TH x TH block of tiles.
+// Layout on chip: two LDS buffers hold the current left and right operand of a product; everything that
+// is only combined element-wise (A, A^2, y02, the additive part) lives in registers of the lane that owns
+// the element in the MFMA result layout.  Products are 16x16 tiles of MFMA 16x16x4 in the matrix dtype on
+// the zero-padded matrix; 1 wave for n <= 16, otherwise 2x2 waves, each owning a TH x TH block of tiles.
+//
+// fp32: the left operand is kept row-major and the right operand transposed, so that on both sides a lane
+// fetches four consecutive k of its row or column with one 16-byte read (lane group g takes k = 16G + 4g + q
+// in step q of group G); with a pitch of 4*odd words these reads, the 16-byte stores of a result tile into
+// the transposed buffer and its 4-byte stores into the row-major buffer are all free of bank conflicts.
+// Every wave computes its full block of tiles; the buffers are padded to 2*TH tiles per side.
+// fp64: one 8-byte read per fragment, each buffer with the pitch that keeps its side conflict free.
 #include "expm_internal.h"
 
 namespace expmk {
@@ -23,12 +28,15 @@ template <typename T, int NT> struct FusedCfg {
     static constexpr int TH = (NT + WG - 1) / WG;       // tiles per wave per dimension
     static constexpr int kThreads = 64 * WG * WG;
     static constexpr bool kF32 = sizeof(T) == 4;
-    // left operand: 16 lanes read 16 consecutive rows at one k -> pitch = 4*odd words (f32) / 2*odd (f64)
-    static constexpr int LPA = NP + (kF32 ? 4 : 2);
-    // right operand: the four 16-lane groups read four k rows -> pitch = 16*odd elements
-    static constexpr int LPB = kF32 ? (NT % 2 == 0 ? NP + 16 : NP + 32) : (NT % 2 == 0 ? NP + 16 : NP);
-    static constexpr int kBytesP = NP * LPA * (int)sizeof(T);
-    static constexpr int kBytesQ = NP * LPB * (int)sizeof(T);
+    static constexpr bool kWide = kF32;                  // 16-byte fragment reads, right operand transposed
+    static constexpr int NPP = 16 * WG * TH;             // rows and columns covered by the waves' tile blocks
+    static constexpr int kRows = kWide ? NPP : NP;
+    // fp64 left operand: 16 lanes read 16 consecutive rows at one k -> pitch = 2*odd words
+    static constexpr int LPA = kWide ? NPP + 4 : NP + 2;
+    // fp64 right operand: the four 16-lane groups read four k rows -> pitch = 16*odd elements
+    static constexpr int LPB = kWide ? NPP + 4 : (NT % 2 == 0 ? NP + 16 : NP);
+    static constexpr int kBytesP = kRows * LPA * (int)sizeof(T);
+    static constexpr int kBytesQ = kRows * LPB * (int)sizeof(T);
     static constexpr int kLds = kBytesP + kBytesQ + (kThreads + 16) * (int)sizeof(double);
     static_assert(kLds <= 163840, "fused path exceeds the LDS of one compute unit");
 };
@@ -36,6 +44,24 @@ template <typename T, int NT> struct FusedCfg {
 template <typename T> struct VecOf;
 template <> struct VecOf<float> { using type = float4; };
 template <> struct VecOf<double> { using type = double2; };
+
+// x of the lane that the DPP control CTRL pairs with this one (within rows of 16 lanes)
+template <int CTRL> __device__ __forceinline__ double dpp_move(double x)
+{
+    const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(x), CTRL, 0xf, 0xf, false);
+    const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(x), CTRL, 0xf, 0xf, false);
+    return __hiloint2double(hi, lo);
+}
+// Reduction over the 16 lanes of a row, result in every lane: mirror the row, mirror its halves, then
+// swap pairs of pairs and pairs -- four steps that each join two disjoint sets of lanes.
+template <typename Op> __device__ __forceinline__ double row16_allreduce(double x, Op op)
+{
+    x = op(x, dpp_move<0x140>(x));  // row_mirror
+    x = op(x, dpp_move<0x141>(x));  // row_half_mirror
+    x = op(x, dpp_move<0x4e>(x));   // quad_perm [2,3,0,1]
+    x = op(x, dpp_move<0xb1>(x));   // quad_perm [1,0,3,2]
+    return x;
+}
 
 __device__ __forceinline__ double pow2neg_f(int e)
 {
@@ -49,7 +75,8 @@ __global__ __launch_bounds__(NT == 1 ? 64 : 256) void fused_expm_kernel(const T 
 {
     using C = FusedCfg<T, NT>;
     using acc_t = typename Mfma<T>::acc_t;
-    constexpr int NP = C::NP, LPA = C::LPA, LPB = C::LPB, TH = C::TH, WG = C::WG;
+    constexpr int NP = C::NP, LPA = C::LPA, LPB = C::LPB, TH = C::TH, WG = C::WG, NR = C::kRows;
+    constexpr bool kWide = C::kWide;
     extern __shared__ __align__(16) unsigned char smem_raw[];
     T *P = reinterpret_cast<T *>(smem_raw);                         // left operand layout
     T *Q = reinterpret_cast<T *>(smem_raw + C::kBytesP);            // right operand layout
@@ -59,117 +86,207 @@ __global__ __launch_bounds__(NT == 1 ? 64 : 256) void fused_expm_kernel(const T 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform, kept in a scalar register
     const int wr = wave / WG, wc = wave % WG;
-    constexpr bool kAllTiles = NT % WG == 0;  // every wave owns a full TH x TH block
+    constexpr bool kAllTiles = kWide || NT % WG == 0;  // every wave computes a full TH x TH block
     auto row_ok = [&](int ti) -> bool { return kAllTiles || wr * TH + ti < NT; };
     auto col_ok = [&](int tj) -> bool { return kAllTiles || wc * TH + tj < NT; };
     const int lj = lane & 15, lg = lane >> 4;
     const size_t moff = (size_t)b * n * n;
     const T *W = Ain + moff;
+    // position of element (r, c) in the left-operand buffer P and in the right-operand buffer Q
+    auto li = [&](int r, int c) -> int { return r * LPA + c; };
+    auto ri = [&](int r, int c) -> int { return kWide ? c * LPB + r : r * LPB + c; };
 
     // ---- load W into both operand layouts, zero padded -------------------------------------------
     constexpr int VN = 16 / (int)sizeof(T);  // elements per 16-byte vector
     const bool vec_ok = (n % VN == 0) && ((reinterpret_cast<uintptr_t>(Ain) | reinterpret_cast<uintptr_t>(Out)) % 16 == 0);
-    if (n < NP) {
-        for (int e = tid; e < NP * NP; e += C::kThreads) {
-            const int r = e / NP, c = e - r * NP;
+    if (n < NR) {
+        for (int e = tid; e < NR * NR; e += C::kThreads) {
+            const int r = e / NR, c = e - r * NR;
             if (r >= n || c >= n) {
-                P[r * LPA + c] = (T)0;
-                Q[r * LPB + c] = (T)0;
+                P[li(r, c)] = (T)0;
+                if constexpr (!kWide) Q[ri(r, c)] = (T)0;
             }
         }
     }
+    // (the transposed copy of the fp32 path is written further down, from registers)
     if (vec_ok) {
         using V = typename VecOf<T>::type;
         const int vpr = n / VN, total = n * vpr;
-#pragma unroll 4
+#pragma unroll(NT >= 4 ? 16 : (NT >= 2 ? 4 : 1))  // all of a thread's loads in flight at once
         for (int e = tid; e < total; e += C::kThreads) {
             const int r = e / vpr, c = (e - r * vpr) * VN;
             const V x = *reinterpret_cast<const V *>(W + (size_t)r * n + c);
-            *reinterpret_cast<V *>(P + r * LPA + c) = x;
-            *reinterpret_cast<V *>(Q + r * LPB + c) = x;
+            *reinterpret_cast<V *>(P + li(r, c)) = x;
+            if constexpr (!kWide) *reinterpret_cast<V *>(Q + ri(r, c)) = x;
         }
     } else {
 #pragma unroll 4
         for (int e = tid; e < n * n; e += C::kThreads) {
             const int r = e / n, c = e - r * n;
             const T x = W[e];
-            P[r * LPA + c] = x;
-            Q[r * LPB + c] = x;
+            P[li(r, c)] = x;
+            if constexpr (!kWide) Q[ri(r, c)] = x;
         }
     }
     __syncthreads();
 
-    // ---- norm of the matrix in P: max column abs-sum (1-norm) or, with norm_inf, max row abs-sum -------
-    // double accumulation, NaN if non-finite.  Thread t sums entries t/NP, t/NP + G, ... of column (row)
-    // t%NP (G groups); the groups are then added in order.
-    auto norm_of = [&](const T *M, int pitch) -> double {
-        constexpr int G = C::kThreads / NP > 0 ? C::kThreads / NP : 1;
-        const int col = tid % NP, grp = tid / NP;
-        double s = 0.0;
-        if (grp < G) {
-#pragma unroll 8
-            for (int r = grp; r < n; r += G) s += fabs((double)(norm_inf ? M[col * pitch + r] : M[r * pitch + col]));
+    // ---- norm of a matrix held in registers in the result layout, get(ti, tj, v) -> element: max column
+    // abs-sum (1-norm) or, with norm_inf, max row abs-sum; sums in double, NaN if not finite.  Each wave adds
+    // up its part of every line (column or row) with lane shuffles, the parts meet in LDS, and every wave
+    // then takes the maximum over all lines itself, so that all lanes return the same bits.
+    auto norm_regs = [&](auto &&get) -> double {
+        constexpr int L = 16 * WG * TH;  // lines covered by the waves' tile blocks
+        auto add = [](double a, double b2) { return a + b2; };
+        auto mxop = [](double a, double b2) { return b2 > a ? b2 : a; };
+        if constexpr (NT == 1) {
+            // one wave, one tile: the shuffles alone finish the sums, nothing goes through LDS
+            double line;
+            if (!norm_inf) {
+                line = 0.0;
+#pragma unroll
+                for (int v = 0; v < 4; ++v) line += fabs((double)get(0, 0, v));
+                line += __shfl_xor(line, 16);
+                line += __shfl_xor(line, 32);  // column lj, complete in every lane
+            } else {
+                double rs[4];
+#pragma unroll
+                for (int v = 0; v < 4; ++v) rs[v] = row16_allreduce(fabs((double)get(0, 0, v)), add);
+                const int bad4 = !(rs[0] + rs[1] + rs[2] + rs[3] <= 1.7976931348623157e308);
+                line = mxop(mxop(rs[0], rs[1]), mxop(rs[2], rs[3]));
+                if (bad4) line = __longlong_as_double(0x7ff8000000000000LL);
+            }
+            const int bad = !(line <= 1.7976931348623157e308);
+            double mx = bad ? 0.0 : line;
+            mx = row16_allreduce(mx, mxop);
+            mx = mxop(mx, __shfl_xor(mx, 16));
+            mx = mxop(mx, __shfl_xor(mx, 32));
+            return __any(bad) ? __longlong_as_double(0x7ff8000000000000LL) : mx;
         }
         __syncthreads();  // red[] free to overwrite
-        red[tid] = s;
-        __syncthreads();
-        double cs = 0.0;
-        if (tid < NP) {
+        if (!norm_inf) {
 #pragma unroll
-            for (int g = 0; g < G; ++g) cs += red[g * NP + tid];
-        }
-        int bad = !(cs <= 1.7976931348623157e308);
-        for (int off = 32; off > 0; off >>= 1) {
-            const double o = __shfl_xor(cs, off);
-            const int ob = __shfl_xor(bad, off);
-            cs = o > cs ? o : cs;
-            bad |= ob;
-        }
-        double *red2 = red + C::kThreads;
-        if (lane == 0) { red2[wave] = cs; red2[8 + wave] = (double)bad; }
-        __syncthreads();
-        double mx = red2[0], anybad = red2[8];
+            for (int tj = 0; tj < TH; ++tj) {
+                double sum = 0.0;
 #pragma unroll
-        for (int w = 1; w < WG * WG; ++w) {
-            mx = red2[w] > mx ? red2[w] : mx;
-            anybad += red2[8 + w];
-        }
-        return anybad != 0.0 ? __longlong_as_double(0x7ff8000000000000LL) : mx;
-    };
-    auto norm1_of_P = [&]() -> double { return norm_of(P, LPA); };
-
-    // ---- acc = P * Q on this wave's block of tiles --------------------------------------------------
-    acc_t acc[TH][TH];
-    auto product = [&]() {
+                for (int ti = 0; ti < TH; ++ti)
+                    if (row_ok(ti) && col_ok(tj)) {
 #pragma unroll
-        for (int ti = 0; ti < TH; ++ti)
-#pragma unroll
-            for (int tj = 0; tj < TH; ++tj) acc[ti][tj] = (acc_t)(0);
-        const T *lp = P + (16 * (wr * TH) + lj) * LPA + lg;
-        const T *rp = Q + lg * LPB + 16 * (wc * TH) + lj;
-        constexpr int NK = NP / 4;  // k-steps; even
-        T a0[TH], b0[TH], a1[TH], b1[TH];
-        auto fetch = [&](T *a, T *bq, int kk) {
-#pragma unroll
-            for (int ti = 0; ti < TH; ++ti) a[ti] = row_ok(ti) ? lp[ti * 16 * LPA + 4 * kk] : (T)0;
-#pragma unroll
-            for (int tj = 0; tj < TH; ++tj) bq[tj] = col_ok(tj) ? rp[4 * kk * LPB + tj * 16] : (T)0;
-        };
-        auto fma_step = [&](const T *a, const T *bq) {
+                        for (int v = 0; v < 4; ++v) sum += fabs((double)get(ti, tj, v));
+                    }
+                sum += __shfl_xor(sum, 16);
+                sum += __shfl_xor(sum, 32);
+                if (lg == 0) red[wr * L + 16 * (wc * TH + tj) + lj] = sum;
+            }
+        } else {
 #pragma unroll
             for (int ti = 0; ti < TH; ++ti)
 #pragma unroll
-                for (int tj = 0; tj < TH; ++tj)
-                    if (row_ok(ti) && col_ok(tj)) acc[ti][tj] = Mfma<T>::run(a[ti], bq[tj], acc[ti][tj]);
-        };
-        // software pipeline: the fragments of the next k-step are in flight while this one multiplies
-        fetch(a0, b0, 0);
+                for (int v = 0; v < 4; ++v) {
+                    double sum = 0.0;
+#pragma unroll
+                    for (int tj = 0; tj < TH; ++tj)
+                        if (row_ok(ti) && col_ok(tj)) sum += fabs((double)get(ti, tj, v));
+                    sum = row16_allreduce(sum, add);
+                    if (lj == 0) red[wc * L + 16 * (wr * TH + ti) + Mfma<T>::row(lg, v)] = sum;
+                }
+        }
+        __syncthreads();
+        double mx = 0.0;
+        int bad = 0;
+        for (int line = lane; line < L; line += 64) {
+            double t = red[line];
+            if (WG == 2) t += red[L + line];
+            bad |= !(t <= 1.7976931348623157e308);
+            mx = t > mx ? t : mx;
+        }
+        mx = row16_allreduce(mx, mxop);
+        mx = mxop(mx, __shfl_xor(mx, 16));
+        mx = mxop(mx, __shfl_xor(mx, 32));
+        return __any(bad) ? __longlong_as_double(0x7ff8000000000000LL) : mx;
+    };
+
+    // ---- acc = L * R on this wave's block of tiles; L in left-operand layout, R in right-operand layout ----
+    // Fragments of the next step are in flight while this one multiplies.  A prefetch past the end wraps to
+    // step 0 (read, not used) so that the loop body has no branch and every wait is exact.
+    acc_t acc[TH][TH];
+    auto product = [&](const T *Lb, const T *Rb) {
+        if constexpr (kWide) {
+            // One group = four k-steps = one 16-byte fragment per tile row and per tile column.
+            using V = typename VecOf<T>::type;
+            constexpr int NG = NP / 16;
+            const T *lp = Lb + (16 * (wr * TH) + lj) * LPA + 4 * lg;
+            const T *rp = Rb + (16 * (wc * TH) + lj) * LPB + 4 * lg;
+            V a0[TH], b0[TH], a1[TH], b1[TH];
+            auto fetch = [&](V *a, V *bq, int g) {
+#pragma unroll
+                for (int t = 0; t < TH; ++t) a[t] = *reinterpret_cast<const V *>(lp + t * 16 * LPA + 16 * g);
+#pragma unroll
+                for (int t = 0; t < TH; ++t) bq[t] = *reinterpret_cast<const V *>(rp + t * 16 * LPB + 16 * g);
+            };
+            // 4*TH*TH MFMAs; the 2*TH fragment reads issued just before are spread between the first of them,
+            // one read per TH MFMAs: a lone wave per SIMD loses matrix-core cycles to every other instruction
+            // it has to issue in a row.
+            auto fma_group = [&](const V *a, const V *bq, bool first, bool spread) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+#pragma unroll
+                    for (int ti = 0; ti < TH; ++ti)
+#pragma unroll
+                        for (int tj = 0; tj < TH; ++tj) {
+                            const T av_ = reinterpret_cast<const T *>(&a[ti])[q], bv_ = reinterpret_cast<const T *>(&bq[tj])[q];
+                            acc[ti][tj] = (first && q == 0) ? Mfma<T>::run(av_, bv_, (acc_t)(0))
+                                                            : Mfma<T>::run(av_, bv_, acc[ti][tj]);
+                        }
+                if (spread) {
+#pragma unroll
+                    for (int i = 0; i < 2 * TH; ++i) {
+                        __builtin_amdgcn_sched_group_barrier(0x008, TH, 0);  // MFMA
+                        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // LDS read
+                    }
+                    __builtin_amdgcn_sched_group_barrier(0x008, 4 * TH * TH - 2 * TH * TH, 0);
+                }
+            };
+            fetch(a0, b0, 0);
+            if (NG > 1) fetch(a1, b1, 1);
+            fma_group(a0, b0, true, false);  // group 0 starts the accumulators
 #pragma unroll 1
-        for (int kk = 0; kk < NK; kk += 2) {
-            fetch(a1, b1, kk + 1);
-            fma_step(a0, b0);
-            if (kk + 2 < NK) fetch(a0, b0, kk + 2);
-            fma_step(a1, b1);
+            for (int g = 1; g + 1 < NG; g += 2) {
+                fetch(a0, b0, g + 1);
+                fma_group(a1, b1, false, true);
+                fetch(a1, b1, g + 2 < NG ? g + 2 : 0);
+                fma_group(a0, b0, false, true);
+            }
+            if ((NG - 1) % 2 == 1) fma_group(a1, b1, false, false);
+        } else {
+#pragma unroll
+            for (int ti = 0; ti < TH; ++ti)
+#pragma unroll
+                for (int tj = 0; tj < TH; ++tj) acc[ti][tj] = (acc_t)(0);
+            const T *lp = Lb + (16 * (wr * TH) + lj) * LPA + lg;
+            const T *rp = Rb + lg * LPB + 16 * (wc * TH) + lj;
+            constexpr int NK = NP / 4;  // k-steps; even
+            T a0[TH], b0[TH], a1[TH], b1[TH];
+            auto fetch = [&](T *a, T *bq, int kk) {
+#pragma unroll
+                for (int ti = 0; ti < TH; ++ti) a[ti] = row_ok(ti) ? lp[ti * 16 * LPA + 4 * kk] : (T)0;
+#pragma unroll
+                for (int tj = 0; tj < TH; ++tj) bq[tj] = col_ok(tj) ? rp[4 * kk * LPB + tj * 16] : (T)0;
+            };
+            auto fma_step = [&](const T *a, const T *bq) {
+#pragma unroll
+                for (int ti = 0; ti < TH; ++ti)
+#pragma unroll
+                    for (int tj = 0; tj < TH; ++tj)
+                        if (row_ok(ti) && col_ok(tj)) acc[ti][tj] = Mfma<T>::run(a[ti], bq[tj], acc[ti][tj]);
+            };
+            fetch(a0, b0, 0);
+#pragma unroll 1
+            for (int kk = 0; kk < NK; kk += 2) {
+                fetch(a1, b1, kk + 1);
+                fma_step(a0, b0);
+                fetch(a0, b0, kk + 2 < NK ? kk + 2 : 0);
+                fma_step(a1, b1);
+            }
         }
     };
     // visit every element this lane owns: f(ti, tj, v, row, col)
@@ -185,18 +302,43 @@ __global__ __launch_bounds__(NT == 1 ? 64 : 256) void fused_expm_kernel(const T 
                 }
     };
     auto dg = [&](int r, int c) -> T { return (r == c && r < n) ? (T)1 : (T)0; };
+    // Q(r, c) = val(ti, tj, v, r, c) for every element this lane owns.  In the transposed fp32 buffer the four
+    // rows a lane holds of one column are adjacent: one 16-byte store per tile.
+    auto store_right = [&](auto &&val) {
+#pragma unroll
+        for (int ti = 0; ti < TH; ++ti)
+#pragma unroll
+            for (int tj = 0; tj < TH; ++tj)
+                if (row_ok(ti) && col_ok(tj)) {
+                    const int rb = 16 * (wr * TH + ti), c = 16 * (wc * TH + tj) + lj;
+                    if constexpr (kWide) {
+                        typename VecOf<T>::type x;
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) reinterpret_cast<T *>(&x)[v] = val(ti, tj, v, rb + 4 * lg + v, c);
+                        *reinterpret_cast<typename VecOf<T>::type *>(Q + c * LPB + rb + 4 * lg) = x;
+                    } else {
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) {
+                            const int r = rb + Mfma<T>::row(lg, v);
+                            Q[ri(r, c)] = val(ti, tj, v, r, c);
+                        }
+                    }
+                }
+    };
 
     // element-wise state in registers: A, A^2, y02, additive part
     T av[TH][TH][4], a2v[TH][TH][4], yv[TH][TH][4], gv[TH][TH][4];
     for_owned([&](int ti, int tj, int v, int r, int c) {
-        av[ti][tj][v] = P[r * LPA + c];
+        av[ti][tj][v] = P[li(r, c)];
         a2v[ti][tj][v] = (T)0;
     });
+    // the transposed copy; visible after the barriers of the norm below
+    if constexpr (kWide) store_right([&](int ti, int tj, int v, int, int) { return av[ti][tj][v]; });
 
     int m = 0, s = 0, flags = 0;
     // The polynomial X ends in registers xv (aliasing acc's storage is left to the compiler).
     T xv[TH][TH][4];
-    const double n1 = norm1_of_P();
+    const double n1 = norm_regs([&](int ti, int tj, int v) { return av[ti][tj][v]; });
     T a3v[TH][TH][4], a4v[TH][TH][4];  // W^3, W^4 of the Paterson-Stockmeyer variant
     if constexpr (SCHEME == kSchemePS) {
         // Algorithm 3: powers are formed one by one, only as far as the orders tried need them.
@@ -205,36 +347,36 @@ __global__ __launch_bounds__(NT == 1 ? 64 : 256) void fused_expm_kernel(const T 
         bool need_more = false;
         select_ps_order_scaling(nrm, 1, eps, m, s, flags, need_more);
         if (need_more) {
-            product();  // W * W
+            product(P, Q);  // W * W
             __syncthreads();
             for_owned([&](int ti, int tj, int v, int r, int c) {
                 a2v[ti][tj][v] = acc[ti][tj][v];
-                P[r * LPA + c] = acc[ti][tj][v];
+                P[li(r, c)] = acc[ti][tj][v];
             });
             __syncthreads();
-            nrm[1] = norm1_of_P();
+            nrm[1] = norm_regs([&](int ti, int tj, int v) { return a2v[ti][tj][v]; });
             select_ps_order_scaling(nrm, 2, eps, m, s, flags, need_more);
         }
         if (need_more) {
-            product();  // W^2 * W
+            product(P, Q);  // W^2 * W
             __syncthreads();
             for_owned([&](int ti, int tj, int v, int r, int c) {
                 a3v[ti][tj][v] = acc[ti][tj][v];
-                P[r * LPA + c] = acc[ti][tj][v];
+                P[li(r, c)] = acc[ti][tj][v];
             });
             __syncthreads();
-            nrm[2] = norm1_of_P();
+            nrm[2] = norm_regs([&](int ti, int tj, int v) { return a3v[ti][tj][v]; });
             select_ps_order_scaling(nrm, 3, eps, m, s, flags, need_more);
         }
         if (need_more) {
-            product();  // W^3 * W
+            product(P, Q);  // W^3 * W
             __syncthreads();
             for_owned([&](int ti, int tj, int v, int r, int c) {
                 a4v[ti][tj][v] = acc[ti][tj][v];
-                P[r * LPA + c] = acc[ti][tj][v];
+                P[li(r, c)] = acc[ti][tj][v];
             });
             __syncthreads();
-            nrm[3] = norm1_of_P();
+            nrm[3] = norm_regs([&](int ti, int tj, int v) { return a4v[ti][tj][v]; });
             select_ps_order_scaling(nrm, 4, eps, m, s, flags, need_more);
         }
     } else if constexpr (SCHEME == kSchemeBaseline) {
@@ -252,22 +394,22 @@ __global__ __launch_bounds__(NT == 1 ? 64 : 256) void fused_expm_kernel(const T 
             for_owned([&](int ti, int tj, int v, int r, int c) {
                 av[ti][tj][v] *= sg;
                 yv[ti][tj][v] = av[ti][tj][v];
-                P[r * LPA + c] = av[ti][tj][v];   // left operand: the scaled matrix, fixed
-                Q[r * LPB + c] = av[ti][tj][v];   // right operand: the current term Y
+                P[li(r, c)] = av[ti][tj][v];   // left operand: the scaled matrix, fixed
             });
+            store_right([&](int ti, int tj, int v, int, int) { return av[ti][tj][v]; });  // right operand: the term Y
             __syncthreads();
             int k = 2;
             for (int it = 0; it < 256; ++it) {
-                const double ny = norm_of(Q, LPB);
+                const double ny = norm_regs([&](int ti, int tj, int v) { return yv[ti][tj][v]; });
                 if (!(ny > eps)) break;
                 for_owned([&](int ti, int tj, int v, int, int) { xv[ti][tj][v] += yv[ti][tj][v]; });
                 ++m;
-                product();
+                product(P, Q);
                 const T kk = (T)k;
                 for_owned([&](int ti, int tj, int v, int, int) { yv[ti][tj][v] = acc[ti][tj][v] / kk; });
                 ++k;
                 __syncthreads();
-                for_owned([&](int ti, int tj, int v, int r, int c) { Q[r * LPB + c] = yv[ti][tj][v]; });
+                store_right([&](int ti, int tj, int v, int, int) { return yv[ti][tj][v]; });
                 __syncthreads();
             }
         }
@@ -277,14 +419,14 @@ __global__ __launch_bounds__(NT == 1 ? 64 : 256) void fused_expm_kernel(const T 
         const bool finite1 = n1 == n1;
         const bool tiny = finite1 && (n1 == 0.0 || (0.5 * n1 * n1 + (1.0 / 6.0) * n1 * n1 * n1 <= eps));
         if (finite1 && !tiny) {
-            product();  // W * W
+            product(P, Q);  // W * W
             __syncthreads();
             for_owned([&](int ti, int tj, int v, int r, int c) {
                 a2v[ti][tj][v] = acc[ti][tj][v];
-                P[r * LPA + c] = acc[ti][tj][v];
+                P[li(r, c)] = acc[ti][tj][v];
             });
             __syncthreads();
-            n2 = norm1_of_P();
+            n2 = norm_regs([&](int ti, int tj, int v) { return a2v[ti][tj][v]; });
         }
         select_order_scaling(n1, n2, eps, m, s, flags);
     }
@@ -331,17 +473,17 @@ __global__ __launch_bounds__(NT == 1 ? 64 : 256) void fused_expm_kernel(const T 
             for (int r = 0; r <= 4; ++r) cf[r] = r <= j ? (T)inv_factorial((k - 1) * j + r) : (T)0;
             __syncthreads();  // every wave is done with P (norm) before it is overwritten
             for_owned([&](int ti, int tj, int v, int r, int c) {
-                Q[r * LPB + c] = pw(j, ti, tj, v);  // right operand of every Horner step: A^j
                 T h = cf[0] * dg(r, c) + cf[1] * av[ti][tj][v] + cf[2] * a2v[ti][tj][v];
                 if (j >= 3) h += cf[3] * a3v[ti][tj][v];
                 if (j >= 4) h += cf[4] * a4v[ti][tj][v];
-                P[r * LPA + c] = h;              // top block c_{(k-1)j} I + ... + c_m A^j
+                P[li(r, c)] = h;              // top block c_{(k-1)j} I + ... + c_m A^j
             });
+            store_right([&](int ti, int tj, int v, int, int) { return pw(j, ti, tj, v); });  // right operand of every Horner step: A^j
             for (int q = k - 2; q >= 0; --q) {
 #pragma unroll
                 for (int r = 0; r <= 3; ++r) cf[r] = r < j ? (T)inv_factorial(q * j + r) : (T)0;
                 __syncthreads();
-                product();
+                product(P, Q);
                 for_owned([&](int ti, int tj, int v, int r, int c) {
                     T h = acc[ti][tj][v] + cf[0] * dg(r, c) + cf[1] * av[ti][tj][v];
                     if (j >= 3) h += cf[2] * a2v[ti][tj][v];
@@ -350,7 +492,7 @@ __global__ __launch_bounds__(NT == 1 ? 64 : 256) void fused_expm_kernel(const T 
                 });
                 if (q > 0) {
                     __syncthreads();
-                    for_owned([&](int ti, int tj, int v, int r, int c) { P[r * LPA + c] = xv[ti][tj][v]; });
+                    for_owned([&](int ti, int tj, int v, int r, int c) { P[li(r, c)] = xv[ti][tj][v]; });
                 }
             }
         }
@@ -361,7 +503,7 @@ __global__ __launch_bounds__(NT == 1 ? 64 : 256) void fused_expm_kernel(const T 
         for_owned([&](int ti, int tj, int v, int r, int c) {
             av[ti][tj][v] *= sg;
             a2v[ti][tj][v] *= sg2;
-            P[r * LPA + c] = a2v[ti][tj][v];
+            P[li(r, c)] = a2v[ti][tj][v];
         });
     }
 
@@ -377,11 +519,11 @@ __global__ __launch_bounds__(NT == 1 ? 64 : 256) void fused_expm_kernel(const T 
         __syncthreads();  // every wave is done with P (norm) before it is overwritten
         for_owned([&](int ti, int tj, int v, int r, int c) {
             const T a = av[ti][tj][v], a2 = a2v[ti][tj][v];
-            P[r * LPA + c] = (a2 / (T)4 + a) / (T)3 + dg(r, c);
-            Q[r * LPB + c] = a2 / (T)2;
+            P[li(r, c)] = (a2 / (T)4 + a) / (T)3 + dg(r, c);
         });
+        store_right([&](int ti, int tj, int v, int, int) { return a2v[ti][tj][v] / (T)2; });
         __syncthreads();
-        product();
+        product(P, Q);
         for_owned([&](int ti, int tj, int v, int r, int c) { xv[ti][tj][v] = acc[ti][tj][v] + av[ti][tj][v] + dg(r, c); });
     } else {
         const bool hi = m == 15;
@@ -389,19 +531,19 @@ __global__ __launch_bounds__(NT == 1 ? 64 : 256) void fused_expm_kernel(const T 
         const T c3 = (T)(hi ? EXPM_T15_C3 : EXPM_T8_C3), c4 = (T)(hi ? EXPM_T15_C4 : EXPM_T8_C4);
         const T c5 = (T)(hi ? EXPM_T15_C5 : EXPM_T8_C5), c6 = (T)(hi ? EXPM_T15_C6 : EXPM_T8_C6);
         // y02 = A2 * (c1 A2 + c2 A): left operand A2 is already in P
-        for_owned([&](int ti, int tj, int v, int r, int c) { Q[r * LPB + c] = c1 * a2v[ti][tj][v] + c2 * av[ti][tj][v]; });
+        store_right([&](int ti, int tj, int v, int, int) { return c1 * a2v[ti][tj][v] + c2 * av[ti][tj][v]; });
         __syncthreads();
-        product();
+        product(P, Q);
         __syncthreads();
         for_owned([&](int ti, int tj, int v, int r, int c) {
             const T y = acc[ti][tj][v], a = av[ti][tj][v], a2 = a2v[ti][tj][v];
             yv[ti][tj][v] = y;
-            P[r * LPA + c] = y + c3 * a2 + c4 * a;
-            Q[r * LPB + c] = y + c5 * a2;
+            P[li(r, c)] = y + c3 * a2 + c4 * a;
             gv[ti][tj][v] = hi ? c6 * y + (T)EXPM_T15_C7 * a2 : c6 * y + a2 / (T)2 + a + dg(r, c);
         });
+        store_right([&](int ti, int tj, int v, int, int) { return yv[ti][tj][v] + c5 * a2v[ti][tj][v]; });
         __syncthreads();
-        product();
+        product(P, Q);
         if (!hi) {
             for_owned([&](int ti, int tj, int v, int, int) { xv[ti][tj][v] = acc[ti][tj][v] + gv[ti][tj][v]; });
         } else {
@@ -409,15 +551,18 @@ __global__ __launch_bounds__(NT == 1 ? 64 : 256) void fused_expm_kernel(const T 
                     c12 = (T)EXPM_T15_C12, c13 = (T)EXPM_T15_C13, c14 = (T)EXPM_T15_C14, c15 = (T)EXPM_T15_C15,
                     c16 = (T)EXPM_T15_C16;
             __syncthreads();
+            store_right([&](int ti, int tj, int v, int, int) {
+                const T y1 = acc[ti][tj][v] + gv[ti][tj][v];  // y12
+                return y1 + c10 * yv[ti][tj][v] + c11 * av[ti][tj][v];
+            });
             for_owned([&](int ti, int tj, int v, int r, int c) {
                 const T a = av[ti][tj][v], a2 = a2v[ti][tj][v], y0 = yv[ti][tj][v];
                 const T y1 = acc[ti][tj][v] + gv[ti][tj][v];  // y12
-                P[r * LPA + c] = y1 + c8 * a2 + c9 * a;
-                Q[r * LPB + c] = y1 + c10 * y0 + c11 * a;
+                P[li(r, c)] = y1 + c8 * a2 + c9 * a;
                 gv[ti][tj][v] = c12 * y1 + c13 * y0 + c14 * a2 + c15 * a + c16 * dg(r, c);
             });
             __syncthreads();
-            product();
+            product(P, Q);
             for_owned([&](int ti, int tj, int v, int, int) { xv[ti][tj][v] = acc[ti][tj][v] + gv[ti][tj][v]; });
         }
     }
@@ -427,18 +572,16 @@ __global__ __launch_bounds__(NT == 1 ? 64 : 256) void fused_expm_kernel(const T 
     // ---- squaring phase: X in both operand layouts, product, repeat ------------------------------------
     for (int q = 0; q < s; ++q) {
         __syncthreads();
-        for_owned([&](int ti, int tj, int v, int r, int c) {
-            P[r * LPA + c] = xv[ti][tj][v];
-            Q[r * LPB + c] = xv[ti][tj][v];
-        });
+        for_owned([&](int ti, int tj, int v, int r, int c) { P[li(r, c)] = xv[ti][tj][v]; });
+        store_right([&](int ti, int tj, int v, int, int) { return xv[ti][tj][v]; });
         __syncthreads();
-        product();
+        product(P, Q);
         for_owned([&](int ti, int tj, int v, int, int) { xv[ti][tj][v] = acc[ti][tj][v]; });
     }
 
     // ---- store through P so that global writes are whole rows -----------------------------------------
     __syncthreads();
-    for_owned([&](int ti, int tj, int v, int r, int c) { P[r * LPA + c] = xv[ti][tj][v]; });
+    for_owned([&](int ti, int tj, int v, int r, int c) { P[li(r, c)] = xv[ti][tj][v]; });
     __syncthreads();
     if (vec_ok) {
         using V = typename VecOf<T>::type;
@@ -446,13 +589,13 @@ __global__ __launch_bounds__(NT == 1 ? 64 : 256) void fused_expm_kernel(const T 
 #pragma unroll 4
         for (int e = tid; e < total; e += C::kThreads) {
             const int r = e / vpr, c = (e - r * vpr) * VN;
-            *reinterpret_cast<V *>(O + (size_t)r * n + c) = *reinterpret_cast<const V *>(P + r * LPA + c);
+            *reinterpret_cast<V *>(O + (size_t)r * n + c) = *reinterpret_cast<const V *>(P + li(r, c));
         }
     } else {
 #pragma unroll 4
         for (int e = tid; e < n * n; e += C::kThreads) {
             const int r = e / n, c = e - r * n;
-            O[e] = P[r * LPA + c];
+            O[e] = P[li(r, c)];
         }
     }
 }
