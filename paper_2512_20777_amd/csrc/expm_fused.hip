@@ -37,8 +37,13 @@ template <typename T, int NT> struct FusedCfg {
     static constexpr int LPB = kWide ? NPP + 4 : (NT % 2 == 0 ? NP + 16 : NP);
     static constexpr int kBytesP = kRows * LPA * (int)sizeof(T);
     static constexpr int kBytesQ = kRows * LPB * (int)sizeof(T);
-    static constexpr int kLds = kBytesP + kBytesQ + (kThreads + 16) * (int)sizeof(double);
-    static_assert(kLds <= 163840, "fused path exceeds the LDS of one compute unit");
+    // Single-wave matrices are packed four to a workgroup (one wave each, nothing shared between them):
+    // fewer, larger workgroups start faster than four times as many one-wave ones.
+    static constexpr int kMPW = NT == 1 ? 4 : 1;
+    static constexpr int kBlock = kThreads * kMPW;
+    static constexpr int kLdsPer = kBytesP + kBytesQ + (kThreads + 16) * (int)sizeof(double);
+    static constexpr int kLds = kLdsPer * kMPW;
+    static_assert(kLdsPer % 16 == 0 && kLds <= 163840, "fused path exceeds the LDS of one compute unit");
 };
 
 template <typename T> struct VecOf;
@@ -69,22 +74,37 @@ __device__ __forceinline__ double pow2neg_f(int e)
 }
 
 template <typename T, int NT, int SCHEME>
-__global__ __launch_bounds__(NT == 1 ? 64 : 256) void fused_expm_kernel(const T *__restrict__ Ain, T *__restrict__ Out,
-                                                                        int n, double eps, int select_only,
-                                                                        int norm_inf, MatInfo *__restrict__ info)
+__global__ __launch_bounds__(256) void fused_expm_kernel(const T *__restrict__ Ain, T *__restrict__ Out, int n, int batch,
+                                                         double eps, int select_only, int norm_inf,
+                                                         MatInfo *__restrict__ info)
 {
     using C = FusedCfg<T, NT>;
     using acc_t = typename Mfma<T>::acc_t;
     constexpr int NP = C::NP, LPA = C::LPA, LPB = C::LPB, TH = C::TH, WG = C::WG, NR = C::kRows;
     constexpr bool kWide = C::kWide;
-    extern __shared__ __align__(16) unsigned char smem_raw[];
+    extern __shared__ __align__(16) unsigned char smem_all[];
+    // matrix of this wave (packed single-wave case) or of this workgroup
+    const int slot = C::kMPW > 1 ? __builtin_amdgcn_readfirstlane(threadIdx.x >> 6) : 0;
+    const int b = blockIdx.x * C::kMPW + slot;
+    if (b >= batch) return;  // a whole wave of a packed workgroup; those synchronise per wave only (sync below)
+    unsigned char *smem_raw = smem_all + slot * C::kLdsPer;
     T *P = reinterpret_cast<T *>(smem_raw);                         // left operand layout
     T *Q = reinterpret_cast<T *>(smem_raw + C::kBytesP);            // right operand layout
     double *red = reinterpret_cast<double *>(smem_raw + C::kBytesP + C::kBytesQ);
+    // Barrier between the phases of one matrix.  A single wave runs its LDS instructions in order, so it
+    // only has to keep the compiler from moving accesses across this point.
+    auto sync = [&]() {
+        if constexpr (NT == 1) {
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        } else {
+            __syncthreads();
+        }
+    };
 
-    const int b = blockIdx.x;
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform, kept in a scalar register
+    const int tid = C::kMPW > 1 ? (int)(threadIdx.x & 63) : (int)threadIdx.x, lane = tid & 63;
+    const int wave = C::kMPW > 1 ? 0 : __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform, in a scalar register
     const int wr = wave / WG, wc = wave % WG;
     constexpr bool kAllTiles = kWide || NT % WG == 0;  // every wave computes a full TH x TH block
     auto row_ok = [&](int ti) -> bool { return kAllTiles || wr * TH + ti < NT; };
@@ -109,26 +129,31 @@ __global__ __launch_bounds__(NT == 1 ? 64 : 256) void fused_expm_kernel(const T 
         }
     }
     // (the transposed copy of the fp32 path is written further down, from registers)
+    // Threads walk the padded rows (a compile-time width, so no division by n); columns past n are skipped.
+    constexpr int CV = NR / VN;
     if (vec_ok) {
         using V = typename VecOf<T>::type;
-        const int vpr = n / VN, total = n * vpr;
 #pragma unroll(NT >= 4 ? 16 : (NT >= 2 ? 4 : 1))  // all of a thread's loads in flight at once
-        for (int e = tid; e < total; e += C::kThreads) {
-            const int r = e / vpr, c = (e - r * vpr) * VN;
-            const V x = *reinterpret_cast<const V *>(W + (size_t)r * n + c);
-            *reinterpret_cast<V *>(P + li(r, c)) = x;
-            if constexpr (!kWide) *reinterpret_cast<V *>(Q + ri(r, c)) = x;
+        for (int e = tid; e < n * CV; e += C::kThreads) {
+            const int r = e / CV, c = (e - r * CV) * VN;
+            if (c < n) {
+                const V x = *reinterpret_cast<const V *>(W + (size_t)r * n + c);
+                *reinterpret_cast<V *>(P + li(r, c)) = x;
+                if constexpr (!kWide) *reinterpret_cast<V *>(Q + ri(r, c)) = x;
+            }
         }
     } else {
 #pragma unroll 4
-        for (int e = tid; e < n * n; e += C::kThreads) {
-            const int r = e / n, c = e - r * n;
-            const T x = W[e];
-            P[li(r, c)] = x;
-            if constexpr (!kWide) Q[ri(r, c)] = x;
+        for (int e = tid; e < n * NR; e += C::kThreads) {
+            const int r = e / NR, c = e - r * NR;
+            if (c < n) {
+                const T x = W[(size_t)r * n + c];
+                P[li(r, c)] = x;
+                if constexpr (!kWide) Q[ri(r, c)] = x;
+            }
         }
     }
-    __syncthreads();
+    sync();
 
     // ---- norm of a matrix held in registers in the result layout, get(ti, tj, v) -> element: max column
     // abs-sum (1-norm) or, with norm_inf, max row abs-sum; sums in double, NaN if not finite.  Each wave adds
@@ -162,7 +187,7 @@ __global__ __launch_bounds__(NT == 1 ? 64 : 256) void fused_expm_kernel(const T 
             mx = mxop(mx, __shfl_xor(mx, 32));
             return __any(bad) ? __longlong_as_double(0x7ff8000000000000LL) : mx;
         }
-        __syncthreads();  // red[] free to overwrite
+        sync();  // red[] free to overwrite
         if (!norm_inf) {
 #pragma unroll
             for (int tj = 0; tj < TH; ++tj) {
@@ -190,7 +215,7 @@ __global__ __launch_bounds__(NT == 1 ? 64 : 256) void fused_expm_kernel(const T 
                     if (lj == 0) red[wc * L + 16 * (wr * TH + ti) + Mfma<T>::row(lg, v)] = sum;
                 }
         }
-        __syncthreads();
+        sync();
         double mx = 0.0;
         int bad = 0;
         for (int line = lane; line < L; line += 64) {
@@ -348,34 +373,34 @@ __global__ __launch_bounds__(NT == 1 ? 64 : 256) void fused_expm_kernel(const T 
         select_ps_order_scaling(nrm, 1, eps, m, s, flags, need_more);
         if (need_more) {
             product(P, Q);  // W * W
-            __syncthreads();
+            sync();
             for_owned([&](int ti, int tj, int v, int r, int c) {
                 a2v[ti][tj][v] = acc[ti][tj][v];
                 P[li(r, c)] = acc[ti][tj][v];
             });
-            __syncthreads();
+            sync();
             nrm[1] = norm_regs([&](int ti, int tj, int v) { return a2v[ti][tj][v]; });
             select_ps_order_scaling(nrm, 2, eps, m, s, flags, need_more);
         }
         if (need_more) {
             product(P, Q);  // W^2 * W
-            __syncthreads();
+            sync();
             for_owned([&](int ti, int tj, int v, int r, int c) {
                 a3v[ti][tj][v] = acc[ti][tj][v];
                 P[li(r, c)] = acc[ti][tj][v];
             });
-            __syncthreads();
+            sync();
             nrm[2] = norm_regs([&](int ti, int tj, int v) { return a3v[ti][tj][v]; });
             select_ps_order_scaling(nrm, 3, eps, m, s, flags, need_more);
         }
         if (need_more) {
             product(P, Q);  // W^3 * W
-            __syncthreads();
+            sync();
             for_owned([&](int ti, int tj, int v, int r, int c) {
                 a4v[ti][tj][v] = acc[ti][tj][v];
                 P[li(r, c)] = acc[ti][tj][v];
             });
-            __syncthreads();
+            sync();
             nrm[3] = norm_regs([&](int ti, int tj, int v) { return a4v[ti][tj][v]; });
             select_ps_order_scaling(nrm, 4, eps, m, s, flags, need_more);
         }
@@ -390,14 +415,14 @@ __global__ __launch_bounds__(NT == 1 ? 64 : 256) void fused_expm_kernel(const T 
             double t = n1;
             while (!(t < 0.5)) { t *= 0.5; ++s; }
             const T sg = (T)ldexp(1.0, -s);
-            __syncthreads();
+            sync();
             for_owned([&](int ti, int tj, int v, int r, int c) {
                 av[ti][tj][v] *= sg;
                 yv[ti][tj][v] = av[ti][tj][v];
                 P[li(r, c)] = av[ti][tj][v];   // left operand: the scaled matrix, fixed
             });
             store_right([&](int ti, int tj, int v, int, int) { return av[ti][tj][v]; });  // right operand: the term Y
-            __syncthreads();
+            sync();
             int k = 2;
             for (int it = 0; it < 256; ++it) {
                 const double ny = norm_regs([&](int ti, int tj, int v) { return yv[ti][tj][v]; });
@@ -408,9 +433,9 @@ __global__ __launch_bounds__(NT == 1 ? 64 : 256) void fused_expm_kernel(const T 
                 const T kk = (T)k;
                 for_owned([&](int ti, int tj, int v, int, int) { yv[ti][tj][v] = acc[ti][tj][v] / kk; });
                 ++k;
-                __syncthreads();
+                sync();
                 store_right([&](int ti, int tj, int v, int, int) { return yv[ti][tj][v]; });
-                __syncthreads();
+                sync();
             }
         }
     } else {
@@ -420,12 +445,12 @@ __global__ __launch_bounds__(NT == 1 ? 64 : 256) void fused_expm_kernel(const T 
         const bool tiny = finite1 && (n1 == 0.0 || (0.5 * n1 * n1 + (1.0 / 6.0) * n1 * n1 * n1 <= eps));
         if (finite1 && !tiny) {
             product(P, Q);  // W * W
-            __syncthreads();
+            sync();
             for_owned([&](int ti, int tj, int v, int r, int c) {
                 a2v[ti][tj][v] = acc[ti][tj][v];
                 P[li(r, c)] = acc[ti][tj][v];
             });
-            __syncthreads();
+            sync();
             n2 = norm_regs([&](int ti, int tj, int v) { return a2v[ti][tj][v]; });
         }
         select_order_scaling(n1, n2, eps, m, s, flags);
@@ -471,7 +496,7 @@ __global__ __launch_bounds__(NT == 1 ? 64 : 256) void fused_expm_kernel(const T 
             T cf[5];
 #pragma unroll
             for (int r = 0; r <= 4; ++r) cf[r] = r <= j ? (T)inv_factorial((k - 1) * j + r) : (T)0;
-            __syncthreads();  // every wave is done with P (norm) before it is overwritten
+            sync();  // every wave is done with P (norm) before it is overwritten
             for_owned([&](int ti, int tj, int v, int r, int c) {
                 T h = cf[0] * dg(r, c) + cf[1] * av[ti][tj][v] + cf[2] * a2v[ti][tj][v];
                 if (j >= 3) h += cf[3] * a3v[ti][tj][v];
@@ -482,7 +507,7 @@ __global__ __launch_bounds__(NT == 1 ? 64 : 256) void fused_expm_kernel(const T 
             for (int q = k - 2; q >= 0; --q) {
 #pragma unroll
                 for (int r = 0; r <= 3; ++r) cf[r] = r < j ? (T)inv_factorial(q * j + r) : (T)0;
-                __syncthreads();
+                sync();
                 product(P, Q);
                 for_owned([&](int ti, int tj, int v, int r, int c) {
                     T h = acc[ti][tj][v] + cf[0] * dg(r, c) + cf[1] * av[ti][tj][v];
@@ -491,7 +516,7 @@ __global__ __launch_bounds__(NT == 1 ? 64 : 256) void fused_expm_kernel(const T 
                     xv[ti][tj][v] = h;
                 });
                 if (q > 0) {
-                    __syncthreads();
+                    sync();
                     for_owned([&](int ti, int tj, int v, int r, int c) { P[li(r, c)] = xv[ti][tj][v]; });
                 }
             }
@@ -516,13 +541,13 @@ __global__ __launch_bounds__(NT == 1 ? 64 : 256) void fused_expm_kernel(const T 
         });
     } else if (m == 4) {
         // T4 = ((A2/4 + A)/3 + I) * (A2/2) + A + I
-        __syncthreads();  // every wave is done with P (norm) before it is overwritten
+        sync();  // every wave is done with P (norm) before it is overwritten
         for_owned([&](int ti, int tj, int v, int r, int c) {
             const T a = av[ti][tj][v], a2 = a2v[ti][tj][v];
             P[li(r, c)] = (a2 / (T)4 + a) / (T)3 + dg(r, c);
         });
         store_right([&](int ti, int tj, int v, int, int) { return a2v[ti][tj][v] / (T)2; });
-        __syncthreads();
+        sync();
         product(P, Q);
         for_owned([&](int ti, int tj, int v, int r, int c) { xv[ti][tj][v] = acc[ti][tj][v] + av[ti][tj][v] + dg(r, c); });
     } else {
@@ -532,9 +557,9 @@ __global__ __launch_bounds__(NT == 1 ? 64 : 256) void fused_expm_kernel(const T 
         const T c5 = (T)(hi ? EXPM_T15_C5 : EXPM_T8_C5), c6 = (T)(hi ? EXPM_T15_C6 : EXPM_T8_C6);
         // y02 = A2 * (c1 A2 + c2 A): left operand A2 is already in P
         store_right([&](int ti, int tj, int v, int, int) { return c1 * a2v[ti][tj][v] + c2 * av[ti][tj][v]; });
-        __syncthreads();
+        sync();
         product(P, Q);
-        __syncthreads();
+        sync();
         for_owned([&](int ti, int tj, int v, int r, int c) {
             const T y = acc[ti][tj][v], a = av[ti][tj][v], a2 = a2v[ti][tj][v];
             yv[ti][tj][v] = y;
@@ -542,7 +567,7 @@ __global__ __launch_bounds__(NT == 1 ? 64 : 256) void fused_expm_kernel(const T 
             gv[ti][tj][v] = hi ? c6 * y + (T)EXPM_T15_C7 * a2 : c6 * y + a2 / (T)2 + a + dg(r, c);
         });
         store_right([&](int ti, int tj, int v, int, int) { return yv[ti][tj][v] + c5 * a2v[ti][tj][v]; });
-        __syncthreads();
+        sync();
         product(P, Q);
         if (!hi) {
             for_owned([&](int ti, int tj, int v, int, int) { xv[ti][tj][v] = acc[ti][tj][v] + gv[ti][tj][v]; });
@@ -550,7 +575,7 @@ __global__ __launch_bounds__(NT == 1 ? 64 : 256) void fused_expm_kernel(const T 
             const T c8 = (T)EXPM_T15_C8, c9 = (T)EXPM_T15_C9, c10 = (T)EXPM_T15_C10, c11 = (T)EXPM_T15_C11,
                     c12 = (T)EXPM_T15_C12, c13 = (T)EXPM_T15_C13, c14 = (T)EXPM_T15_C14, c15 = (T)EXPM_T15_C15,
                     c16 = (T)EXPM_T15_C16;
-            __syncthreads();
+            sync();
             store_right([&](int ti, int tj, int v, int, int) {
                 const T y1 = acc[ti][tj][v] + gv[ti][tj][v];  // y12
                 return y1 + c10 * yv[ti][tj][v] + c11 * av[ti][tj][v];
@@ -561,7 +586,7 @@ __global__ __launch_bounds__(NT == 1 ? 64 : 256) void fused_expm_kernel(const T 
                 P[li(r, c)] = y1 + c8 * a2 + c9 * a;
                 gv[ti][tj][v] = c12 * y1 + c13 * y0 + c14 * a2 + c15 * a + c16 * dg(r, c);
             });
-            __syncthreads();
+            sync();
             product(P, Q);
             for_owned([&](int ti, int tj, int v, int, int) { xv[ti][tj][v] = acc[ti][tj][v] + gv[ti][tj][v]; });
         }
@@ -571,31 +596,30 @@ __global__ __launch_bounds__(NT == 1 ? 64 : 256) void fused_expm_kernel(const T 
 
     // ---- squaring phase: X in both operand layouts, product, repeat ------------------------------------
     for (int q = 0; q < s; ++q) {
-        __syncthreads();
+        sync();
         for_owned([&](int ti, int tj, int v, int r, int c) { P[li(r, c)] = xv[ti][tj][v]; });
         store_right([&](int ti, int tj, int v, int, int) { return xv[ti][tj][v]; });
-        __syncthreads();
+        sync();
         product(P, Q);
         for_owned([&](int ti, int tj, int v, int, int) { xv[ti][tj][v] = acc[ti][tj][v]; });
     }
 
     // ---- store through P so that global writes are whole rows -----------------------------------------
-    __syncthreads();
+    sync();
     for_owned([&](int ti, int tj, int v, int r, int c) { P[li(r, c)] = xv[ti][tj][v]; });
-    __syncthreads();
+    sync();
     if (vec_ok) {
         using V = typename VecOf<T>::type;
-        const int vpr = n / VN, total = n * vpr;
 #pragma unroll 4
-        for (int e = tid; e < total; e += C::kThreads) {
-            const int r = e / vpr, c = (e - r * vpr) * VN;
-            *reinterpret_cast<V *>(O + (size_t)r * n + c) = *reinterpret_cast<const V *>(P + li(r, c));
+        for (int e = tid; e < n * CV; e += C::kThreads) {
+            const int r = e / CV, c = (e - r * CV) * VN;
+            if (c < n) *reinterpret_cast<V *>(O + (size_t)r * n + c) = *reinterpret_cast<const V *>(P + li(r, c));
         }
     } else {
 #pragma unroll 4
-        for (int e = tid; e < n * n; e += C::kThreads) {
-            const int r = e / n, c = e - r * n;
-            O[e] = P[li(r, c)];
+        for (int e = tid; e < n * NR; e += C::kThreads) {
+            const int r = e / NR, c = e - r * NR;
+            if (c < n) O[(size_t)r * n + c] = P[li(r, c)];
         }
     }
 }
@@ -612,8 +636,9 @@ hipError_t launch_fused_t(const void *A, void *out, int n, int batch, double eps
         if (e != hipSuccess) return e;
         attr_done = true;
     }
-    hipLaunchKernelGGL((fused_expm_kernel<T, NT, SCHEME>), dim3(batch), dim3(C::kThreads), C::kLds, stream,
-                       reinterpret_cast<const T *>(A), reinterpret_cast<T *>(out), n, eps, select_only, norm_inf, info);
+    hipLaunchKernelGGL((fused_expm_kernel<T, NT, SCHEME>), dim3((batch + C::kMPW - 1) / C::kMPW), dim3(C::kBlock), C::kLds,
+                       stream, reinterpret_cast<const T *>(A), reinterpret_cast<T *>(out), n, batch, eps, select_only,
+                       norm_inf, info);
     return hipGetLastError();
 }
 
