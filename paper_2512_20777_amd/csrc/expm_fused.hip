@@ -624,6 +624,284 @@ __global__ __launch_bounds__(256) void fused_expm_kernel(const T *__restrict__ A
     }
 }
 
+// ---------------------------------------------------------------------------------------------------
+// Matrices of at most one MFMA tile (n <= 16): one wave per matrix, everything in registers, no LDS.
+//
+// Every matrix M of the computation is held twice, in the MFMA result layout: h[v] = M(row(g,v), j) and
+// t[v] = M(j, row(g,v)) = M^T in the same layout (lane = 16 g + j).  With the k index of step q of a
+// product taken as row(g,q), t of the left factor is exactly the left-operand fragment and h of the right
+// factor the right-operand fragment, so  D = L R  is  D.h = sum_q mfma(L.t[q], R.h[q])  and, because
+// D^T = R^T L^T,  D.t = sum_q mfma(R.h[q], L.t[q]).  Both forms of the result come out of the matrix cores
+// in the layout they are needed in next; nothing is transposed through memory.  The 1-norm is taken from
+// h (column j is summed within the lane and across the four lane groups), the infinity norm from t.
+// Four matrices share a workgroup (one wave each, nothing in common).
+// ---------------------------------------------------------------------------------------------------
+template <typename T> struct Pair {
+    T h[4], t[4];
+};
+
+template <typename T, int SCHEME>
+__global__ __launch_bounds__(256) void fused_tile_kernel(const T *__restrict__ Ain, T *__restrict__ Out, int n, int batch,
+                                                         double eps, int select_only, int norm_inf,
+                                                         MatInfo *__restrict__ info)
+{
+    using acc_t = typename Mfma<T>::acc_t;
+    using M = Pair<T>;
+    const int b = blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    if (b >= batch) return;
+    const int lane = threadIdx.x & 63, lj = lane & 15, lg = lane >> 4;
+    const size_t moff = (size_t)b * n * n;
+    const T *W = Ain + moff;
+    int rw[4];
+    bool in[4];  // element (rw[v], lj) -- and (lj, rw[v]) -- lies inside the n x n matrix
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+        rw[v] = Mfma<T>::row(lg, v);
+        in[v] = rw[v] < n && lj < n;
+    }
+    auto each = [&](auto &&f) {
+#pragma unroll
+        for (int v = 0; v < 4; ++v) f(v);
+    };
+    // D = L * R in both forms; the transposed form is skipped (left equal to h) when nothing multiplies D again
+    auto mul = [&](const M &L, const M &R, bool both = true) -> M {
+        acc_t dh = (acc_t)(0), dt = (acc_t)(0);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) dh = Mfma<T>::run(L.t[q], R.h[q], dh);
+        if (both) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) dt = Mfma<T>::run(R.h[q], L.t[q], dt);
+        }
+        M d;
+        each([&](int v) { d.h[v] = dh[v]; d.t[v] = both ? dt[v] : dh[v]; });
+        return d;
+    };
+    // e = f(x.., identity) applied to both forms; the identity is symmetric
+    T dgv[4];
+    each([&](int v) { dgv[v] = (rw[v] == lj && lj < n) ? (T)1 : (T)0; });
+    // max column abs-sum of the matrix whose result-layout registers are x (double sums, NaN if not finite)
+    auto colnorm = [&](const T (&x)[4]) -> double {
+        double sum = 0.0;
+        each([&](int v) { sum += fabs((double)x[v]); });
+        sum += __shfl_xor(sum, 16);
+        sum += __shfl_xor(sum, 32);  // column lj, complete in every lane
+        const int bad = !(sum <= 1.7976931348623157e308);
+        double mx = bad ? 0.0 : sum;
+        mx = row16_allreduce(mx, [](double a, double c) { return c > a ? c : a; });
+        return __any(bad) ? __longlong_as_double(0x7ff8000000000000LL) : mx;
+    };
+    auto norm = [&](const M &x) -> double { return norm_inf ? colnorm(x.t) : colnorm(x.h); };
+
+    // W is read once, in the form whose loads are whole row segments (rows rw[v], 16 consecutive columns);
+    // indices past n are clamped and the value dropped, so no load is predicated.  The transposed form
+    // comes from the matrix cores: with h as the left-operand fragment and the identity on the right,
+    // sum_q mfma(h[q], I[q]) is W^T I in the result layout (exact: products with 1 and sums with 0).
+    M w;
+    {
+        const int cj = lj < n ? lj : n - 1;
+        T ld[4];
+        each([&](int v) { ld[v] = W[(size_t)(rw[v] < n ? rw[v] : n - 1) * n + cj]; });
+        each([&](int v) { w.h[v] = in[v] ? ld[v] : (T)0; });
+        acc_t tt = (acc_t)(0);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) tt = Mfma<T>::run(w.h[q], (rw[q] == lj ? (T)1 : (T)0), tt);
+        each([&](int v) { w.t[v] = tt[v]; });
+    }
+
+    int m = 0, s = 0, flags = 0;
+    M w2, w3, w4, x;
+    each([&](int v) { w2.h[v] = w2.t[v] = w3.h[v] = w3.t[v] = w4.h[v] = w4.t[v] = (T)0; x.h[v] = x.t[v] = dgv[v]; });
+    const double n1 = norm(w);
+    if constexpr (SCHEME == kSchemePS) {
+        // Algorithm 3: powers are formed one by one, only as far as the orders tried need them
+        double nrm[4] = {n1, 0.0, 0.0, 0.0};
+        bool need_more = false;
+        select_ps_order_scaling(nrm, 1, eps, m, s, flags, need_more);
+        if (need_more) {
+            w2 = mul(w, w);
+            nrm[1] = norm(w2);
+            select_ps_order_scaling(nrm, 2, eps, m, s, flags, need_more);
+        }
+        if (need_more) {
+            w3 = mul(w2, w);
+            nrm[2] = norm(w3);
+            select_ps_order_scaling(nrm, 3, eps, m, s, flags, need_more);
+        }
+        if (need_more) {
+            w4 = mul(w3, w);
+            nrm[3] = norm(w4);
+            select_ps_order_scaling(nrm, 4, eps, m, s, flags, need_more);
+        }
+    } else if constexpr (SCHEME == kSchemeBaseline) {
+        // The comparison baseline of the paper (its Algorithm 1): s from ||W|| / 2^s < 1/2, then Taylor terms
+        // Y <- W Y / k are added while ||Y|| > eps; x holds X when the loop is done.
+        if (!(n1 <= 1.7976931348623157e308)) {
+            m = -1; s = -1; flags = 1;
+        } else if (n1 > 0.0) {
+            double tt = n1;
+            while (!(tt < 0.5)) { tt *= 0.5; ++s; }
+            const T sg = (T)ldexp(1.0, -s);
+            each([&](int v) { w.h[v] *= sg; w.t[v] *= sg; });
+            M y = w;
+            int k = 2;
+            for (int it = 0; it < 256; ++it) {
+                const double ny = norm(y);
+                if (!(ny > eps)) break;
+                each([&](int v) { x.h[v] += y.h[v]; x.t[v] += y.t[v]; });
+                ++m;
+                const M p = mul(w, y);
+                const T kk = (T)k;
+                each([&](int v) { y.h[v] = p.h[v] / kk; y.t[v] = p.t[v] / kk; });
+                ++k;
+            }
+        }
+    } else {
+        double n2 = 0.0;
+        // orders 0 and 1 need no product: Algorithm 4 forms W^2 only once the m = 1 test has failed
+        const bool finite1 = n1 == n1;
+        const bool tiny = finite1 && (n1 == 0.0 || (0.5 * n1 * n1 + (1.0 / 6.0) * n1 * n1 * n1 <= eps));
+        if (finite1 && !tiny) {
+            w2 = mul(w, w);
+            n2 = norm(w2);
+        }
+        select_order_scaling(n1, n2, eps, m, s, flags);
+    }
+    if (lane == 0) {
+        MatInfo mi;
+        mi.m = m; mi.s = s; mi.len = 0; mi.flags = flags;
+        info[b] = mi;
+    }
+    if (select_only) return;
+    T *O = Out + moff;
+    if (m < 0) {
+        const T qnan = (T)__longlong_as_double(0x7ff8000000000000LL);
+        each([&](int v) { if (in[v]) O[(size_t)rw[v] * n + lj] = qnan; });
+        return;
+    }
+
+    // f(h-or-t registers...) on both forms
+    if constexpr (SCHEME == kSchemeBaseline) {
+        // nothing left to evaluate: the term loop above produced X
+    } else if constexpr (SCHEME == kSchemePS) {
+        // ---- Paterson-Stockmeyer: T_m(A) = Horner in A^j with blocks of degree < j, m = j*k -----------------
+        const int j = ps_j(m), k = ps_k(m);
+        if (s > 0) {
+            const T sg = (T)pow2neg_f(s), sg2 = (T)pow2neg_f(2 * s), sg3 = (T)pow2neg_f(3 * s), sg4 = (T)pow2neg_f(4 * s);
+            each([&](int v) {
+                w.h[v] *= sg; w.t[v] *= sg;
+                w2.h[v] *= sg2; w2.t[v] *= sg2;
+                w3.h[v] *= sg3; w3.t[v] *= sg3;
+                w4.h[v] *= sg4; w4.t[v] *= sg4;
+            });
+        }
+        if (k == 1) {  // orders 0, 1, 2: no further product
+            each([&](int v) {
+                T xh = dgv[v], xt = dgv[v];
+                if (m >= 1) { xh += w.h[v]; xt += w.t[v]; }
+                if (m == 2) { xh += w2.h[v] / (T)2; xt += w2.t[v] / (T)2; }
+                x.h[v] = xh; x.t[v] = xt;
+            });
+        } else {
+            const M &aj = j == 2 ? w2 : (j == 3 ? w3 : w4);  // right operand of every Horner step: A^j
+            T cf[5];
+#pragma unroll
+            for (int r = 0; r <= 4; ++r) cf[r] = r <= j ? (T)inv_factorial((k - 1) * j + r) : (T)0;
+            M hcur;  // top block c_{(k-1)j} I + ... + c_m A^j
+            each([&](int v) {
+                hcur.h[v] = cf[0] * dgv[v] + cf[1] * w.h[v] + cf[2] * w2.h[v] + cf[3] * w3.h[v] + cf[4] * w4.h[v];
+                hcur.t[v] = cf[0] * dgv[v] + cf[1] * w.t[v] + cf[2] * w2.t[v] + cf[3] * w3.t[v] + cf[4] * w4.t[v];
+            });
+            for (int q = k - 2; q >= 0; --q) {
+#pragma unroll
+                for (int r = 0; r <= 3; ++r) cf[r] = r < j ? (T)inv_factorial(q * j + r) : (T)0;
+                const M p = mul(hcur, aj, q > 0 || s > 0);
+                each([&](int v) {
+                    hcur.h[v] = p.h[v] + cf[0] * dgv[v] + cf[1] * w.h[v] + cf[2] * w2.h[v] + cf[3] * w3.h[v];
+                    hcur.t[v] = p.t[v] + cf[0] * dgv[v] + cf[1] * w.t[v] + cf[2] * w2.t[v] + cf[3] * w3.t[v];
+                });
+            }
+            x = hcur;
+        }
+    } else {
+        // ---- scale: A = W / 2^s, A2 = W2 / 4^s (exact) ---------------------------------------------------
+        if (s > 0) {
+            const T sg = (T)pow2neg_f(s), sg2 = (T)pow2neg_f(2 * s);
+            each([&](int v) { w.h[v] *= sg; w.t[v] *= sg; w2.h[v] *= sg2; w2.t[v] *= sg2; });
+        }
+        const M &a = w, &a2 = w2;
+        if (m <= 2) {
+            each([&](int v) {
+                T xh = dgv[v], xt = dgv[v];
+                if (m >= 1) { xh += a.h[v]; xt += a.t[v]; }
+                if (m == 2) { xh += a2.h[v] / (T)2; xt += a2.t[v] / (T)2; }
+                x.h[v] = xh; x.t[v] = xt;
+            });
+        } else if (m == 4) {
+            // T4 = ((A2/4 + A)/3 + I) * (A2/2) + A + I
+            M L, R;
+            each([&](int v) {
+                L.h[v] = (a2.h[v] / (T)4 + a.h[v]) / (T)3 + dgv[v];
+                L.t[v] = (a2.t[v] / (T)4 + a.t[v]) / (T)3 + dgv[v];
+                R.h[v] = a2.h[v] / (T)2;
+                R.t[v] = a2.t[v] / (T)2;
+            });
+            const M p = mul(L, R, s > 0);
+            each([&](int v) { x.h[v] = p.h[v] + a.h[v] + dgv[v]; x.t[v] = p.t[v] + a.t[v] + dgv[v]; });
+        } else {
+            const bool hi = m == 15;
+            const T c1 = (T)(hi ? EXPM_T15_C1 : EXPM_T8_C1), c2 = (T)(hi ? EXPM_T15_C2 : EXPM_T8_C2);
+            const T c3 = (T)(hi ? EXPM_T15_C3 : EXPM_T8_C3), c4 = (T)(hi ? EXPM_T15_C4 : EXPM_T8_C4);
+            const T c5 = (T)(hi ? EXPM_T15_C5 : EXPM_T8_C5), c6 = (T)(hi ? EXPM_T15_C6 : EXPM_T8_C6);
+            // y02 = A2 * (c1 A2 + c2 A)
+            M R;
+            each([&](int v) { R.h[v] = c1 * a2.h[v] + c2 * a.h[v]; R.t[v] = c1 * a2.t[v] + c2 * a.t[v]; });
+            const M y0 = mul(a2, R);
+            M L, g;
+            each([&](int v) {
+                L.h[v] = y0.h[v] + c3 * a2.h[v] + c4 * a.h[v];
+                L.t[v] = y0.t[v] + c3 * a2.t[v] + c4 * a.t[v];
+                R.h[v] = y0.h[v] + c5 * a2.h[v];
+                R.t[v] = y0.t[v] + c5 * a2.t[v];
+                g.h[v] = hi ? c6 * y0.h[v] + (T)EXPM_T15_C7 * a2.h[v] : c6 * y0.h[v] + a2.h[v] / (T)2 + a.h[v] + dgv[v];
+                g.t[v] = hi ? c6 * y0.t[v] + (T)EXPM_T15_C7 * a2.t[v] : c6 * y0.t[v] + a2.t[v] / (T)2 + a.t[v] + dgv[v];
+            });
+            const M p1 = mul(L, R, hi || s > 0);
+            if (!hi) {
+                each([&](int v) { x.h[v] = p1.h[v] + g.h[v]; x.t[v] = p1.t[v] + g.t[v]; });
+            } else {
+                const T c8 = (T)EXPM_T15_C8, c9 = (T)EXPM_T15_C9, c10 = (T)EXPM_T15_C10, c11 = (T)EXPM_T15_C11,
+                        c12 = (T)EXPM_T15_C12, c13 = (T)EXPM_T15_C13, c14 = (T)EXPM_T15_C14, c15 = (T)EXPM_T15_C15,
+                        c16 = (T)EXPM_T15_C16;
+                each([&](int v) {
+                    const T y1h = p1.h[v] + g.h[v], y1t = p1.t[v] + g.t[v];  // y12
+                    L.h[v] = y1h + c8 * a2.h[v] + c9 * a.h[v];
+                    L.t[v] = y1t + c8 * a2.t[v] + c9 * a.t[v];
+                    R.h[v] = y1h + c10 * y0.h[v] + c11 * a.h[v];
+                    R.t[v] = y1t + c10 * y0.t[v] + c11 * a.t[v];
+                    g.h[v] = c12 * y1h + c13 * y0.h[v] + c14 * a2.h[v] + c15 * a.h[v] + c16 * dgv[v];
+                    g.t[v] = c12 * y1t + c13 * y0.t[v] + c14 * a2.t[v] + c15 * a.t[v] + c16 * dgv[v];
+                });
+                const M p2 = mul(L, R, s > 0);
+                each([&](int v) { x.h[v] = p2.h[v] + g.h[v]; x.t[v] = p2.t[v] + g.t[v]; });
+            }
+        }
+    }
+
+    // ---- squaring phase ----------------------------------------------------------------------------
+    for (int q = 0; q < s; ++q) x = mul(x, x, q + 1 < s);
+
+    each([&](int v) { if (in[v]) O[(size_t)rw[v] * n + lj] = x.h[v]; });
+}
+
+template <typename T, int SCHEME>
+hipError_t launch_tile_t(const void *A, void *out, int n, int batch, double eps, int select_only, int norm_inf,
+                         MatInfo *info, hipStream_t stream)
+{
+    hipLaunchKernelGGL((fused_tile_kernel<T, SCHEME>), dim3((batch + 3) / 4), dim3(256), 0, stream,
+                       reinterpret_cast<const T *>(A), reinterpret_cast<T *>(out), n, batch, eps, select_only, norm_inf, info);
+    return hipGetLastError();
+}
+
 template <typename T, int NT, int SCHEME>
 hipError_t launch_fused_t(const void *A, void *out, int n, int batch, double eps, int select_only, int norm_inf,
                           MatInfo *info, hipStream_t stream)
@@ -653,6 +931,15 @@ hipError_t launch_small(const void *A, void *out, int n, int batch, int dtype, d
                         int scheme, int norm_inf, MatInfo *info, hipStream_t stream)
 {
     const int nt = (n + 15) / 16;
+    if (nt == 1 && dtype == 1) {
+        // One tile in fp64: the register-resident kernel.  (In fp32 the doubled matrix-core work of that design
+        // costs more than the LDS round trips of the general kernel save, so fp32 stays there.)
+        return scheme == kSchemePS
+                   ? launch_tile_t<double, kSchemePS>(A, out, n, batch, eps, select_only, norm_inf, info, stream)
+                   : (scheme == kSchemeBaseline
+                          ? launch_tile_t<double, kSchemeBaseline>(A, out, n, batch, eps, select_only, norm_inf, info, stream)
+                          : launch_tile_t<double, kSchemeSastre>(A, out, n, batch, eps, select_only, norm_inf, info, stream));
+    }
 #define EXPM_FUSED_CASE(TYPE, K)                                                                              \
     case K:                                                                                                   \
         return scheme == kSchemePS                                                                            \
@@ -665,7 +952,7 @@ hipError_t launch_small(const void *A, void *out, int n, int batch, int dtype, d
                                                                    norm_inf, info, stream));
     if (dtype == 1) {
         switch (nt) {
-            EXPM_FUSED_CASE(double, 1) EXPM_FUSED_CASE(double, 2) EXPM_FUSED_CASE(double, 3)
+            EXPM_FUSED_CASE(double, 2) EXPM_FUSED_CASE(double, 3)
             EXPM_FUSED_CASE(double, 4) EXPM_FUSED_CASE(double, 5) EXPM_FUSED_CASE(double, 6)
         default: return hipErrorInvalidValue;
         }
