@@ -103,6 +103,7 @@ __global__ __launch_bounds__(256) void fused_expm_kernel(const T *__restrict__ A
         }
     };
 
+    __builtin_assume(n >= 1 && n <= NP);  // the launcher picks NT = ceil(n / 16); lets the copy loops below fold for small NT
     const int tid = C::kMPW > 1 ? (int)(threadIdx.x & 63) : (int)threadIdx.x, lane = tid & 63;
     const int wave = C::kMPW > 1 ? 0 : __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform, in a scalar register
     const int wr = wave / WG, wc = wave % WG;
@@ -326,7 +327,9 @@ __global__ __launch_bounds__(256) void fused_expm_kernel(const T *__restrict__ A
                         f(ti, tj, v, 16 * (wr * TH + ti) + Mfma<T>::row(lg, v), 16 * (wc * TH + tj) + lj);
                 }
     };
-    auto dg = [&](int r, int c) -> T { return (r == c && r < n) ? (T)1 : (T)0; };
+    // identity term; it also lands on the diagonal of the zero padding, which is a block of its own
+    // (padded rows and columns of every operand are zero) and is never stored
+    auto dg = [&](int r, int c) -> T { return r == c ? (T)1 : (T)0; };
     // Q(r, c) = val(ti, tj, v, r, c) for every element this lane owns.  In the transposed fp32 buffer the four
     // rows a lane holds of one column are adjacent: one 16-byte store per tile.
     auto store_right = [&](auto &&val) {
@@ -540,11 +543,11 @@ __global__ __launch_bounds__(256) void fused_expm_kernel(const T *__restrict__ A
             xv[ti][tj][v] = x;
         });
     } else if (m == 4) {
-        // T4 = ((A2/4 + A)/3 + I) * (A2/2) + A + I
+        // T4 = (A2/12 + A/3 + I) * (A2/2) + A + I
         sync();  // every wave is done with P (norm) before it is overwritten
         for_owned([&](int ti, int tj, int v, int r, int c) {
             const T a = av[ti][tj][v], a2 = a2v[ti][tj][v];
-            P[li(r, c)] = (a2 / (T)4 + a) / (T)3 + dg(r, c);
+            P[li(r, c)] = a2 * (T)(1.0 / 12.0) + a * (T)(1.0 / 3.0) + dg(r, c);
         });
         store_right([&](int ti, int tj, int v, int, int) { return a2v[ti][tj][v] / (T)2; });
         sync();
@@ -678,7 +681,7 @@ __global__ __launch_bounds__(256) void fused_tile_kernel(const T *__restrict__ A
     };
     // e = f(x.., identity) applied to both forms; the identity is symmetric
     T dgv[4];
-    each([&](int v) { dgv[v] = (rw[v] == lj && lj < n) ? (T)1 : (T)0; });
+    each([&](int v) { dgv[v] = rw[v] == lj ? (T)1 : (T)0; });  // also on the padding's diagonal: a block of its own
     // max column abs-sum of the matrix whose result-layout registers are x (double sums, NaN if not finite)
     auto colnorm = [&](const T (&x)[4]) -> double {
         double sum = 0.0;
@@ -837,11 +840,11 @@ __global__ __launch_bounds__(256) void fused_tile_kernel(const T *__restrict__ A
                 x.h[v] = xh; x.t[v] = xt;
             });
         } else if (m == 4) {
-            // T4 = ((A2/4 + A)/3 + I) * (A2/2) + A + I
+            // T4 = (A2/12 + A/3 + I) * (A2/2) + A + I
             M L, R;
             each([&](int v) {
-                L.h[v] = (a2.h[v] / (T)4 + a.h[v]) / (T)3 + dgv[v];
-                L.t[v] = (a2.t[v] / (T)4 + a.t[v]) / (T)3 + dgv[v];
+                L.h[v] = a2.h[v] * (T)(1.0 / 12.0) + a.h[v] * (T)(1.0 / 3.0) + dgv[v];
+                L.t[v] = a2.t[v] * (T)(1.0 / 12.0) + a.t[v] * (T)(1.0 / 3.0) + dgv[v];
                 R.h[v] = a2.h[v] / (T)2;
                 R.t[v] = a2.t[v] / (T)2;
             });
