@@ -393,3 +393,46 @@ def test_flow_setting_of_the_paper_tol_1e8_inf_norm(ex):
     print("   F1 orders:", hist, "max s", int(s.max()), flush=True)
     assert hist.get(1, 0) > 0 and hist.get(2, 0) > 0 and hist.get(4, 0) > 0 and hist.get(15, 0) > 0
     assert int(s.max()) <= 3   # norm 12.8 needs s = 3 at this tolerance (the paper's worked example)
+
+
+# ------------------------------------------------------------------------------------------------
+# one-tile fp64 matrices (n <= 16): the register-resident kernel; every order, scaling, both norms
+# ------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("n", [3, 9, 16])
+def test_one_tile_fp64_all_orders_both_norms(ex, n):
+    from paper_2512_20777_amd import workloads
+    a = workloads.random_stack(1200 + n, 48, n, np.float64, 1e-9, 300.0, kind="dense" if n % 2 else "triu")
+    a[0] = 0.0                                  # order 0
+    a[1] *= 1e-12 / max(np.abs(a[1]).sum(axis=0).max(), 1e-300)   # order 1
+    got, m, s, info, stats = _run_and_check(ex, a, label="one tile fp64 n=%d" % n)
+    assert stats["fused_path"] == 1
+    assert {0, 1, 2, 4, 8, 15} <= set(int(x) for x in m) and int(s.max()) >= 4
+    _run_inf_norm(ex, a, U64, "one tile fp64 inf-norm n=%d" % n)
+    _run_inf_norm(ex, a, 1e-8, "one tile fp64 inf-norm tol 1e-8 n=%d" % n)
+
+
+def test_one_tile_fp64_nonfinite_and_nilpotent(ex):
+    import torch
+    rng = np.random.default_rng(77)
+    n = 11
+    a = rng.standard_normal((6, n, n)) * 0.3
+    a[2, 4, 7] = np.nan
+    a[4, 0, 0] = np.inf
+    a[5] = np.triu(a[5], 1)                     # nilpotent: the series is finite, order 15 covers n - 1 = 10
+    a[5] *= 0.4 / np.abs(a[5]).sum(axis=0).max()
+    d = torch.from_numpy(a).cuda()
+    out, status = ex.expm(d, U64)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    # the asynchronous call cannot report it; the statistics of the call and expm_select do
+    assert ex.expm_get_stats()["warning"] == 1
+    m, s, st2 = ex.expm_select(d, U64)
+    assert st2 == 1 and (m[2], s[2]) == (-1, -1) and (m[4], s[4]) == (-1, -1)
+    assert np.isnan(got[2]).all() and np.isnan(got[4]).all()
+    for b in (0, 1, 3, 5):
+        assert np.isfinite(got[b]).all()
+    from oracle import oracle_expm_batch
+    X, info = oracle_expm_batch(a[[0, 1, 3, 5]], U64)
+    for i, b in enumerate((0, 1, 3, 5)):
+        assert np.linalg.norm(got[b] - X[i]) / np.linalg.norm(X[i]) <= 1e-11
+    assert np.all(np.tril(got[5], -1) == 0.0)   # upper triangular input: exact zeros below the diagonal
