@@ -643,8 +643,9 @@ template <typename T> struct Pair {
     T h[4], t[4];
 };
 
+// (register budget of 128 per lane: the four workgroups a compute unit gets at a batch of 4096 are resident together)
 template <typename T, int SCHEME>
-__global__ __launch_bounds__(256) void fused_tile_kernel(const T *__restrict__ Ain, T *__restrict__ Out, int n, int batch,
+__global__ __launch_bounds__(256, 4) void fused_tile_kernel(const T *__restrict__ Ain, T *__restrict__ Out, int n, int batch,
                                                          double eps, int select_only, int norm_inf,
                                                          MatInfo *__restrict__ info)
 {
