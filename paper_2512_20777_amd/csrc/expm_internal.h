@@ -49,6 +49,25 @@ struct MatInfo {
     int flags;  // bit0 non-finite, bit1 s hit the cap
 };
 
+// Scaling that one error term asks for (last steps of Algorithms 3 and 4): the smallest s >= 0 with
+// e / 2^(w s) <= eps, i.e. ceil(log2(e / eps) / w) clipped to [0, cap].  Found from the binary exponents of e
+// and eps and one exact comparison against eps * 2^(w s) instead of a division and a logarithm: with
+// e = fe 2^xe and eps = fp 2^xp (fe, fp in [1/2, 1)) the ratio lies in (2^(d-1), 2^(d+1)), d = xe - xp, so
+// s is floor((d-1)/w) + 1 or one more.
+__host__ __device__ inline int scaling_for_term(double e, double eps, int w)
+{
+    if (!(e <= 1.7976931348623157e308)) return kSCap;
+    if (e <= eps) return 0;  // also e <= 0
+    int xe, xp;
+    (void)frexp(e, &xe);
+    (void)frexp(eps, &xp);
+    const int d = xe - xp;  // >= 0 here
+    int s1 = d >= 1 ? (d - 1) / w + 1 : 0;
+    if (s1 > kSCap) return kSCap;
+    if (e > ldexp(eps, w * s1)) ++s1;
+    return s1 > kSCap ? kSCap : s1;
+}
+
 // ---------------------------------------------------------------------------------------------
 // Algorithm 4 (Sec. 3.3) on the two norms n1 = ||W||_1, n2 = ||W^2||_1, tolerance eps.
 // Bounds per order from the table that follows Algorithm 4.  All in double.
@@ -94,20 +113,8 @@ __host__ __device__ inline void select_order_scaling(double n1, double n2, doubl
     e2 = inv17f * p8 * n1;
     if (e1 + e2 <= eps) return;
     // scaling from each of the two terms alone, the larger wins (Sec. 3.2, last paragraph)
-    const double ee[2] = {e1, e2};
-    for (int i = 0; i < 2; ++i) {
-        int s1;
-        const double e = ee[i];
-        if (!(e <= 1.7976931348623157e308)) {
-            s1 = kSCap;
-        } else if (e <= 0.0) {
-            s1 = 0;
-        } else {
-            const double q = ceil(log2(e / eps) / (double)(16 + i));
-            s1 = q > (double)kSCap ? kSCap : (q < 0.0 ? 0 : (int)q);
-        }
-        if (s1 > s) s = s1;
-    }
+    const int sa = scaling_for_term(e1, eps, 16), sb = scaling_for_term(e2, eps, 17);
+    s = sa > sb ? sa : sb;
     if (s >= kSCap) { s = kSCap; flags |= 2; }
 }
 
@@ -165,20 +172,8 @@ __host__ __device__ inline void select_ps_order_scaling(const double nrm[4], int
         }
         if (e1 + e2 <= eps) return;
     }
-    const double ee[2] = {e1, e2};
-    for (int i = 0; i < 2; ++i) {
-        int s1;
-        const double e = ee[i];
-        if (!(e <= 1.7976931348623157e308)) {
-            s1 = kSCap;
-        } else if (e <= 0.0) {
-            s1 = 0;
-        } else {
-            const double q = ceil(log2(e / eps) / (double)(17 + i));
-            s1 = q > (double)kSCap ? kSCap : (q < 0.0 ? 0 : (int)q);
-        }
-        if (s1 > s) s = s1;
-    }
+    const int sa = scaling_for_term(e1, eps, 17), sb = scaling_for_term(e2, eps, 18);
+    s = sa > sb ? sa : sb;
     if (s >= kSCap) { s = kSCap; flags |= 2; }
 }
 

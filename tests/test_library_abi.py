@@ -115,29 +115,84 @@ def test_selection_rule_of_the_library_matches_the_oracle_on_a_grid_of_norms(tmp
         '#define __host__\n#define __device__\n#define __forceinline__ inline\n'
         'namespace hipstub {}\n'
         + _selection_source() +
-        'int main(int argc, char** argv) { double n1 = atof(argv[1]), n2 = atof(argv[2]), eps = atof(argv[3]);'
-        ' int m, s, f; expmk::select_order_scaling(n1, n2, eps, m, s, f); printf("%d %d %d\\n", m, s, f); return 0; }\n')
+        'int main() { double n1, n2, eps; while (scanf("%lf %lf %lf", &n1, &n2, &eps) == 3) {'
+        ' int m, s, f; expmk::select_order_scaling(n1, n2, eps, m, s, f); printf("%d %d %d\\n", m, s, f); } return 0; }\n')
     exe = tmp_path / "sel"
     subprocess.run(["g++", "-O1", "-o", str(exe), str(src)], check=True)
     rng = np.random.default_rng(17)
+    cases = []
     for eps in (2.0 ** -53, 2.0 ** -24, 1e-8):
-        for _ in range(60):
-            n1 = float(10.0 ** rng.uniform(-9, 4))
+        for _ in range(1500):
+            n1 = float(10.0 ** rng.uniform(-9, 7))
             n2 = float(n1 * n1 * 10.0 ** rng.uniform(-3, 0))
-            exp = oracle_select_from_norms(n1, n2, eps)
-            corners = {oracle_select_from_norms(n1 * a, n2 * b, eps) for a in (1 - 1e-6, 1 + 1e-6) for b in (1 - 1e-6, 1 + 1e-6)}
-            out = subprocess.run([str(exe), repr(n1), repr(n2), repr(eps)], capture_output=True, text=True, check=True)
-            m, s, _f = [int(x) for x in out.stdout.split()]
-            if len(corners) == 1:
-                assert (m, s) == exp, (n1, n2, eps, (m, s), exp)
-            else:
-                assert (m, s) in corners
+            cases.append((n1, n2, eps))
+        # the scaling switches exactly where a term equals eps * 2^(16 k) or eps * 2^(17 k): hit those points
+        # (n2 = n1^2: E1 = |1/16! - b16| n1^16) and their neighbours
+        d16 = 2.1711086342891295e-14
+        for k in range(1, 22):
+            x = (eps * 2.0 ** (16 * k) / d16) ** (1.0 / 16.0)
+            for f in (1 - 3e-6, 1 - 1e-9, 1.0, 1 + 1e-9, 1 + 3e-6):
+                cases.append((x * f, (x * f) ** 2, eps))
+    out = subprocess.run([str(exe)], input="".join("%r %r %r\n" % c for c in cases), capture_output=True, text=True,
+                         check=True)
+    got = [tuple(int(x) for x in ln.split()[:2]) for ln in out.stdout.splitlines()]
+    assert len(got) == len(cases)
+    seen_s = set()
+    for (n1, n2, eps), (m, s) in zip(cases, got):
+        exp = oracle_select_from_norms(n1, n2, eps)
+        corners = {oracle_select_from_norms(n1 * a, n2 * b, eps) for a in (1 - 1e-6, 1 + 1e-6) for b in (1 - 1e-6, 1 + 1e-6)}
+        if len(corners) == 1:
+            assert (m, s) == exp, (n1, n2, eps, (m, s), exp)
+        else:
+            assert (m, s) in corners, (n1, n2, eps, (m, s), corners)
+        seen_s.add(s)
+    assert seen_s >= set(range(0, 21))   # every scaling up to the cap was exercised
 
 
-def _selection_source():
+def test_paterson_stockmeyer_selection_of_the_library_matches_the_oracle(tmp_path):
+    """Same check for the selection of the Paterson-Stockmeyer variant (four power norms)."""
+    import subprocess
+    import numpy as np
+    from oracle import oracle_select_ps_from_norms
+    src = tmp_path / "selps.cpp"
+    src.write_text(
+        '#include <cstdio>\n#include <cstdlib>\n#include <cmath>\n'
+        '#define __host__\n#define __device__\n#define __forceinline__ inline\n'
+        + _selection_source("// Products after the powers") +
+        'int main() { double n[4], eps; while (scanf("%lf %lf %lf %lf %lf", &n[0], &n[1], &n[2], &n[3], &eps) == 5) {'
+        ' int m, s, f; bool more; expmk::select_ps_order_scaling(n, 4, eps, m, s, f, more); printf("%d %d\\n", m, s); }'
+        ' return 0; }\n')
+    exe = tmp_path / "selps"
+    subprocess.run(["g++", "-O1", "-o", str(exe), str(src)], check=True)
+    rng = np.random.default_rng(23)
+    cases = []
+    for eps in (2.0 ** -53, 2.0 ** -24, 1e-8):
+        for _ in range(1200):
+            n1 = float(10.0 ** rng.uniform(-9, 7))
+            n2 = float(n1 ** 2 * 10.0 ** rng.uniform(-2, 0))
+            n3 = float(n1 * n2 * 10.0 ** rng.uniform(-1, 0))
+            n4 = float(n2 * n2 * 10.0 ** rng.uniform(-1, 0))
+            cases.append((n1, n2, n3, n4, eps))
+    out = subprocess.run([str(exe)], input="".join("%r %r %r %r %r\n" % c for c in cases), capture_output=True,
+                         text=True, check=True)
+    got = [tuple(int(x) for x in ln.split()) for ln in out.stdout.splitlines()]
+    assert len(got) == len(cases)
+    seen_s = set()
+    for c, ms in zip(cases, got):
+        n1, n2, n3, n4, eps = c
+        exp = oracle_select_ps_from_norms(n1, n2, n3, n4, eps)
+        corners = {oracle_select_ps_from_norms(n1 * a, n2 * b, n3 * b, n4 * b, eps)
+                   for a in (1 - 1e-6, 1 + 1e-6) for b in (1 - 1e-6, 1 + 1e-6)}
+        if len(corners) == 1:
+            assert ms == exp, (c, ms, exp)
+        seen_s.add(ms[1])
+    assert seen_s >= set(range(0, 21))
+
+
+def _selection_source(end_marker="// Rounds after the W^2 product"):
     """The selection function and its constants cut out of the kernel header (plain C++ once the
     HIP qualifiers are defined away)."""
     text = open(os.path.join(ROOT, "paper_2512_20777_amd", "csrc", "expm_internal.h")).read()
     start = text.index("#define EXPM_T8_C1")
-    end = text.index("// Rounds after the W^2 product")
+    end = text.index(end_marker)
     return "namespace expmk {\n" + text[start:end] + "}\n"
