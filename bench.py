@@ -17,8 +17,8 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 PEAK = {"hbm": 8000.0, "mfma_f32": 157.3, "mfma_f64": 78.6}  # GB/s, TFLOP/s (MI355X published)
-DEFAULT_STEPS = {"F1": 200, "C1": 200, "C2": 200, "C3": 50, "C4": 20, "C5f64": 4, "C5f32": 6}
-DEFAULT_WARMUP = {"F1": 20, "C1": 20, "C2": 20, "C3": 10, "C4": 4, "C5f64": 2, "C5f32": 2}
+DEFAULT_STEPS = {"F1": 200, "C1": 200, "C2": 200, "C3": 100, "C4": 60, "C5f64": 4, "C5f32": 6}
+DEFAULT_WARMUP = {"F1": 20, "C1": 20, "C2": 20, "C3": 20, "C4": 15, "C5f64": 2, "C5f32": 2}
 
 
 def source_sha1():

@@ -44,6 +44,8 @@ bool g_profile = false;
 std::vector<ProfEvent> g_events;
 std::vector<hipEvent_t> g_event_pool;
 hipEvent_t g_summary_ready = nullptr;
+hipStream_t g_side_stream = nullptr;          // norm of W beside the W^2 round (default priority)
+hipEvent_t g_fork = nullptr, g_join = nullptr;
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
@@ -60,7 +62,7 @@ int hip_fail(hipError_t e)
     } while (0)
 
 struct Layout {
-    size_t info, order, summary, n1, n2, n3, n4, colpart, mats, total;
+    size_t info, order, summary, n1, n2, n3, n4, colpart, colpart_w, mats, total;
     size_t mat_bytes;
 };
 
@@ -81,9 +83,12 @@ Layout make_layout(int n, int batch, int dtype)
     L.n4 = off;      off = align_up(off + (size_t)batch * nblk * sizeof(double), 256);
     L.mat_bytes = 0;
     L.colpart = off;
+    L.colpart_w = off;
     L.mats = off;
     if (!small_path_supported(n, dtype)) {
-        // column-sum partials: 32-row chunks for W, one per tile row (>= 64 rows) for W2
+        // column-sum partials: 32-row chunks for W, one per tile row (>= 64 rows) for the powers
+        off = align_up(off + (size_t)batch * general_colchunks(n) * n * sizeof(double), 256);
+        L.colpart_w = off;
         off = align_up(off + (size_t)batch * general_colchunks(n) * n * sizeof(double), 256);
         L.mats = off;
         L.mat_bytes = align_up((size_t)batch * n * n * w, 256);
@@ -204,6 +209,7 @@ Bound bind(const void *A, void *out, int n, int batch, int dtype, int norm_kind)
     B.gb.n3 = reinterpret_cast<double *>(base + B.L.n3);
     B.gb.n4 = reinterpret_cast<double *>(base + B.L.n4);
     B.gb.colpart = reinterpret_cast<double *>(base + B.L.colpart);
+    B.gb.colpart_w = reinterpret_cast<double *>(base + B.L.colpart_w);
     B.gb.base[BUF_W] = const_cast<void *>(A);
     for (int i = 0; i < 7; ++i) B.gb.base[BUF_W2 + i] = base + B.L.mats + (size_t)i * B.L.mat_bytes;
     B.gb.base[BUF_OUT] = out;
@@ -216,11 +222,28 @@ int run_selection_general(const Bound &B, int n, int batch, int dtype, double to
 {
     const double w = dtype == EXPM_DTYPE_F64 ? 8.0 : 4.0;
     const double nn = (double)n * n;
-    {
-        Bracket br(stream, EXPM_KCLASS_NORM, 0.0, batch * nn * w);
-        EXPM_TRY(launch_colabs(B.gb, n, batch, dtype, stream));
-        EXPM_TRY(launch_colmax(B.gb, n, batch, 1, B.gb.norm_inf ? 1 : general_colchunks(n), stream));
+    // The norm of W needs nothing but W: its two kernels run on a side stream beside the W^2 round (they fill
+    // the compute units that round leaves idle towards its end) and join before the selection.  With the
+    // per-class timers on, everything stays on the caller's stream so that each class is timed by itself.
+    // (only for matrices below 1024: beyond that the pass is a fraction of a percent of the call, and its reads
+    // beside the start of a long product round cost that round more than they save)
+    const bool side = !g_profile && n < 1024;
+    if (side) {
+        if (!g_side_stream) {
+            EXPM_TRY(hipStreamCreateWithFlags(&g_side_stream, hipStreamNonBlocking));
+            EXPM_TRY(hipEventCreateWithFlags(&g_fork, hipEventDisableTiming));
+            EXPM_TRY(hipEventCreateWithFlags(&g_join, hipEventDisableTiming));
+        }
+        EXPM_TRY(hipEventRecord(g_fork, stream));
+        EXPM_TRY(hipStreamWaitEvent(g_side_stream, g_fork, 0));
     }
+    {
+        hipStream_t ns = side ? g_side_stream : stream;
+        Bracket br(stream, EXPM_KCLASS_NORM, 0.0, batch * nn * w);
+        EXPM_TRY(launch_colabs(B.gb, n, batch, dtype, ns));
+        EXPM_TRY(launch_colmax(B.gb, n, batch, 1, B.gb.norm_inf ? 1 : general_colchunks(n), ns));
+    }
+    if (side) EXPM_TRY(hipEventRecord(g_join, g_side_stream));
     const int wt0 = choose_tile_shape(n, batch);
     {
         Bracket br(stream, EXPM_KCLASS_GEMM, 2.0 * nn * n * batch, 2.0 * batch * nn * w);
@@ -241,6 +264,7 @@ int run_selection_general(const Bound &B, int n, int batch, int dtype, double to
             EXPM_TRY(launch_colmax(B.gb, n, batch, which, (n + 32 * wt0 - 1) / (32 * wt0), stream));
         }
     }
+    if (side) EXPM_TRY(hipStreamWaitEvent(stream, g_join, 0));
     {
         Bracket br(stream, EXPM_KCLASS_SELECT, 0.0, 0.0);
         EXPM_TRY(launch_select_plan(B.gb, n, batch, tol, scheme, stream));
@@ -490,6 +514,9 @@ int expm_shutdown(void)
     }
     if (g_ws.host_summary) (void)hipHostFree(g_ws.host_summary);
     if (g_summary_ready) { (void)hipEventDestroy(g_summary_ready); g_summary_ready = nullptr; }
+    if (g_fork) { (void)hipEventDestroy(g_fork); g_fork = nullptr; }
+    if (g_join) { (void)hipEventDestroy(g_join); g_join = nullptr; }
+    if (g_side_stream) { (void)hipStreamDestroy(g_side_stream); g_side_stream = nullptr; }
     free(g_ws.host_info);
     g_ws = Workspace{};
     g_last = LastCall{};

@@ -624,20 +624,20 @@ hipError_t launch_colabs(const GeneralBuffers &gb, int n, int batch, int dtype, 
         dim3 grid((n + 3) / 4, batch);
         if (dtype == 1)
             hipLaunchKernelGGL(rowabs_kernel<double>, grid, dim3(256), 0, stream,
-                               reinterpret_cast<const double *>(gb.base[BUF_W]), gb.colpart, n);
+                               reinterpret_cast<const double *>(gb.base[BUF_W]), gb.colpart_w, n);
         else
             hipLaunchKernelGGL(rowabs_kernel<float>, grid, dim3(256), 0, stream,
-                               reinterpret_cast<const float *>(gb.base[BUF_W]), gb.colpart, n);
+                               reinterpret_cast<const float *>(gb.base[BUF_W]), gb.colpart_w, n);
         return hipGetLastError();
     }
     const int chunks = general_colchunks(n);
     dim3 grid((n + 255) / 256, chunks, batch);
     if (dtype == 1)
         hipLaunchKernelGGL(colabs_kernel<double>, grid, dim3(256), 0, stream,
-                           reinterpret_cast<const double *>(gb.base[BUF_W]), gb.colpart, n, chunks);
+                           reinterpret_cast<const double *>(gb.base[BUF_W]), gb.colpart_w, n, chunks);
     else
         hipLaunchKernelGGL(colabs_kernel<float>, grid, dim3(256), 0, stream,
-                           reinterpret_cast<const float *>(gb.base[BUF_W]), gb.colpart, n, chunks);
+                           reinterpret_cast<const float *>(gb.base[BUF_W]), gb.colpart_w, n, chunks);
     return hipGetLastError();
 }
 
@@ -645,7 +645,8 @@ hipError_t launch_colmax(const GeneralBuffers &gb, int n, int batch, int which, 
 {
     const int nblk = general_colblocks(n);
     double *dst = which == 1 ? gb.n1 : (which == 2 ? gb.n2 : (which == 3 ? gb.n3 : gb.n4));
-    hipLaunchKernelGGL(colmax_kernel, dim3(nblk, batch), dim3(256), 0, stream, gb.colpart, dst, n, chunks, nblk);
+    hipLaunchKernelGGL(colmax_kernel, dim3(nblk, batch), dim3(256), 0, stream, which == 1 ? gb.colpart_w : gb.colpart, dst, n,
+                       chunks, nblk);
     return hipGetLastError();
 }
 

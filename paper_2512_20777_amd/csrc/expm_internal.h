@@ -365,7 +365,8 @@ __device__ __forceinline__ Step<T> build_step_ps(int m, int s, int r)
 // ---------------------------------------------------------------------------------------------
 struct GeneralBuffers {
     void *base[BUF_COUNT];   // device pointers, [batch][n][n] each (BUF_W = input, BUF_OUT = output)
-    double *colpart;         // [batch][chunks][n] column abs-sum partials (chunks: see the launchers)
+    double *colpart;         // [batch][chunks][n] column abs-sum partials of the power rounds (chunks: see the launchers)
+    double *colpart_w;       // the same for W itself; a buffer of its own: that pass may run beside the W^2 round
     double *n1, *n2, *n3, *n4;  // [batch][colblocks] per-column-block maxima of the column sums of W .. W^4
     MatInfo *info;           // [batch]
     int *order;              // [batch] matrices sorted by chain length, longest first
