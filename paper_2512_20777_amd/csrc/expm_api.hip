@@ -407,11 +407,15 @@ int expm_ex(const void *A, int n, int batch, int dtype, double tol, int scheme, 
     // Work that does not need the host's view of the plan is queued before the wait, so the device
     // stays busy while the summary is read: operand preparation, and the first chain round over the
     // whole batch (workgroups of matrices that need no product leave at once).
-    {
-        Bracket br(stream, EXPM_KCLASS_SELECT, 0.0, 0.0);
-        EXPM_TRY(launch_prepare(B.gb, n, batch, dtype, scheme, stream));
-    }
-    {
+    if (first_round_is_self_contained(n, scheme)) {
+        // no preparation pass: round 1 combines W^2 and W while it stages its tiles and finishes orders <= 2 itself
+        Bracket br(stream, EXPM_KCLASS_GEMM, 0.0, 0.0);  // its work is filled in once the plan is known
+        EXPM_TRY(launch_first_round(B.gb, n, batch, dtype, stream));
+    } else {
+        {
+            Bracket br(stream, EXPM_KCLASS_SELECT, 0.0, 0.0);
+            EXPM_TRY(launch_prepare(B.gb, n, batch, dtype, scheme, stream));
+        }
         Bracket br(stream, EXPM_KCLASS_GEMM, 0.0, 0.0);  // its work is filled in once the plan is known
         EXPM_TRY(launch_chain_round(B.gb, n, batch, 1, dtype, choose_tile_shape(n, batch), scheme, stream));
     }

@@ -76,6 +76,19 @@ __device__ __forceinline__ int xcd_remap(int pid, int total)
 // bounds checks, or 16-byte vectors with none (n a multiple of the tile and of the k-block: every tile full).
 constexpr int kAccessScalar = 0, kAccessVector = 1, kAccessFull = 2;
 
+// grouped tile order: 8 tile-rows at a time, column by column
+__device__ __forceinline__ void tile_position(int tile, int tiles, int &tm, int &tn)
+{
+    const int GM = 8;
+    const int per_group = GM * tiles;
+    const int group = tile / per_group;
+    const int first = group * GM;
+    const int gsz = min(tiles - first, GM);
+    const int rem = tile - group * per_group;
+    tm = first + rem % gsz;
+    tn = rem / gsz;
+}
+
 template <typename T, int ALIGNED>
 __device__ __forceinline__ typename Tile<T>::vec_t load_vec(const T *__restrict__ p, int row, int col, int n)
 {
@@ -98,7 +111,11 @@ __device__ __forceinline__ typename Tile<T>::vec_t load_vec(const T *__restrict_
     return v;
 }
 
-template <typename T, int WT, int ALIGNED>
+// FIRST: chain round 1 of the main scheme without a preparation pass.  The operand that is a linear combination of
+// W^2 and W (right factor c1 A^2 + c2 A of y02 for orders 8 and 15+, left factor A^2/12 + A/3 + I of T_4) is formed
+// while its tile is staged (one more vector per staged vector, combined just before the LDS store), and the
+// workgroups of matrices of order <= 2, which need no product, write their tile of the result and leave.
+template <typename T, int WT, int ALIGNED, bool FIRST = false>
 __global__ __launch_bounds__(kThreads, WT == 4 ? 2 : 4) void gemm_round_kernel(GemmParams p)
 {
     using V = typename Tile<T>::vec_t;
@@ -127,6 +144,8 @@ __global__ __launch_bounds__(kThreads, WT == 4 ? 2 : 4) void gemm_round_kernel(G
     const int tile = wid - slot * tiles2;
     int b;
     Step<T> st;
+    int first_m = 0;      // FIRST: order of this matrix (4: left operand combined, 8 / 15: right operand combined)
+    T xa = (T)1, xb = (T)0;  // FIRST: coefficients of W^2 and W in the combined operand
     if (p.round <= 0) {
         b = slot;
         st.L = p.round == 0 ? BUF_W : (p.round == -1 ? BUF_W2 : BUF_W3);
@@ -136,21 +155,50 @@ __global__ __launch_bounds__(kThreads, WT == 4 ? 2 : 4) void gemm_round_kernel(G
     } else {
         b = p.order[slot];
         const MatInfo mi = p.info[b];
-        if (p.round > mi.len) return;
-        st = p.scheme == kSchemePS ? build_step_ps<T>(mi.m, mi.s, p.round) : build_step<T>(mi.m, mi.s, p.round);
+        if constexpr (FIRST) {
+            first_m = mi.m;
+            if (mi.m <= 2) {
+                // no product: P_0 = I, T_1 = A + I, T_2 = A^2/2 + A + I (s = 0 for these orders), NaN if not finite
+                int tm0, tn0;
+                tile_position(tile, p.tiles, tm0, tn0);
+                const size_t mo = (size_t)b * n * n;
+                const T *Wp = reinterpret_cast<const T *>(p.base[BUF_W]) + mo;
+                const T *W2p = reinterpret_cast<const T *>(p.base[BUF_W2]) + mo;
+                T *O = reinterpret_cast<T *>(p.base[BUF_OUT]) + mo;
+                for (int e = tid; e < BM * BN; e += kThreads) {
+                    const int r = tm0 * BM + e / BN, c = tn0 * BN + e % BN;
+                    if (r < n && c < n) {
+                        const size_t idx = (size_t)r * n + c;
+                        const T dg = r == c ? (T)1 : (T)0;
+                        T o;
+                        if (mi.m < 0) o = (T)__longlong_as_double(0x7ff8000000000000LL);
+                        else if (mi.m == 0) o = dg;
+                        else if (mi.m == 1) o = Wp[idx] + dg;
+                        else o = W2p[idx] / (T)2 + Wp[idx] + dg;
+                        O[idx] = o;
+                    }
+                }
+                return;
+            }
+            st = build_step<T>(mi.m, mi.s, 1);
+            // both operands start from W^2; the combined side adds W
+            st.L = BUF_W2; st.R = BUF_W2;
+            if (mi.m == 4) {
+                xa = (T)(1.0 / 12.0); xb = (T)(1.0 / 3.0);   // left factor A^2/12 + A/3 + I (s = 0)
+                st.acc_scale = (T)0.5;                        // right factor A^2/2
+            } else if (mi.m == 8) {
+                xa = (T)EXPM_T8_C1; xb = (T)EXPM_T8_C2;       // right factor c1 A^2 + c2 A (s = 0)
+            } else {
+                const double sg = mi.s > 0 ? pow2neg(mi.s) : 1.0, sg2 = mi.s > 0 ? pow2neg(2 * mi.s) : 1.0;
+                xa = (T)(EXPM_T15_C1 * sg2); xb = (T)(EXPM_T15_C2 * sg);
+            }
+        } else {
+            if (p.round > mi.len) return;
+            st = p.scheme == kSchemePS ? build_step_ps<T>(mi.m, mi.s, p.round) : build_step<T>(mi.m, mi.s, p.round);
+        }
     }
-    // grouped tile order: 8 tile-rows at a time, column by column
     int tm, tn;
-    {
-        const int GM = 8;
-        const int per_group = GM * p.tiles;
-        const int group = tile / per_group;
-        const int first = group * GM;
-        const int gsz = min(p.tiles - first, GM);
-        const int rem = tile - group * per_group;
-        tm = first + rem % gsz;
-        tn = rem / gsz;
-    }
+    tile_position(tile, p.tiles, tm, tn);
     const size_t moff = (size_t)b * n * n;
     const T *Lp = reinterpret_cast<const T *>(p.base[st.L]) + moff;
     const T *Rp = reinterpret_cast<const T *>(p.base[st.R]) + moff;
@@ -179,12 +227,42 @@ __global__ __launch_bounds__(kThreads, WT == 4 ? 2 : 4) void gemm_round_kernel(G
 
     const int kblocks = (n + BK - 1) / BK;
     V ra[WT], rb[WT];
+    // FIRST: the vectors of W that go into the combined operand, at the A positions (order 4) or the B positions
+    V rx[FIRST ? WT : 1];
+    const T *Xp = reinterpret_cast<const T *>(p.base[BUF_W]) + moff;
+    const bool comb_a = FIRST && first_m == 4;  // uniform over the workgroup
+    auto fetch_x = [&](int k0) {
+        if constexpr (FIRST) {
+#pragma unroll
+            for (int i = 0; i < WT; ++i)
+                rx[i] = comb_a ? load_vec<T, ALIGNED>(Xp, row0 + a_row0 + 32 * i, k0 + a_col, n)
+                               : load_vec<T, ALIGNED>(Xp, k0 + b_row0 + BSTEP * i, col0 + b_col, n);
+        }
+    };
+    // combined operand = xa * (vector of W^2) + xb * (vector of W) (+ I on the left side), element by element
+    auto combine = [&](int k0) {
+        if constexpr (FIRST) {
+#pragma unroll
+            for (int i = 0; i < WT; ++i) {
+                T *dst = reinterpret_cast<T *>(comb_a ? &ra[i] : &rb[i]);
+                const T *x = reinterpret_cast<const T *>(&rx[i]);
+#pragma unroll
+                for (int e = 0; e < VN; ++e) {
+                    T v = xa * dst[e] + xb * x[e];
+                    if (comb_a && row0 + a_row0 + 32 * i == k0 + a_col + e) v += (T)1;
+                    dst[e] = v;
+                }
+            }
+        }
+    };
     // prologue: first k-block into stage 0
 #pragma unroll
     for (int i = 0; i < WT; ++i) {
         ra[i] = load_vec<T, ALIGNED>(Lp, row0 + a_row0 + 32 * i, a_col, n);
         rb[i] = load_vec<T, ALIGNED>(Rp, b_row0 + BSTEP * i, col0 + b_col, n);
     }
+    fetch_x(0);
+    combine(0);
 #pragma unroll
     for (int i = 0; i < WT; ++i) {
         *reinterpret_cast<V *>(smem + a_lds + 32 * i * kAPitch) = ra[i];
@@ -210,6 +288,7 @@ __global__ __launch_bounds__(kThreads, WT == 4 ? 2 : 4) void gemm_round_kernel(G
                 ra[i] = load_vec<T, ALIGNED>(Lp, row0 + a_row0 + 32 * i, k0 + a_col, n);
                 rb[i] = load_vec<T, ALIGNED>(Rp, k0 + b_row0 + BSTEP * i, col0 + b_col, n);
             }
+            fetch_x(k0);
         }
         // A fragments: each lane's KQ k-values of a row are two 16-byte halves; one half (VN k-steps) at a
         // time keeps the live registers low, the co-resident waves cover the LDS latency
@@ -235,6 +314,7 @@ __global__ __launch_bounds__(kThreads, WT == 4 ? 2 : 4) void gemm_round_kernel(G
             }
         }
         if (more) {
+            combine((kb + 1) * BK);
 #pragma unroll
             for (int i = 0; i < WT; ++i) {
                 *reinterpret_cast<V *>(nxt + a_lds + 32 * i * kAPitch) = ra[i];
@@ -535,18 +615,18 @@ __global__ __launch_bounds__(256) void prepare_kernel(GemmParams p)
     }
 }
 
-template <typename T, int WT, int ALIGNED>
+template <typename T, int WT, int ALIGNED, bool FIRST = false>
 hipError_t launch_gemm_t(const GemmParams &p, hipStream_t stream)
 {
     static bool attr_done = false;
     const int lds = 2 * stage_bytes<T, WT>();
     if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_round_kernel<T, WT, ALIGNED>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_round_kernel<T, WT, ALIGNED, FIRST>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, lds);
         if (e != hipSuccess) return e;
         attr_done = true;
     }
-    hipLaunchKernelGGL((gemm_round_kernel<T, WT, ALIGNED>), dim3(p.total), dim3(kThreads), lds, stream, p);
+    hipLaunchKernelGGL((gemm_round_kernel<T, WT, ALIGNED, FIRST>), dim3(p.total), dim3(kThreads), lds, stream, p);
     return hipGetLastError();
 }
 
@@ -588,7 +668,31 @@ hipError_t launch_gemm(const GemmParams &p, int dtype, int wt, bool ptr_align16,
     return wt == 4 ? launch_gemm_a<float, 4>(p, al, stream) : launch_gemm_a<float, 2>(p, al, stream);
 }
 
+// chain round 1 with the operands formed on the fly (64x64 tiles only)
+template <typename T>
+hipError_t launch_gemm_first(const GemmParams &p, bool aligned, hipStream_t stream)
+{
+    if (aligned && p.n % 64 == 0 && p.n % Tile<T>::BK == 0) return launch_gemm_t<T, 2, kAccessFull, true>(p, stream);
+    return aligned ? launch_gemm_t<T, 2, kAccessVector, true>(p, stream) : launch_gemm_t<T, 2, kAccessScalar, true>(p, stream);
+}
+
 }  // namespace
+
+// True when chain round 1 forms its operands itself and no preparation pass is needed: the main scheme on
+// matrices below 1024, which always run on 64x64 tiles.  (Above, the pass is half a percent of a call and the
+// register-bound 128x128 kernels have no room for the extra vectors.)
+bool first_round_is_self_contained(int n, int scheme)
+{
+    return scheme == kSchemeSastre && n < 1024 && choose_tile_shape(n, 1) == 2;
+}
+
+hipError_t launch_first_round(const GeneralBuffers &gb, int n, int batch, int dtype, hipStream_t stream)
+{
+    const GemmParams p = make_params(gb, n, 1, batch, 2, kSchemeSastre);
+    if (p.total <= 0) return hipSuccess;
+    if (dtype == 1) return launch_gemm_first<double>(p, gb.ptr_align16 && n % 2 == 0, stream);
+    return launch_gemm_first<float>(p, gb.ptr_align16 && n % 4 == 0, stream);
+}
 
 // Tile shape for a round with `matrices` active matrices of order n: 128x128 tiles (WT = 4) for large
 // matrices unless they would leave compute units idle or poorly balanced, 64x64 tiles (WT = 2) otherwise.

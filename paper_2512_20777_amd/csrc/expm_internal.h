@@ -390,6 +390,8 @@ hipError_t launch_power_round(const GeneralBuffers &gb, int n, int batch, int dt
                               hipStream_t stream);
 hipError_t launch_select_plan(const GeneralBuffers &gb, int n, int batch, double eps, int scheme, hipStream_t stream);
 hipError_t launch_prepare(const GeneralBuffers &gb, int n, int batch, int dtype, int scheme, hipStream_t stream);
+bool first_round_is_self_contained(int n, int scheme);
+hipError_t launch_first_round(const GeneralBuffers &gb, int n, int batch, int dtype, hipStream_t stream);
 hipError_t launch_chain_round(const GeneralBuffers &gb, int n, int active, int round, int dtype, int wt, int scheme,
                               hipStream_t stream);
 
