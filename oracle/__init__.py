@@ -13,4 +13,6 @@ from .expm_oracle import (  # noqa: F401
     oracle_select_ps_from_norms,
     oracle_expm_ps_batch,
     oracle_expm_baseline_batch,
+    oracle_lowrank_batch,
+    oracle_lowrank_select_from_norm,
 )

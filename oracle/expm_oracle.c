@@ -36,7 +36,9 @@
  *
  * The file also holds the Paterson-Stockmeyer variant of the paper (Algorithm 3 selection,
  * plain Taylor polynomial T_m, m in {1,2,4,6,9,12,16}) and the baseline of the paper's
- * comparison (its Algorithm 1); see further down.
+ * comparison (its Algorithm 1); see further down.  Last comes the low-rank variant of Sec. 2.2
+ * (W = A1 A2, the series in V = A2 A1, no scaling), pinned in tests/test_lowrank.py by the full-size
+ * exponential of A1 A2, the rank-one closed form, a nilpotent pair and exact-rational checks of the order.
  *
  * Pins (tests/test_oracle_pins.py): the two worked selection examples of the
  * paper (Remark 1; Sec. 4.2, normal matrix of norm 12.8), closed forms
@@ -44,6 +46,7 @@
  * identities, a brute-force long-double series, hand-computed products, and
  * closed-form switch points of the selection for W = x*I.
  */
+#include <float.h>
 #include <math.h>
 #include <stdlib.h>
 #include <string.h>
@@ -619,6 +622,140 @@ int oracle_expm_baseline_batch(const double *W, int n, int batch, double eps, do
             if (work)
                 expm_baseline_matrix(W + (size_t)b * nn, n, eps, X + (size_t)b * nn, work,
                                      &m[b], &s[b], &n1[b], &near[b]);
+        }
+        free(work);
+    }
+    return fail ? -3 : used;
+}
+
+/* ----------------------------------------------------------------------------------------------
+ * Low-rank parameterisation W = A1 A2 (Sec. 2.2, the equation for e^W in terms of V = A2 A1):
+ *     e^W ~ I + A1 ( sum_{i=0..m} V^i / (i+1)! ) A2,   A1: n x t, A2: t x n, V: t x t, no scaling (s = 0).
+ * Order: the Paterson-Stockmeyer orders 1,2,4,6,9,12,16, the smallest whose truncation bound
+ *     ||V||^(m+1) / (m+2)! / (1 - ||V|| / (m+3))          (the bound printed after that equation; Theorem 3 with p = 1)
+ * is at most eps (it needs ||V|| < m+3).  ||V|| = 0 gives m = 0 (the sum is I and the result I + A1 A2 is exact);
+ * if no order reaches eps the largest one is used and flag 2 says that the tolerance is not guaranteed
+ * (this variant does not scale).  m = -1 for a non-finite norm.
+ * ------------------------------------------------------------------------------------------ */
+static double lowrank_bound(double v, int m)
+{
+    if (!(v < (double)(m + 3)))
+        return INFINITY;
+    return ipow(v, m + 1) / factorial(m + 2) / (1.0 - v / (double)(m + 3));
+}
+
+void oracle_lowrank_select_from_norm(double v1, double eps, int *m_out, int *flag_out)
+{
+    static const int M[7] = {1, 2, 4, 6, 9, 12, 16};
+    *flag_out = 0;
+    if (!(v1 <= DBL_MAX)) {
+        *m_out = -1;
+        *flag_out = 1;
+        return;
+    }
+    if (v1 == 0.0) {
+        *m_out = 0;
+        return;
+    }
+    for (int i = 0; i < 7; ++i)
+        if (lowrank_bound(v1, M[i]) <= eps) {
+            *m_out = M[i];
+            return;
+        }
+    *m_out = 16;
+    *flag_out = 2;
+}
+
+/* plain rectangular product C (p x r) = A (p x q) * B (q x r), row-major, i-k-j loop order */
+static void matmul_rect(const double *A, const double *B, double *C, int p, int q, int r)
+{
+    for (int i = 0; i < p; ++i) {
+        double *c = C + (size_t)i * r;
+        for (int j = 0; j < r; ++j)
+            c[j] = 0.0;
+        for (int k = 0; k < q; ++k) {
+            const double a = A[(size_t)i * q + k];
+            const double *b = B + (size_t)k * r;
+            for (int j = 0; j < r; ++j)
+                c[j] += a * b[j];
+        }
+    }
+}
+
+/* One pair (A1, A2).  work: 3*t*t + max(t*n, t*t) doubles.  X: n x n. */
+static void lowrank_matrix(const double *A1, const double *A2, int n, int t, double eps, double *X, double *work,
+                           int *m_out, int *flag_out, double *v1_out, int *near)
+{
+    const size_t tt = (size_t)t * t;
+    double *V = work, *Phi = work + tt, *term = work + 2 * tt, *PA2 = work + 3 * tt; /* PA2: t x n */
+    matmul_rect(A2, A1, V, t, n, t);
+    const double v1 = oracle_norm1(V, t);
+    int m, flag;
+    oracle_lowrank_select_from_norm(v1, eps, &m, &flag);
+    *v1_out = v1;
+    *m_out = m;
+    *flag_out = flag;
+    *near = 0;
+    if (m >= 0) {
+        int ma, mb, fa, fb;
+        oracle_lowrank_select_from_norm(v1 * (1.0 - 1e-6), eps, &ma, &fa);
+        oracle_lowrank_select_from_norm(v1 * (1.0 + 1e-6), eps, &mb, &fb);
+        if (ma != m || mb != m)
+            *near = 1;
+    }
+    if (m < 0) {
+        for (size_t e = 0; e < (size_t)n * n; ++e)
+            X[e] = NAN;
+        return;
+    }
+    /* Phi = sum_{i=0..m} V^i / (i+1)!, term by term: term_0 = I, term_i = term_{i-1} V / (i+1) */
+    memset(Phi, 0, sizeof(double) * tt);
+    memset(term, 0, sizeof(double) * tt);
+    for (int i = 0; i < t; ++i) {
+        Phi[(size_t)i * t + i] = 1.0;
+        term[(size_t)i * t + i] = 1.0;
+    }
+    for (int i = 1; i <= m; ++i) {
+        double *next = PA2; /* the last scratch area holds at least t*t doubles */
+        matmul_rect(term, V, next, t, t, t);
+        for (size_t e = 0; e < tt; ++e) {
+            term[e] = next[e] / (double)(i + 1);
+            Phi[e] += term[e];
+        }
+    }
+    matmul_rect(Phi, A2, PA2, t, t, n);
+    matmul_rect(A1, PA2, X, n, t, n);
+    for (int i = 0; i < n; ++i)
+        X[(size_t)i * n + i] += 1.0;
+}
+
+/* Batch: A1 [batch][n][t], A2 [batch][t][n], X [batch][n][n]; returns threads used or -3. */
+int oracle_lowrank_batch(const double *A1, const double *A2, int n, int t, int batch, double eps, double *X,
+                         int *m, int *flag, double *v1, int *near, int threads)
+{
+    int used = 1;
+#ifdef _OPENMP
+    if (threads <= 0)
+        threads = omp_get_max_threads();
+    used = threads;
+    omp_set_num_threads(threads);
+#else
+    (void)threads;
+#endif
+    int fail = 0;
+    const size_t tt = (size_t)t * t, tn = (size_t)t * n;
+#pragma omp parallel
+    {
+        double *work = (double *)malloc(sizeof(double) * (3 * tt + (tn > tt ? tn : tt)) + 8);
+        if (!work) {
+#pragma omp atomic write
+            fail = 1;
+        }
+#pragma omp for schedule(dynamic, 1)
+        for (int b = 0; b < batch; ++b) {
+            if (work)
+                lowrank_matrix(A1 + (size_t)b * n * t, A2 + (size_t)b * tn, n, t, eps, X + (size_t)b * n * n, work,
+                               &m[b], &flag[b], &v1[b], &near[b]);
         }
         free(work);
     }

@@ -62,6 +62,11 @@ def _load():
         lib.oracle_expm_baseline_batch.restype = ctypes.c_int
         lib.oracle_expm_baseline_batch.argtypes = [dp, ctypes.c_int, ctypes.c_int, ctypes.c_double, dp,
                                                    ip, ip, dp, ip, ctypes.c_int]
+        lib.oracle_lowrank_select_from_norm.restype = None
+        lib.oracle_lowrank_select_from_norm.argtypes = [ctypes.c_double, ctypes.c_double, ip, ip]
+        lib.oracle_lowrank_batch.restype = ctypes.c_int
+        lib.oracle_lowrank_batch.argtypes = [dp, dp, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_double, dp,
+                                             ip, ip, dp, ip, ctypes.c_int]
         lib.oracle_max_threads.restype = ctypes.c_int
         lib.oracle_max_threads.argtypes = []
         _lib = lib
@@ -219,6 +224,37 @@ def oracle_expm_baseline_batch(W, tol: float, threads: int = 0):
         if used < 0:
             raise MemoryError("oracle_expm_baseline_batch")
     return X, dict(m=m, s=s, n1=n1, near=near.astype(bool), threads=used)
+
+
+def oracle_lowrank_select_from_norm(v1: float, tol: float) -> Tuple[int, int]:
+    """Order of the low-rank variant (Sec. 2.2) from ||A2 A1||_1 -> (m, flag); flag 2: tolerance not reached."""
+    m, f = ctypes.c_int(0), ctypes.c_int(0)
+    _load().oracle_lowrank_select_from_norm(float(v1), float(tol), ctypes.byref(m), ctypes.byref(f))
+    return m.value, f.value
+
+
+def oracle_lowrank_batch(A1, A2, tol: float, threads: int = 0):
+    """e^(A1 A2) = I + A1 phi_m(A2 A1) A2 on a batch: A1 [b][n][t], A2 [b][t][n]
+    -> (X fp64 [b][n][n], dict of arrays m, flag, v1, near, threads)."""
+    a1 = np.ascontiguousarray(np.asarray(A1, dtype=np.float64))
+    a2 = np.ascontiguousarray(np.asarray(A2, dtype=np.float64))
+    if a1.ndim == 2:
+        a1, a2 = a1[None], a2[None]
+    assert a1.ndim == 3 and a2.ndim == 3 and a1.shape[0] == a2.shape[0]
+    b, n, t = a1.shape
+    assert a2.shape[1] == t and a2.shape[2] == n
+    X = np.empty((b, n, n), dtype=np.float64)
+    m = np.zeros(b, dtype=np.int32)
+    flag = np.zeros(b, dtype=np.int32)
+    near = np.zeros(b, dtype=np.int32)
+    v1 = np.zeros(b, dtype=np.float64)
+    used = 0
+    if b > 0 and n > 0 and t > 0:
+        used = _load().oracle_lowrank_batch(_dptr(a1), _dptr(a2), n, t, b, float(tol), _dptr(X), _iptr(m), _iptr(flag),
+                                            _dptr(v1), _iptr(near), int(threads))
+        if used < 0:
+            raise MemoryError("oracle_lowrank_batch")
+    return X, dict(m=m, flag=flag, v1=v1, near=near.astype(bool), threads=used)
 
 
 def oracle_max_threads() -> int:
