@@ -111,6 +111,7 @@ int expm(const void *A, int n, int batch, int dtype, double tol, void *out, void
 #define EXPM_SCHEME_SASTRE   0
 #define EXPM_SCHEME_PS       1
 #define EXPM_SCHEME_BASELINE 2
+#define EXPM_SCHEME_LOWRANK_CORE 3  /* reported by expm_get_stats() after expm_lowrank(); not an argument value */
 int expm_select_scheme(const void *A, int n, int batch, int dtype, double tol, int scheme,
                        int32_t *m_out, int32_t *s_out);
 int expm_scheme(const void *A, int n, int batch, int dtype, double tol, int scheme, void *out, void *stream);
@@ -128,6 +129,30 @@ int expm_select_ex(const void *A, int n, int batch, int dtype, double tol, int s
                    int32_t *m_out, int32_t *s_out);
 int expm_ex(const void *A, int n, int batch, int dtype, double tol, int scheme, int norm_kind, void *out,
             void *stream);
+
+/*
+ * Low-rank variant (Sec. 2.2): for W = A1 A2 with A1 n x t and A2 t x n,
+ *     e^W = I + A1 (sum_{i=0..m} V^i / (i+1)!) A2,   V = A2 A1  (t x t),
+ * evaluated without scaling (s = 0, as the paper prescribes for this variant).  The order m is the smallest of
+ * 1, 2, 4, 6, 9, 12, 16 whose truncation bound ||V||_1^(m+1) / (m+2)! / (1 - ||V||_1/(m+3)) (the bound printed
+ * with that equation; Theorem 3 with p = 1) is at most tol; the series is evaluated by Paterson-Stockmeyer
+ * (powers up to V^j, Horner in V^j; the paper does not print optimised coefficients for this series).
+ * ||V||_1 = 0 gives m = 0 and the exact result I + A1 A2.  If no order reaches tol (||V||_1 beyond about 1 at
+ * tol = 2^-53, 2.9 at 1e-8) the largest order is used and EXPM_WARN_SCALING_CAP is reported: tolerance not
+ * guaranteed.  A non-finite V gives m = -1 and an all-NaN result (EXPM_WARN_NONFINITE).
+ *
+ *   A1     DEVICE, const, [batch][n][t] row-major.      A2   DEVICE, const, [batch][t][n] row-major.
+ *   n, t   >= 0; t <= 128 (fp32) / 96 (fp64), otherwise EXPM_ERR_UNSUPPORTED; batch <= 65535.
+ *   tol    as for expm_select.                           out  DEVICE, [batch][n][n], must not overlap A1, A2.
+ *   m_out  HOST, int32[batch].
+ * expm_lowrank_select is synchronous (null stream) and returns the warning; expm_lowrank is asynchronous on
+ * `stream` and returns 0 or an error, its warnings surface through expm_get_stats() (n of the statistics is t,
+ * products counts the t x t products of the core series).  Both use the cached workspace.
+ */
+int expm_lowrank_select(const void *A1, const void *A2, int n, int t, int batch, int dtype, double tol,
+                        int32_t *m_out);
+int expm_lowrank(const void *A1, const void *A2, int n, int t, int batch, int dtype, double tol, void *out,
+                 void *stream);
 
 /*
  * Bytes of device workspace the library holds for a call of this shape (the fused

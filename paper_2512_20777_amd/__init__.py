@@ -14,6 +14,8 @@ from .binding import (  # noqa: F401
     ExpmError,
     expm,
     expm_get_stats,
+    expm_lowrank,
+    expm_lowrank_select,
     expm_profile_enable,
     expm_profile_read,
     expm_profile_reset,

@@ -77,6 +77,10 @@ def load_library():
     lib.expm_select_ex.argtypes = [vp, ci, ci, ci, cd, ci, ci, i32p, i32p]
     lib.expm_ex.restype = ci
     lib.expm_ex.argtypes = [vp, ci, ci, ci, cd, ci, ci, vp, vp]
+    lib.expm_lowrank_select.restype = ci
+    lib.expm_lowrank_select.argtypes = [vp, vp, ci, ci, ci, ci, cd, i32p]
+    lib.expm_lowrank.restype = ci
+    lib.expm_lowrank.argtypes = [vp, vp, ci, ci, ci, ci, cd, vp, vp]
     lib.expm_workspace_bytes.restype = ctypes.c_size_t
     lib.expm_workspace_bytes.argtypes = [ci, ci, ci]
     lib.expm_reserve.restype = ci
@@ -167,6 +171,56 @@ def expm(A, tol: float = 0.0, out=None, stream=None, scheme: int = SCHEME_SASTRE
     else:
         with torch.cuda.device(dev):
             st = lib.expm_ex(A.data_ptr(), n, batch, dt, tol, scheme, norm, out.data_ptr(), sp)
+    if st < 0:
+        _check(st)
+    return out, st
+
+
+def _describe_pair(A1, A2):
+    import torch
+    for x in (A1, A2):
+        if not isinstance(x, torch.Tensor) or not x.is_cuda:
+            raise ExpmError(-1, "inputs must be torch tensors in device memory")
+        if x.dim() != 3 or not x.is_contiguous():
+            raise ExpmError(-1, "inputs must be contiguous [batch][n][t] and [batch][t][n]")
+    b, n, t = A1.shape
+    if tuple(A2.shape) != (b, t, n) or A2.dtype is not A1.dtype or A2.device != A1.device:
+        raise ExpmError(-1, "A2 must be [batch][t][n] of the dtype and on the device of A1")
+    if A1.dtype is torch.float32:
+        dt = DTYPE_F32
+    elif A1.dtype is torch.float64:
+        dt = DTYPE_F64
+    else:
+        raise ExpmError(-1, "dtype must be float32 or float64")
+    return n, t, b, dt
+
+
+def expm_lowrank_select(A1, A2, tol: float = 0.0):
+    """Order m of the low-rank variant per pair (int32 numpy array) and the status."""
+    import numpy as np
+    import torch
+    n, t, batch, dt = _describe_pair(A1, A2)
+    m = np.zeros(batch, dtype=np.int32)
+    with torch.cuda.device(A1.device):
+        torch.cuda.current_stream().synchronize()  # the C entry point runs on the null stream
+        st = load_library().expm_lowrank_select(A1.data_ptr(), A2.data_ptr(), n, t, batch, dt, float(tol),
+                                                m.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)))
+    return m, _check(st)
+
+
+def expm_lowrank(A1, A2, tol: float = 0.0, out=None, stream=None):
+    """e^(A1 A2) = I + A1 phi(A2 A1) A2 for [batch][n][t] and [batch][t][n] device tensors; returns (out, status)."""
+    import torch
+    lib = _lib if _lib is not None else load_library()
+    n, t, batch, dt = _describe_pair(A1, A2)
+    if out is None:
+        out = torch.empty((batch, n, n), dtype=A1.dtype, device=A1.device)
+    elif tuple(out.shape) != (batch, n, n) or out.dtype is not A1.dtype or out.device != A1.device or not out.is_contiguous():
+        raise ExpmError(-1, "out must be a contiguous [batch][n][n] tensor of the inputs' dtype and device")
+    dev = A1.device.index
+    sp = stream.cuda_stream if stream is not None else torch.cuda.current_stream(dev).cuda_stream
+    with torch.cuda.device(dev):
+        st = lib.expm_lowrank(A1.data_ptr(), A2.data_ptr(), n, t, batch, dt, tol, out.data_ptr(), sp)
     if st < 0:
         _check(st)
     return out, st

@@ -12,7 +12,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _CSRC = os.path.join(_HERE, "csrc")
 LIB_NAME = "libexpm_mi355x.so"
 LIB_PATH = os.path.join(_HERE, LIB_NAME)
-SOURCES = ["expm_api.hip", "expm_general.hip", "expm_fused.hip"]
+SOURCES = ["expm_api.hip", "expm_general.hip", "expm_fused.hip", "expm_lowrank.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

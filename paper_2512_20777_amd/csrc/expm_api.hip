@@ -438,6 +438,135 @@ int expm_ex(const void *A, int n, int batch, int dtype, double tol, int scheme, 
     return warning_from_flags(flags);
 }
 
+// ---- low-rank variant (Sec. 2.2): e^(A1 A2) = I + A1 phi(A2 A1) A2 ------------------------------------------
+namespace {
+
+struct LowrankLayout {
+    Layout ctl;
+    size_t V, Phi, U, total;
+};
+
+LowrankLayout make_lowrank_layout(int n, int t, int batch, int dtype)
+{
+    LowrankLayout L{};
+    const size_t w = dtype == EXPM_DTYPE_F64 ? 8 : 4;
+    L.ctl = make_layout(t, batch, dtype);  // t is within the fused path: control records only
+    size_t off = align_up(L.ctl.total, 256);
+    L.V = off;   off = align_up(off + (size_t)batch * t * t * w, 256);
+    L.Phi = off; off = align_up(off + (size_t)batch * t * t * w, 256);
+    L.U = off;   off = align_up(off + (size_t)batch * n * t * w, 256);
+    L.total = off;
+    return L;
+}
+
+int check_lowrank_args(const void *A1, const void *A2, int n, int t, int batch, int dtype, double &tol)
+{
+    if (n < 0 || t < 0 || batch < 0) return EXPM_ERR_INVALID_ARG;
+    if (dtype != EXPM_DTYPE_F32 && dtype != EXPM_DTYPE_F64) return EXPM_ERR_INVALID_ARG;
+    if (n > 0 && t > 0 && batch > 0 && (A1 == nullptr || A2 == nullptr)) return EXPM_ERR_INVALID_ARG;
+    if (n > 46340 || batch > 65535) return EXPM_ERR_INVALID_ARG;  // int index arithmetic; the batch is a grid dimension
+    if ((double)batch * (double)n * (double)n > 9.0e15) return EXPM_ERR_INVALID_ARG;
+    const double u = dtype == EXPM_DTYPE_F64 ? ldexp(1.0, -53) : ldexp(1.0, -24);
+    if (!(tol == tol) || tol < 0.0) return EXPM_ERR_TOLERANCE;
+    if (tol == 0.0) tol = u;
+    if (tol < u) return EXPM_ERR_TOLERANCE;
+    if (t > 0 && !small_path_supported(t, dtype)) return EXPM_ERR_UNSUPPORTED;  // the core series runs on chip
+    return EXPM_OK;
+}
+
+// V = A2 A1 and, unless select_only, Phi = series of V; leaves the per-matrix records (m, flags) in the workspace
+int run_lowrank_core(const void *A1, const void *A2, int n, int t, int batch, int dtype, double tol, int select_only,
+                     const LowrankLayout &L, hipStream_t stream)
+{
+    unsigned char *base = static_cast<unsigned char *>(g_ws.dev);
+    const double w = dtype == EXPM_DTYPE_F64 ? 8.0 : 4.0;
+    {
+        Bracket br(stream, EXPM_KCLASS_GEMM, 2.0 * t * (double)t * n * batch, ((2.0 * n * t) + (double)t * t) * batch * w);
+        EXPM_TRY(launch_rect_gemm(A2, A1, base + L.V, t, t, n, n, t, t, (size_t)t * n, (size_t)n * t, (size_t)t * t, batch,
+                                  dtype, 0, stream));
+    }
+    Bracket br(stream, EXPM_KCLASS_FUSED, 0.0, 2.0 * batch * (double)t * t * w);
+    EXPM_TRY(launch_small(base + L.V, base + L.Phi, t, batch, dtype, tol, select_only, kSchemePhi, 0,
+                          reinterpret_cast<MatInfo *>(base + L.ctl.info), stream));
+    return EXPM_OK;
+}
+
+void remember_lowrank(int t, int batch, int dtype, hipStream_t stream, const LowrankLayout &L)
+{
+    g_last.valid = true;
+    g_last.scheme = kSchemePhi;
+    g_last.n = t; g_last.batch = batch; g_last.dtype = dtype;
+    g_last.rounds = 0; g_last.fused = 1; g_last.stream = stream;
+    g_last.info_dev = reinterpret_cast<MatInfo *>(static_cast<unsigned char *>(g_ws.dev) + L.ctl.info);
+    g_last.summary_dev = reinterpret_cast<int *>(static_cast<unsigned char *>(g_ws.dev) + L.ctl.summary);
+}
+
+}  // namespace
+
+int expm_lowrank_select(const void *A1, const void *A2, int n, int t, int batch, int dtype, double tol, int32_t *m_out)
+{
+    int rc = check_lowrank_args(A1, A2, n, t, batch, dtype, tol);
+    if (rc != EXPM_OK) return rc;
+    if (batch > 0 && m_out == nullptr) return EXPM_ERR_INVALID_ARG;
+    if (batch == 0) return EXPM_OK;
+    if (n == 0 || t == 0) {
+        for (int b = 0; b < batch; ++b) m_out[b] = 0;
+        return EXPM_OK;
+    }
+    const LowrankLayout L = make_lowrank_layout(n, t, batch, dtype);
+    rc = ensure_workspace(L.total, batch);
+    if (rc != EXPM_OK) return rc;
+    hipStream_t stream = nullptr;
+    rc = run_lowrank_core(A1, A2, n, t, batch, dtype, tol, 1, L, stream);
+    if (rc != EXPM_OK) return rc;
+    remember_lowrank(t, batch, dtype, stream, L);
+    EXPM_TRY(hipMemcpyAsync(g_ws.host_info, g_last.info_dev, (size_t)batch * sizeof(MatInfo), hipMemcpyDeviceToHost, stream));
+    EXPM_TRY(hipStreamSynchronize(stream));
+    int flags = 0;
+    for (int b = 0; b < batch; ++b) {
+        m_out[b] = g_ws.host_info[b].m;
+        flags |= g_ws.host_info[b].flags;
+    }
+    return warning_from_flags(flags);
+}
+
+int expm_lowrank(const void *A1, const void *A2, int n, int t, int batch, int dtype, double tol, void *out, void *stream_v)
+{
+    int rc = check_lowrank_args(A1, A2, n, t, batch, dtype, tol);
+    if (rc != EXPM_OK) return rc;
+    if (n == 0 || batch == 0) return EXPM_OK;
+    if (out == nullptr) return EXPM_ERR_INVALID_ARG;
+    const size_t w = dtype == EXPM_DTYPE_F64 ? 8 : 4;
+    {
+        const uintptr_t o0 = (uintptr_t)out, ob = (size_t)batch * n * n * w, ib = (size_t)batch * n * t * w;
+        const uintptr_t a1 = (uintptr_t)A1, a2 = (uintptr_t)A2;
+        if (t > 0 && ((a1 < o0 + ob && o0 < a1 + ib) || (a2 < o0 + ob && o0 < a2 + ib))) return EXPM_ERR_INVALID_ARG;
+        if ((o0 | (t > 0 ? (a1 | a2) : 0)) % w) return EXPM_ERR_INVALID_ARG;
+    }
+    hipStream_t stream = static_cast<hipStream_t>(stream_v);
+    const LowrankLayout L = make_lowrank_layout(n, t, batch, dtype);
+    rc = ensure_workspace(L.total, batch);
+    if (rc != EXPM_OK) return rc;
+    unsigned char *base = static_cast<unsigned char *>(g_ws.dev);
+    if (t > 0) {
+        rc = run_lowrank_core(A1, A2, n, t, batch, dtype, tol, 0, L, stream);
+        if (rc != EXPM_OK) return rc;
+        // U = A1 Phi
+        Bracket br(stream, EXPM_KCLASS_GEMM, 2.0 * n * (double)t * t * batch, (2.0 * n * t + (double)t * t) * batch * (double)w);
+        EXPM_TRY(launch_rect_gemm(A1, base + L.Phi, base + L.U, n, t, t, t, t, t, (size_t)n * t, (size_t)t * t, (size_t)n * t,
+                                  batch, dtype, 0, stream));
+    }
+    {
+        // out = U A2 + I  (t = 0: the empty product, out = I)
+        Bracket br(stream, EXPM_KCLASS_GEMM, 2.0 * n * (double)n * t * batch, ((double)n * n + 2.0 * n * t) * batch * (double)w);
+        EXPM_TRY(launch_rect_gemm(base + L.U, A2, out, n, n, t, t, n, n, (size_t)n * t, (size_t)t * n, (size_t)n * n, batch,
+                                  dtype, 1, stream));
+    }
+    if (t > 0) remember_lowrank(t, batch, dtype, stream, L);
+    else g_last.valid = false;
+    return EXPM_OK;
+}
+
 int expm_get_stats(struct expm_stats *st)
 {
     if (!st) return EXPM_ERR_INVALID_ARG;
@@ -462,6 +591,8 @@ int expm_get_stats(struct expm_stats *st)
         int pi = 0;
         if (g_last.scheme == kSchemePS) {
             pi = mi.m < 2 ? 0 : ps_j(mi.m) - 1 + ps_k(mi.m) - 1;
+        } else if (g_last.scheme == kSchemePhi) {
+            pi = mi.m < 2 ? 0 : ps_j(mi.m) - 1 + ps_k(mi.m) - 1;   // products of the t x t core series only
         } else if (g_last.scheme == kSchemeBaseline) {
             pi = mi.m < 1 ? 0 : mi.m - 1;   // the paper prices degree m at (m-1) products (its eq. for C_orig)
         } else {

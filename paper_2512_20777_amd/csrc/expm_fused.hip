@@ -407,6 +407,38 @@ __global__ __launch_bounds__(256) void fused_expm_kernel(const T *__restrict__ A
             nrm[3] = norm_regs([&](int ti, int tj, int v) { return a4v[ti][tj][v]; });
             select_ps_order_scaling(nrm, 4, eps, m, s, flags, need_more);
         }
+    } else if constexpr (SCHEME == kSchemePhi) {
+        // Core series of the low-rank variant: the order follows from the norm alone, no scaling; the powers the
+        // Paterson-Stockmeyer form of that order needs are formed as above (P: newest power, Q: the matrix).
+        select_lowrank_order(n1, eps, m, flags);
+        const int jn = m >= 0 ? ps_j(m) : 0;
+        if (jn >= 2) {
+            product(P, Q);
+            sync();
+            for_owned([&](int ti, int tj, int v, int r, int c) {
+                a2v[ti][tj][v] = acc[ti][tj][v];
+                P[li(r, c)] = acc[ti][tj][v];
+            });
+            sync();
+        }
+        if (jn >= 3) {
+            product(P, Q);
+            sync();
+            for_owned([&](int ti, int tj, int v, int r, int c) {
+                a3v[ti][tj][v] = acc[ti][tj][v];
+                P[li(r, c)] = acc[ti][tj][v];
+            });
+            sync();
+        }
+        if (jn >= 4) {
+            product(P, Q);
+            sync();
+            for_owned([&](int ti, int tj, int v, int r, int c) {
+                a4v[ti][tj][v] = acc[ti][tj][v];
+                P[li(r, c)] = acc[ti][tj][v];
+            });
+            sync();
+        }
     } else if constexpr (SCHEME == kSchemeBaseline) {
         // The comparison baseline of the paper (its Algorithm 1): s from ||W|| / 2^s < 1/2, then Taylor terms
         // Y <- W Y / k are added while ||Y|| > eps.  The whole loop runs here because the degree reached
@@ -473,8 +505,10 @@ __global__ __launch_bounds__(256) void fused_expm_kernel(const T *__restrict__ A
 
     if constexpr (SCHEME == kSchemeBaseline) {
         // nothing left to evaluate: the term loop above produced X
-    } else if constexpr (SCHEME == kSchemePS) {
-        // ---- Paterson-Stockmeyer: T_m(A) = Horner in A^j with blocks of degree < j, m = j*k -----------------
+    } else if constexpr (SCHEME == kSchemePS || SCHEME == kSchemePhi) {
+        // ---- Paterson-Stockmeyer: sum_i c_i A^i = Horner in A^j with blocks of degree < j, m = j*k ----------
+        // c_i = 1/i! (the Taylor polynomial T_m) or 1/(i+1)! (the series of the low-rank variant)
+        constexpr int kShift = SCHEME == kSchemePhi ? 1 : 0;
         const int j = ps_j(m), k = ps_k(m);
         if (s > 0) {
             const T sg = (T)pow2neg_f(s), sg2 = (T)pow2neg_f(2 * s), sg3 = (T)pow2neg_f(3 * s), sg4 = (T)pow2neg_f(4 * s);
@@ -489,16 +523,17 @@ __global__ __launch_bounds__(256) void fused_expm_kernel(const T *__restrict__ A
             return r == 1 ? av[ti][tj][v] : (r == 2 ? a2v[ti][tj][v] : (r == 3 ? a3v[ti][tj][v] : a4v[ti][tj][v]));
         };
         if (k == 1) {  // orders 0, 1, 2: no further product
+            const T c1 = (T)inv_factorial(1 + kShift), c2 = (T)inv_factorial(2 + kShift);
             for_owned([&](int ti, int tj, int v, int r, int c) {
                 T x = dg(r, c);
-                if (m >= 1) x += av[ti][tj][v];
-                if (m == 2) x += a2v[ti][tj][v] / (T)2;
+                if (m >= 1) x += c1 * av[ti][tj][v];
+                if (m == 2) x += c2 * a2v[ti][tj][v];
                 xv[ti][tj][v] = x;
             });
         } else {
             T cf[5];
 #pragma unroll
-            for (int r = 0; r <= 4; ++r) cf[r] = r <= j ? (T)inv_factorial((k - 1) * j + r) : (T)0;
+            for (int r = 0; r <= 4; ++r) cf[r] = r <= j ? (T)inv_factorial((k - 1) * j + r + kShift) : (T)0;
             sync();  // every wave is done with P (norm) before it is overwritten
             for_owned([&](int ti, int tj, int v, int r, int c) {
                 T h = cf[0] * dg(r, c) + cf[1] * av[ti][tj][v] + cf[2] * a2v[ti][tj][v];
@@ -509,7 +544,7 @@ __global__ __launch_bounds__(256) void fused_expm_kernel(const T *__restrict__ A
             store_right([&](int ti, int tj, int v, int, int) { return pw(j, ti, tj, v); });  // right operand of every Horner step: A^j
             for (int q = k - 2; q >= 0; --q) {
 #pragma unroll
-                for (int r = 0; r <= 3; ++r) cf[r] = r < j ? (T)inv_factorial(q * j + r) : (T)0;
+                for (int r = 0; r <= 3; ++r) cf[r] = r < j ? (T)inv_factorial(q * j + r + kShift) : (T)0;
                 sync();
                 product(P, Q);
                 for_owned([&](int ti, int tj, int v, int r, int c) {
@@ -935,7 +970,7 @@ hipError_t launch_small(const void *A, void *out, int n, int batch, int dtype, d
                         int scheme, int norm_inf, MatInfo *info, hipStream_t stream)
 {
     const int nt = (n + 15) / 16;
-    if (nt == 1 && dtype == 1) {
+    if (nt == 1 && dtype == 1 && scheme != kSchemePhi) {
         // One tile in fp64: the register-resident kernel.  (In fp32 the doubled matrix-core work of that design
         // costs more than the LDS round trips of the general kernel save, so fp32 stays there.)
         return scheme == kSchemePS
@@ -944,18 +979,18 @@ hipError_t launch_small(const void *A, void *out, int n, int batch, int dtype, d
                           ? launch_tile_t<double, kSchemeBaseline>(A, out, n, batch, eps, select_only, norm_inf, info, stream)
                           : launch_tile_t<double, kSchemeSastre>(A, out, n, batch, eps, select_only, norm_inf, info, stream));
     }
-#define EXPM_FUSED_CASE(TYPE, K)                                                                              \
-    case K:                                                                                                   \
-        return scheme == kSchemePS                                                                            \
-                   ? launch_fused_t<TYPE, K, kSchemePS>(A, out, n, batch, eps, select_only, norm_inf, info,   \
-                                                        stream)                                              \
-                   : (scheme == kSchemeBaseline                                                               \
-                          ? launch_fused_t<TYPE, K, kSchemeBaseline>(A, out, n, batch, eps, select_only,      \
-                                                                     norm_inf, info, stream)                  \
-                          : launch_fused_t<TYPE, K, kSchemeSastre>(A, out, n, batch, eps, select_only,        \
-                                                                   norm_inf, info, stream));
+#define EXPM_FUSED_ARGS A, out, n, batch, eps, select_only, norm_inf, info, stream
+#define EXPM_FUSED_CASE(TYPE, K)                                                               \
+    case K:                                                                                    \
+        switch (scheme) {                                                                      \
+        case kSchemePS: return launch_fused_t<TYPE, K, kSchemePS>(EXPM_FUSED_ARGS);            \
+        case kSchemeBaseline: return launch_fused_t<TYPE, K, kSchemeBaseline>(EXPM_FUSED_ARGS); \
+        case kSchemePhi: return launch_fused_t<TYPE, K, kSchemePhi>(EXPM_FUSED_ARGS);          \
+        default: return launch_fused_t<TYPE, K, kSchemeSastre>(EXPM_FUSED_ARGS);               \
+        }
     if (dtype == 1) {
         switch (nt) {
+        case 1: return launch_fused_t<double, 1, kSchemePhi>(EXPM_FUSED_ARGS);  // the other schemes: tile kernel above
             EXPM_FUSED_CASE(double, 2) EXPM_FUSED_CASE(double, 3)
             EXPM_FUSED_CASE(double, 4) EXPM_FUSED_CASE(double, 5) EXPM_FUSED_CASE(double, 6)
         default: return hipErrorInvalidValue;
@@ -967,6 +1002,7 @@ hipError_t launch_small(const void *A, void *out, int n, int batch, int dtype, d
     default: return hipErrorInvalidValue;
     }
 #undef EXPM_FUSED_CASE
+#undef EXPM_FUSED_ARGS
 }
 
 }  // namespace expmk

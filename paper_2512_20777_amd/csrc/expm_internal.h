@@ -184,12 +184,40 @@ __host__ __device__ inline int chain_length_ps(int m, int s)
     return ps_k(m) - 1 + s;
 }
 
-// 1/i!, i = 0..16 (i! is exact in double up to 18!, so this is the correctly rounded reciprocal)
+// 1/i!, i = 0..18 (i! is exact in double up to 18!, so this is the correctly rounded reciprocal)
 __host__ __device__ inline double inv_factorial(int i)
 {
     double f = 1.0;
     for (int q = 2; q <= i; ++q) f *= (double)q;
     return 1.0 / f;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Low-rank variant (Sec. 2.2): e^(A1 A2) = I + A1 (sum_{i<=m} V^i/(i+1)!) A2 with V = A2 A1 and no scaling.
+// Order from v1 = ||V||_1: the smallest of the Paterson-Stockmeyer orders whose truncation bound
+// v1^(m+1)/(m+2)!/(1 - v1/(m+3)) (printed after that equation; Theorem 3 with p = 1) is at most eps.
+// v1 = 0: m = 0 (the sum is I, the result exact).  No order reaches eps: the largest, flag bit 1.
+// ---------------------------------------------------------------------------------------------
+__host__ __device__ inline void select_lowrank_order(double v1, double eps, int &m, int &flags)
+{
+    flags = 0;
+    if (!(v1 <= 1.7976931348623157e308)) {
+        m = -1; flags = 1;
+        return;
+    }
+    m = 0;
+    if (v1 == 0.0) return;
+    const int M[7] = {1, 2, 4, 6, 9, 12, 16};
+    for (int i = 0; i < 7; ++i) {
+        m = M[i];
+        if (v1 < (double)(m + 3)) {
+            double pw = 1.0;
+            for (int q = 0; q <= m; ++q) pw *= v1;
+            if (pw * inv_factorial(m + 2) / (1.0 - v1 / (double)(m + 3)) <= eps) return;
+        }
+    }
+    m = 16;
+    flags |= 2;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -228,6 +256,7 @@ template <> struct Mfma<float> {
 constexpr int kSchemeSastre = 0;  // evaluation formulas of Sec. 3.1 with Algorithm 4
 constexpr int kSchemePS = 1;      // Paterson-Stockmeyer with Algorithm 3
 constexpr int kSchemeBaseline = 2;  // the paper's comparison baseline (its Algorithm 1); fused path only
+constexpr int kSchemePhi = 3;       // core series of the low-rank variant, sum_i V^i/(i+1)!, no scaling; fused path only
 
 enum Buf : int { BUF_W = 0, BUF_W2 = 1, BUF_T0 = 2, BUF_T1 = 3, BUF_T2 = 4, BUF_T3 = 5, BUF_T4 = 6, BUF_T5 = 7,
                  BUF_OUT = 8, BUF_COUNT = 9,
@@ -390,6 +419,9 @@ hipError_t launch_power_round(const GeneralBuffers &gb, int n, int batch, int dt
                               hipStream_t stream);
 hipError_t launch_select_plan(const GeneralBuffers &gb, int n, int batch, double eps, int scheme, hipStream_t stream);
 hipError_t launch_prepare(const GeneralBuffers &gb, int n, int batch, int dtype, int scheme, hipStream_t stream);
+hipError_t launch_rect_gemm(const void *A, const void *B, void *C, int M, int N, int K, int lda, int ldb, int ldc,
+                            size_t stride_a, size_t stride_b, size_t stride_c, int batch, int dtype, int add_identity,
+                            hipStream_t stream);
 bool first_round_is_self_contained(int n, int scheme);
 hipError_t launch_first_round(const GeneralBuffers &gb, int n, int batch, int dtype, hipStream_t stream);
 hipError_t launch_chain_round(const GeneralBuffers &gb, int n, int active, int round, int dtype, int wt, int scheme,

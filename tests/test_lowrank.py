@@ -98,3 +98,116 @@ def test_oracle_lowrank_order_is_the_smallest_that_meets_the_printed_bound(eps):
     assert oracle_lowrank_select_from_norm(0.0, eps) == (0, 0)
     assert oracle_lowrank_select_from_norm(float("nan"), eps) == (-1, 1)
     assert oracle_lowrank_select_from_norm(50.0, eps) == (16, 2)
+
+
+# ------------------------------------------------------------------------------------------------
+# GPU parity through the C ABI
+# ------------------------------------------------------------------------------------------------
+GATE = {np.dtype(np.float64): 1e-11, np.dtype(np.float32): 5e-5}
+
+
+@pytest.fixture(scope="module")
+def ex():
+    import torch
+    import paper_2512_20777_amd as ex
+    assert torch.cuda.is_available(), "GPU tests need a device"
+    ex.load_library()
+    return ex
+
+
+def _stack(seed, batch, n, t, dtype, lo, hi):
+    """Pairs whose ||A2 A1||_1 is log-uniform in [lo, hi] (the recipe of the square workloads, applied to V)."""
+    rng = np.random.default_rng(seed)
+    a1 = np.empty((batch, n, t)); a2 = np.empty((batch, t, n))
+    for b in range(batch):
+        a1[b], a2[b] = _pair(rng, n, t, float(lo * (hi / lo) ** rng.uniform()))
+    return a1.astype(dtype), a2.astype(dtype)
+
+
+def _check_lowrank(ex, a1, a2, tol, label):
+    import torch
+    from oracle import oracle_lowrank_batch, oracle_lowrank_select_from_norm
+    X, info = oracle_lowrank_batch(a1, a2, tol)
+    d1, d2 = torch.from_numpy(a1).cuda(), torch.from_numpy(a2).cuda()
+    print("case %s A1 %s A2 %s %s" % (label, a1.shape, a2.shape, a1.dtype), flush=True)
+    out, _ = ex.expm_lowrank(d1, d2, tol)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy().astype(np.float64)
+    stats = ex.expm_get_stats()
+    m, st = ex.expm_lowrank_select(d1, d2, tol)
+    worst, worst_off = 0.0, 0.0
+    for b in range(a1.shape[0]):
+        if m[b] != info["m"][b]:
+            assert info["near"][b], (label, b, m[b], info["m"][b], info["v1"][b])
+            corners = {oracle_lowrank_select_from_norm(info["v1"][b] * f, tol)[0] for f in (1 - 1e-6, 1 + 1e-6)}
+            assert int(m[b]) in corners
+            continue
+        err = np.linalg.norm(got[b] - X[b]) / np.linalg.norm(X[b])
+        worst = max(worst, err)
+        assert err <= GATE[a1.dtype], (label, b, m[b], err)
+        # X is I plus something small: the same gate on the off-diagonal part alone, which the identity does not mask
+        off = ~np.eye(X.shape[1], dtype=bool)
+        if X.shape[1] > 1 and np.linalg.norm(X[b][off]) > 0:
+            err_off = np.linalg.norm((got[b] - X[b])[off]) / np.linalg.norm(X[b][off])
+            worst_off = max(worst_off, err_off)
+            assert err_off <= GATE[a1.dtype], (label, b, m[b], err_off)
+    print("   worst rel Frobenius error %.3e (off-diagonal part %.3e), orders %s, status %d"
+          % (worst, worst_off, sorted(set(int(x) for x in m)), st), flush=True)
+    return m, st, stats, info
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("n,t,dtype", [(64, 16, np.float64), (200, 33, np.float64), (96, 96, np.float64), (7, 3, np.float64),
+                                       (256, 64, np.float32), (130, 17, np.float32), (300, 128, np.float32),
+                                       (40, 1, np.float32)])
+def test_gpu_lowrank_parity(ex, n, t, dtype):
+    u = U32 if dtype == np.float32 else U64
+    hi = 2.0 if dtype == np.float32 else 0.9
+    a1, a2 = _stack(4000 + n + t, 12, n, t, dtype, 1e-7, hi)
+    m, st, stats, info = _check_lowrank(ex, a1, a2, u, "lowrank n=%d t=%d" % (n, t))
+    assert st == 0 and stats["warning"] == 0 and stats["fused_path"] == 1 and stats["n"] == t
+    assert len(set(int(x) for x in m)) >= 3
+
+
+@pytest.mark.gpu
+def test_gpu_lowrank_user_tolerance_orders_and_flags(ex):
+    """eps = 1e-8 as in the paper's experiments: all seven orders occur; a norm beyond the reach of order 16 is
+    flagged, not silently wrong; a pair with A2 A1 = 0 is exact with order 0; non-finite input gives NaN."""
+    import torch
+    n, t = 48, 8
+    a1, a2 = _stack(4100, 40, n, t, np.float64, 1e-5, 2.8)
+    a1[0], a2[0] = a1[0] * 3.0, a2[0] * 3.0                 # ||V|| ~ 9x larger: beyond order 16 at 1e-8
+    a1[1][:] = 0.0; a2[1][:] = 0.0
+    a1[1][:4, :] = 1.0; a2[1][:, 8:] = 2.0                  # A2 A1 = 0, A1 A2 != 0
+    m, st, stats, info = _check_lowrank(ex, a1, a2, 1e-8, "lowrank eps=1e-8")
+    assert set(int(x) for x in m) >= {0, 1, 2, 4, 6, 9, 12, 16}
+    if info["flag"][0] == 2:
+        assert st == 2 and stats["warning"] == 2
+    assert m[1] == 0
+    d1, d2 = torch.from_numpy(a1).cuda(), torch.from_numpy(a2).cuda()
+    out, _ = ex.expm_lowrank(d1, d2, 1e-8)
+    assert np.array_equal(out[1].cpu().numpy(), np.eye(n) + a1[1] @ a2[1])
+    a1[2][3, 1] = np.nan
+    d1 = torch.from_numpy(a1).cuda()
+    out, _ = ex.expm_lowrank(d1, d2, 1e-8)
+    torch.cuda.synchronize()
+    assert bool(torch.isnan(out[2]).all()) and bool(torch.isfinite(out[3]).all())
+    m2, st2 = ex.expm_lowrank_select(d1, d2, 1e-8)
+    assert m2[2] == -1 and st2 in (1, 2)
+
+
+@pytest.mark.gpu
+def test_gpu_lowrank_argument_checks_and_empty_shapes(ex):
+    import torch
+    a1 = torch.zeros(2, 10, 200, dtype=torch.float32, device="cuda")
+    a2 = torch.zeros(2, 200, 10, dtype=torch.float32, device="cuda")
+    with pytest.raises(ex.ExpmError) as e:
+        ex.expm_lowrank(a1, a2)                              # t = 200 is beyond the on-chip core
+    assert e.value.status == -5
+    with pytest.raises(ex.ExpmError):
+        ex.expm_lowrank(a1, a2.transpose(1, 2).contiguous())
+    b1 = torch.zeros(3, 5, 0, dtype=torch.float64, device="cuda")
+    b2 = torch.zeros(3, 0, 5, dtype=torch.float64, device="cuda")
+    out, st = ex.expm_lowrank(b1, b2)                        # t = 0: W = 0, e^W = I
+    torch.cuda.synchronize()
+    assert st == 0 and bool((out == torch.eye(5, dtype=torch.float64, device="cuda")).all())
