@@ -85,6 +85,54 @@ def time_select(ex, torch, d, tol, steps):
     return (time.perf_counter() - t0) * 1e3 / steps
 
 
+def run_lowrank_workload(name, steps, warmup, with_cpu):
+    """Low-rank variant (Sec. 2.2): e^(A1 A2) = I + A1 phi(A2 A1) A2; the n x n output stream bounds it."""
+    import numpy as np
+    import torch
+    import paper_2512_20777_amd as ex
+    from paper_2512_20777_amd import workloads
+    w = workloads.LOWRANK_WORKLOADS[name]
+    a1, a2 = workloads.make_lowrank_workload(name)
+    d1, d2 = torch.from_numpy(a1).cuda(), torch.from_numpy(a2).cuda()
+    n, t, batch = w["n"], w["t"], w["batch"]
+    out = torch.empty((batch, n, n), dtype=d1.dtype, device="cuda")
+    tol = 2.0 ** -24 if w["dtype"] == "f32" else 2.0 ** -53
+    for _ in range(warmup):
+        ex.expm_lowrank(d1, d2, tol, out=out)
+    torch.cuda.synchronize()
+    stats = ex.expm_get_stats()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(steps):
+        ex.expm_lowrank(d1, d2, tol, out=out)
+    e1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3 / steps
+    wb = 4 if w["dtype"] == "f32" else 8
+    algo_bytes = batch * (n * n + 2.0 * n * t) * wb                 # read A1, A2, write e^W
+    flops = batch * (2.0 * t * t * n * 2 + 2.0 * n * n * t) + 2.0 * t ** 3 * stats["products"]
+    ach = algo_bytes / (wall_ms * 1e-3) / 1e9
+    res = {"workload": name, "n": n, "t": t, "batch": batch, "dtype": w["dtype"], "tol": tol, "norm": "one",
+           "steps": steps, "warmup": warmup, "ms_per_step": wall_ms, "ms_per_step_events": e0.elapsed_time(e1) / steps,
+           "matrices_per_s": batch / (wall_ms * 1e-3), "tflops": flops / (wall_ms * 1e-3) / 1e12,
+           "products": stats["products"], "rounds": 0,
+           "hist_m": {str(k): v for k, v in stats["hist_m"].items() if v}, "hist_s": {"0": batch},
+           "select_ms": None, "kernel_ms_per_step": {},
+           "roofline": {"bound": "hbm", "kernel": "rect_gemm_kernel", "achieved": ach, "peak": PEAK["hbm"], "unit": "GB/s",
+                        "frac": ach / PEAK["hbm"], "traffic": None, "whole_call": True}}
+    if with_cpu:
+        from oracle import oracle_lowrank_batch
+        sub = min(batch, 8)
+        oracle_lowrank_batch(a1[:1], a2[:1], tol)
+        t0 = time.perf_counter()
+        _, info = oracle_lowrank_batch(a1[:sub], a2[:sub], tol)
+        sec = time.perf_counter() - t0
+        res["cpu_baseline"] = {"value": sub / sec, "unit": "matrices/s", "cores": int(info["threads"]), "kind": "oracle",
+                               "sample": "first %d pairs of the batch, one run, %.2f s" % (sub, sec)}
+    return res
+
+
 def cpu_baseline(name, a, tol, workloads):
     """The oracle, as it stands, on the host cores: whole batch when that takes seconds, else recorded."""
     import numpy as np
@@ -221,12 +269,18 @@ def pmc_pass(name, steps):
     import torch
     import paper_2512_20777_amd as ex
     from paper_2512_20777_amd import workloads
-    w = workloads.WORKLOADS[name]
-    d = torch.from_numpy(workloads.make_workload(name)).cuda()
-    out = torch.empty_like(d)
-    norm = ex.NORM_INF if w.norm == "inf" else ex.NORM_ONE
-    for _ in range(steps):
-        ex.expm(d, w.tol, out=out, norm=norm)
+    if name in workloads.LOWRANK_WORKLOADS:
+        a1, a2 = workloads.make_lowrank_workload(name)
+        d1, d2 = torch.from_numpy(a1).cuda(), torch.from_numpy(a2).cuda()
+        for _ in range(steps):
+            ex.expm_lowrank(d1, d2)
+    else:
+        w = workloads.WORKLOADS[name]
+        d = torch.from_numpy(workloads.make_workload(name)).cuda()
+        out = torch.empty_like(d)
+        norm = ex.NORM_INF if w.norm == "inf" else ex.NORM_ONE
+        for _ in range(steps):
+            ex.expm(d, w.tol, out=out, norm=norm)
     torch.cuda.synchronize()
     src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device="cuda")   # 256 MiB
     dst = torch.empty_like(src)
@@ -269,9 +323,14 @@ def main():
     if args.pmc_pass:
         pmc_pass(head, args.steps if args.steps > 0 else 3)
         return
-    steps = args.steps if args.steps > 0 else DEFAULT_STEPS[head]
-    warmup = args.warmup if args.warmup >= 0 else DEFAULT_WARMUP[head]
-    main_res = run_workload(head, steps, warmup, not args.no_cpu, args.time_select, args.compare_ps)
+    from paper_2512_20777_amd import workloads
+    lowrank_head = head in workloads.LOWRANK_WORKLOADS
+    steps = args.steps if args.steps > 0 else DEFAULT_STEPS.get(head, 20)
+    warmup = args.warmup if args.warmup >= 0 else DEFAULT_WARMUP.get(head, 5)
+    if lowrank_head:
+        main_res = run_lowrank_workload(head, steps, warmup, not args.no_cpu)
+    else:
+        main_res = run_workload(head, steps, warmup, not args.no_cpu, args.time_select, args.compare_ps)
     per = [main_res]
     if not args.no_others:
         for name in ("C1", "C2", "C3", "C4", "C5f64", "C5f32", "F1"):
@@ -279,14 +338,16 @@ def main():
                 continue
             per.append(run_workload(name, DEFAULT_STEPS[name], DEFAULT_WARMUP[name], not args.no_cpu, args.time_select,
                                     args.compare_ps))
+        if not lowrank_head:
+            per.append(run_lowrank_workload("L1", 20, 5, not args.no_cpu))
         per.sort(key=lambda r: r["workload"])
-    from paper_2512_20777_amd import workloads
+    note = workloads.LOWRANK_WORKLOADS[head]["note"] if lowrank_head else workloads.WORKLOADS[head].note
     line = {
         "metric": "matrix exponentials/sec (+ achieved TFLOP/s and fraction of MFMA/HBM roofline per workload)",
         "value": main_res["matrices_per_s"], "unit": "matrices/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
         "ms_per_step": main_res["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": main_res["dtype"], "data": "synthetic",
-        "config": {"workload": "%s: %s" % (head, workloads.WORKLOADS[head].note), "n": main_res["n"],
+        "config": {"workload": "%s: %s" % (head, note), "n": main_res["n"],
                    "batch": main_res["batch"], "tol": main_res["tol"], "norm": main_res["norm"]},
         "tflops": main_res["tflops"],
         "roofline": {k: main_res["roofline"][k] for k in ("bound", "achieved", "peak", "unit", "frac", "traffic")},

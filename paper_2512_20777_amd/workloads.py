@@ -160,6 +160,35 @@ def random_stack(seed: int, batch: int, n: int, dtype, norm_lo: float, norm_hi: 
     return np.ascontiguousarray(a.astype(dtype))
 
 
+# Low-rank workload (Sec. 2.2): W = A1 A2 with A1 n x t, A2 t x n.  L1 stands for a flow layer on high-dimensional
+# data, the case that variant was proposed for: 64 pairs, n = 1024, t = 64, fp32, factors iid N(0,1) rescaled so that
+# ||A2 A1||_1 is log-uniform in [1e-3, 2] (within reach of the unscaled series at fp32 roundoff).
+LOWRANK_WORKLOADS = {
+    "L1": dict(n=1024, t=64, batch=64, dtype="f32", seed=SEED_BASE + 7, lo=1e-3, hi=2.0,
+               note="64 pairs A1 (1024x64), A2 (64x1024) fp32, iid N(0,1) rescaled, ||A2 A1||_1 log-uniform in [1e-3,2]"),
+}
+
+
+def lowrank_stack(seed: int, batch: int, n: int, t: int, dtype, norm_lo: float, norm_hi: float):
+    """Seeded pairs (A1 [batch][n][t], A2 [batch][t][n]) whose ||A2 A1||_1 is log-uniform in [norm_lo, norm_hi];
+    both factors of a pair get the same scale."""
+    rng = np.random.default_rng(seed)
+    a1 = rng.standard_normal((batch, n, t))
+    a2 = rng.standard_normal((batch, t, n))
+    if batch and n and t:
+        v1 = np.abs(np.matmul(a2, a1)).sum(axis=1).max(axis=1)
+        f = np.sqrt(_log_uniform(rng, norm_lo, norm_hi, batch) / v1)
+        a1 *= f[:, None, None]
+        a2 *= f[:, None, None]
+    return np.ascontiguousarray(a1.astype(dtype)), np.ascontiguousarray(a2.astype(dtype))
+
+
+def make_lowrank_workload(name: str):
+    w = LOWRANK_WORKLOADS[name]
+    dt = np.float32 if w["dtype"] == "f32" else np.float64
+    return lowrank_stack(w["seed"], w["batch"], w["n"], w["t"], dt, w["lo"], w["hi"])
+
+
 def products_for(m: np.ndarray, s: np.ndarray, scheme: str = "sastre") -> np.ndarray:
     """Matrix products the method spends on a matrix with order m and scaling s.
 
