@@ -443,7 +443,8 @@ namespace {
 
 struct LowrankLayout {
     Layout ctl;
-    size_t V, Phi, U, total;
+    size_t V, Vpart, Phi, U, total;
+    int vslices;  // slices of the inner dimension of V = A2 A1
 };
 
 LowrankLayout make_lowrank_layout(int n, int t, int batch, int dtype)
@@ -453,6 +454,9 @@ LowrankLayout make_lowrank_layout(int n, int t, int batch, int dtype)
     L.ctl = make_layout(t, batch, dtype);  // t is within the fused path: control records only
     size_t off = align_up(L.ctl.total, 256);
     L.V = off;   off = align_up(off + (size_t)batch * t * t * w, 256);
+    L.vslices = rect_gemm_slices(t, t, n, batch, dtype == EXPM_DTYPE_F64 ? 1 : 0);
+    L.Vpart = off;
+    if (L.vslices > 1) off = align_up(off + (size_t)batch * L.vslices * t * t * w, 256);
     L.Phi = off; off = align_up(off + (size_t)batch * t * t * w, 256);
     L.U = off;   off = align_up(off + (size_t)batch * n * t * w, 256);
     L.total = off;
@@ -483,7 +487,7 @@ int run_lowrank_core(const void *A1, const void *A2, int n, int t, int batch, in
     {
         Bracket br(stream, EXPM_KCLASS_GEMM, 2.0 * t * (double)t * n * batch, ((2.0 * n * t) + (double)t * t) * batch * w);
         EXPM_TRY(launch_rect_gemm(A2, A1, base + L.V, t, t, n, n, t, t, (size_t)t * n, (size_t)n * t, (size_t)t * t, batch,
-                                  dtype, 0, stream));
+                                  dtype, 0, L.vslices, L.vslices > 1 ? base + L.Vpart : nullptr, stream));
     }
     Bracket br(stream, EXPM_KCLASS_FUSED, 0.0, 2.0 * batch * (double)t * t * w);
     EXPM_TRY(launch_small(base + L.V, base + L.Phi, t, batch, dtype, tol, select_only, kSchemePhi, 0,
@@ -554,13 +558,13 @@ int expm_lowrank(const void *A1, const void *A2, int n, int t, int batch, int dt
         // U = A1 Phi
         Bracket br(stream, EXPM_KCLASS_GEMM, 2.0 * n * (double)t * t * batch, (2.0 * n * t + (double)t * t) * batch * (double)w);
         EXPM_TRY(launch_rect_gemm(A1, base + L.Phi, base + L.U, n, t, t, t, t, t, (size_t)n * t, (size_t)t * t, (size_t)n * t,
-                                  batch, dtype, 0, stream));
+                                  batch, dtype, 0, 1, nullptr, stream));
     }
     {
         // out = U A2 + I  (t = 0: the empty product, out = I)
         Bracket br(stream, EXPM_KCLASS_GEMM, 2.0 * n * (double)n * t * batch, ((double)n * n + 2.0 * n * t) * batch * (double)w);
         EXPM_TRY(launch_rect_gemm(base + L.U, A2, out, n, n, t, t, n, n, (size_t)n * t, (size_t)t * n, (size_t)n * n, batch,
-                                  dtype, 1, stream));
+                                  dtype, 1, 1, nullptr, stream));
     }
     if (t > 0) remember_lowrank(t, batch, dtype, stream, L);
     else g_last.valid = false;

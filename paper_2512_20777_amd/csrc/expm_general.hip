@@ -60,18 +60,6 @@ __device__ __forceinline__ double pow2neg(int e)
     return __longlong_as_double((long long)(1023 - e) << 52);
 }
 
-// Workgroup ids are handed to the 8 XCDs round-robin; remap so that every XCD works on a
-// contiguous range of (matrix, tile) pairs and its L2 sees whole operand panels reused.
-__device__ __forceinline__ int xcd_remap(int pid, int total)
-{
-    const int nx = 8;
-    if (total < 2 * nx) return pid;
-    const int per = (total + nx - 1) / nx;
-    const int tall = total % nx == 0 ? nx : total % nx;  // XCDs that hold `per` ids; the rest hold per-1
-    const int xcd = pid % nx, idx = pid / nx;
-    return xcd < tall ? xcd * per + idx : tall * per + (xcd - tall) * (per - 1) + idx;
-}
-
 // How a product kernel may touch its operands: element by element with bounds checks, 16-byte vectors with
 // bounds checks, or 16-byte vectors with none (n a multiple of the tile and of the k-block: every tile full).
 constexpr int kAccessScalar = 0, kAccessVector = 1, kAccessFull = 2;

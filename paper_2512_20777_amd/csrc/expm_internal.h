@@ -404,6 +404,18 @@ struct GeneralBuffers {
     int norm_inf;            // 0: 1-norm (column sums), 1: infinity-norm (row sums) in the selection
 };
 
+// Workgroup ids are handed to the 8 XCDs round-robin; remap so that every XCD works on a
+// contiguous range of (matrix, tile) pairs and its L2 sees whole operand panels reused.
+__device__ __forceinline__ int xcd_remap(int pid, int total)
+{
+    const int nx = 8;
+    if (total < 2 * nx) return pid;
+    const int per = (total + nx - 1) / nx;
+    const int tall = total % nx == 0 ? nx : total % nx;  // XCDs that hold `per` ids; the rest hold per-1
+    const int xcd = pid % nx, idx = pid / nx;
+    return xcd < tall ? xcd * per + idx : tall * per + (xcd - tall) * (per - 1) + idx;
+}
+
 // small fused path
 bool small_path_supported(int n, int dtype);
 hipError_t launch_small(const void *A, void *out, int n, int batch, int dtype, double eps, int select_only,
@@ -421,7 +433,8 @@ hipError_t launch_select_plan(const GeneralBuffers &gb, int n, int batch, double
 hipError_t launch_prepare(const GeneralBuffers &gb, int n, int batch, int dtype, int scheme, hipStream_t stream);
 hipError_t launch_rect_gemm(const void *A, const void *B, void *C, int M, int N, int K, int lda, int ldb, int ldc,
                             size_t stride_a, size_t stride_b, size_t stride_c, int batch, int dtype, int add_identity,
-                            hipStream_t stream);
+                            int slices, void *partials, hipStream_t stream);
+int rect_gemm_slices(int M, int N, int K, int batch, int dtype);
 bool first_round_is_self_contained(int n, int scheme);
 hipError_t launch_first_round(const GeneralBuffers &gb, int n, int batch, int dtype, hipStream_t stream);
 hipError_t launch_chain_round(const GeneralBuffers &gb, int n, int active, int round, int dtype, int wt, int scheme,

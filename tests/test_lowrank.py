@@ -170,6 +170,29 @@ def test_gpu_lowrank_parity(ex, n, t, dtype):
 
 
 @pytest.mark.gpu
+def test_gpu_lowrank_full_workload(ex):
+    """The benchmark's own workload at full size (64 pairs, n = 1024, t = 64, fp32), every pair against the oracle,
+    in the launch configuration the benchmark times (sliced V product, several column tiles per workgroup)."""
+    from paper_2512_20777_amd import workloads
+    a1, a2 = workloads.make_lowrank_workload("L1")
+    m, st, stats, info = _check_lowrank(ex, a1, a2, U32, "L1 full size")
+    assert st == 0 and stats["warning"] == 0
+    assert len(set(int(x) for x in m)) >= 4
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("n,t,batch,dtype", [(512, 64, 3, np.float64), (1024, 32, 40, np.float32), (600, 24, 110, np.float32),
+                                             (520, 20, 70, np.float64)])
+def test_gpu_lowrank_parity_many_tiles(ex, n, t, batch, dtype):
+    """Shapes with several 128x128 tiles per row (so that a workgroup walks more than one) in both precisions."""
+    u = U32 if dtype == np.float32 else U64
+    hi = 2.0 if dtype == np.float32 else 0.9
+    a1, a2 = _stack(5000 + n + t, batch, n, t, dtype, 1e-5, hi)
+    m, st, stats, info = _check_lowrank(ex, a1, a2, u, "lowrank many tiles n=%d t=%d batch=%d" % (n, t, batch))
+    assert st == 0 and stats["warning"] == 0
+
+
+@pytest.mark.gpu
 def test_gpu_lowrank_user_tolerance_orders_and_flags(ex):
     """eps = 1e-8 as in the paper's experiments: all seven orders occur; a norm beyond the reach of order 16 is
     flagged, not silently wrong; a pair with A2 A1 = 0 is exact with order 0; non-finite input gives NaN."""
