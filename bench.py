@@ -17,8 +17,8 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 PEAK = {"hbm": 8000.0, "mfma_f32": 157.3, "mfma_f64": 78.6}  # GB/s, TFLOP/s (MI355X published)
-DEFAULT_STEPS = {"F1": 200, "C1": 200, "C2": 200, "C3": 100, "C4": 60, "C5f64": 4, "C5f32": 6}
-DEFAULT_WARMUP = {"F1": 20, "C1": 20, "C2": 20, "C3": 20, "C4": 15, "C5f64": 2, "C5f32": 2}
+DEFAULT_STEPS = {"F1": 200, "C1": 200, "C2": 200, "C3": 100, "C4": 60, "C5f64": 4, "C5f32": 6, "L1": 100}
+DEFAULT_WARMUP = {"F1": 20, "C1": 20, "C2": 20, "C3": 20, "C4": 15, "C5f64": 2, "C5f32": 2, "L1": 10}
 
 
 def source_sha1():
@@ -36,13 +36,15 @@ def recorded_traffic(workload, kernel_prefix):
     path = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
     if not os.path.exists(path):
         return None
-    sha, val = None, None
+    sha, val, most = None, None, -1
     for line in open(path):
         if line.startswith("source_sha1"):
             sha = line.split()[1]
         elif not line.startswith("#") and "|" in line:
-            w, k, f, wr, _ = [x.strip() for x in line.split("|")]
-            if w == workload and k.startswith(kernel_prefix):
+            w, k, f, wr, disp = [x.strip() for x in line.split("|")]
+            # several instantiations may match: the one with the most dispatches is the one that carries the time
+            if w == workload and k.startswith(kernel_prefix) and int(disp.split()[1]) > most:
+                most = int(disp.split()[1])
                 val = (float(f.split()[1]) + float(wr.split()[1])) * 1024.0
     return val if sha == source_sha1() else None
 
@@ -85,8 +87,45 @@ def time_select(ex, torch, d, tol, steps):
     return (time.perf_counter() - t0) * 1e3 / steps
 
 
+def small_matrix_context(ex, torch, workloads, name, d, out, norm):
+    """Two figures that put the HBM fraction of a 4096-matrix batch in context: what a plain device copy of the
+    same bytes takes (launch and latency floor of any kernel on so little data), and the same kernel on a batch
+    64 times larger (same recipe and seed), where it runs at its own instruction rate."""
+    w = workloads.WORKLOADS[name]
+    reps = 200
+    for _ in range(10):
+        out.copy_(d)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        out.copy_(d)
+    e1.record()
+    torch.cuda.synchronize()
+    copy_ms = e0.elapsed_time(e1) / reps
+    big = 64 * w.batch
+    ab = torch.from_numpy(workloads.make_workload(name, batch=big)).cuda()
+    ob = torch.empty_like(ab)
+    for _ in range(3):
+        ex.expm(ab, w.tol, out=ob, norm=norm)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(20):
+        ex.expm(ab, w.tol, out=ob, norm=norm)
+    e1.record()
+    torch.cuda.synchronize()
+    big_ms = e0.elapsed_time(e1) / 20
+    nbytes = 2.0 * ab.numel() * ab.element_size()
+    del ab, ob
+    ex.expm(d, w.tol, out=out, norm=norm)  # leave the workload itself as the last call
+    torch.cuda.synchronize()
+    return {"device_copy_same_bytes_ms": copy_ms,
+            "batch_x64": {"batch": big, "ms_per_step": big_ms, "matrices_per_s": big / (big_ms * 1e-3),
+                          "hbm_gbs": nbytes / (big_ms * 1e-3) / 1e9, "hbm_frac": nbytes / (big_ms * 1e-3) / 1e9 / PEAK["hbm"]}}
+
+
 def run_lowrank_workload(name, steps, warmup, with_cpu):
-    """Low-rank variant (Sec. 2.2): e^(A1 A2) = I + A1 phi(A2 A1) A2; the n x n output stream bounds it."""
+    """Low-rank variant (Sec. 2.2): e^(A1 A2) = I + A1 phi(A2 A1) A2."""
     import numpy as np
     import torch
     import paper_2512_20777_amd as ex
@@ -109,18 +148,36 @@ def run_lowrank_workload(name, steps, warmup, with_cpu):
     e1.record()
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3 / steps
+    psteps = max(2, min(steps, 20))
+    ex.expm_profile_reset()
+    ex.expm_profile_enable(True)
+    for _ in range(psteps):
+        ex.expm_lowrank(d1, d2, tol, out=out)
+    torch.cuda.synchronize()
+    prof = ex.expm_profile_read()
+    ex.expm_profile_enable(False)
+    ex.expm_profile_reset()
     wb = 4 if w["dtype"] == "f32" else 8
     algo_bytes = batch * (n * n + 2.0 * n * t) * wb                 # read A1, A2, write e^W
     flops = batch * (2.0 * t * t * n * 2 + 2.0 * n * n * t) + 2.0 * t ** 3 * stats["products"]
-    ach = algo_bytes / (wall_ms * 1e-3) / 1e9
+    # The three rectangular products (V = A2 A1, U = A1 phi, U A2 + I) carry the time; the last one does 2t flops per
+    # output element, which at t = 64 in fp32 is above the ridge of the two roofs (19.7 flop/byte): matrix-core bound.
+    k = prof["gemm"]
+    peak = PEAK["mfma_f64" if w["dtype"] == "f64" else "mfma_f32"]
+    ach = k["flops"] / (k["ms"] * 1e-3) / 1e12
     res = {"workload": name, "n": n, "t": t, "batch": batch, "dtype": w["dtype"], "tol": tol, "norm": "one",
            "steps": steps, "warmup": warmup, "ms_per_step": wall_ms, "ms_per_step_events": e0.elapsed_time(e1) / steps,
            "matrices_per_s": batch / (wall_ms * 1e-3), "tflops": flops / (wall_ms * 1e-3) / 1e12,
            "products": stats["products"], "rounds": 0,
-           "hist_m": {str(k): v for k, v in stats["hist_m"].items() if v}, "hist_s": {"0": batch},
-           "select_ms": None, "kernel_ms_per_step": {},
-           "roofline": {"bound": "hbm", "kernel": "rect_gemm_kernel", "achieved": ach, "peak": PEAK["hbm"], "unit": "GB/s",
-                        "frac": ach / PEAK["hbm"], "traffic": None, "whole_call": True}}
+           "hist_m": {str(kk): v for kk, v in stats["hist_m"].items() if v}, "hist_s": {"0": batch},
+           "select_ms": None,
+           "kernel_ms_per_step": {kk: v["ms"] / psteps for kk, v in prof.items() if v["launches"]},
+           "roofline": {"bound": "mfma", "kernel": "rect_gemm_kernel", "achieved": ach, "peak": peak, "unit": "TFLOP/s",
+                        "frac": ach / peak, "traffic": None, "avg_launch_ms": k["ms"] / k["launches"],
+                        "launches_per_step": k["launches"] / psteps, "whole_call_frac": flops / (wall_ms * 1e-3) / 1e12 / peak,
+                        "hbm_gbs_whole_call": algo_bytes / (wall_ms * 1e-3) / 1e9}}
+    # HBM bytes of the last product (the 128x128-tile instantiation), which carries most of the time
+    res["roofline"]["traffic"] = recorded_traffic(name, "rect_gemm_kernel<%s, 4" % ("float" if w["dtype"] == "f32" else "double"))
     if with_cpu:
         from oracle import oracle_lowrank_batch
         sub = min(batch, 8)
@@ -257,6 +314,8 @@ def run_workload(name, steps, warmup, with_cpu, time_sel=False, compare_ps=False
                 "time_ratio_vs_main": b_ms / wall_ms}
         ex.expm(d, w.tol, out=out, norm=norm)  # leave the main scheme as the last call
         torch.cuda.synchronize()
+    if stats["fused_path"] and res["roofline"]["bound"] == "hbm":
+        res["context"] = small_matrix_context(ex, torch, workloads, name, d, out, norm)
     if with_cpu:
         res["cpu_baseline"] = cpu_baseline(name, a, w.tol, workloads)
     del d, out
@@ -339,7 +398,7 @@ def main():
             per.append(run_workload(name, DEFAULT_STEPS[name], DEFAULT_WARMUP[name], not args.no_cpu, args.time_select,
                                     args.compare_ps))
         if not lowrank_head:
-            per.append(run_lowrank_workload("L1", 20, 5, not args.no_cpu))
+            per.append(run_lowrank_workload("L1", DEFAULT_STEPS["L1"], DEFAULT_WARMUP["L1"], not args.no_cpu))
         per.sort(key=lambda r: r["workload"])
     note = workloads.LOWRANK_WORKLOADS[head]["note"] if lowrank_head else workloads.WORKLOADS[head].note
     line = {
