@@ -88,9 +88,10 @@ def time_select(ex, torch, d, tol, steps):
 
 
 def small_matrix_context(ex, torch, workloads, name, d, out, norm):
-    """Two figures that put the HBM fraction of a 4096-matrix batch in context: what a plain device copy of the
-    same bytes takes (launch and latency floor of any kernel on so little data), and the same kernel on a batch
-    64 times larger (same recipe and seed), where it runs at its own instruction rate."""
+    """Figures that put the HBM fraction of a 4096-matrix batch in context: what a plain device copy of the same
+    bytes takes (launch and latency floor of any kernel on so little data), the same call replayed from a HIP
+    graph, and the same kernel on a batch 64 times larger (same recipe and seed), where it runs at its own
+    instruction rate."""
     w = workloads.WORKLOADS[name]
     reps = 200
     for _ in range(10):
@@ -103,6 +104,23 @@ def small_matrix_context(ex, torch, workloads, name, d, out, norm):
     e1.record()
     torch.cuda.synchronize()
     copy_ms = e0.elapsed_time(e1) / reps
+    # the same call recorded 20 times into a HIP graph and replayed: what a launch-bound caller would do
+    calls = 20
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        for _ in range(calls):
+            ex.expm(d, w.tol, out=out, norm=norm)
+    for _ in range(3):
+        graph.replay()
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(10):
+        graph.replay()
+    e1.record()
+    torch.cuda.synchronize()
+    graph_ms = e0.elapsed_time(e1) / (10 * calls)
+    del graph
     big = 64 * w.batch
     ab = torch.from_numpy(workloads.make_workload(name, batch=big)).cuda()
     ob = torch.empty_like(ab)
@@ -120,6 +138,7 @@ def small_matrix_context(ex, torch, workloads, name, d, out, norm):
     ex.expm(d, w.tol, out=out, norm=norm)  # leave the workload itself as the last call
     torch.cuda.synchronize()
     return {"device_copy_same_bytes_ms": copy_ms,
+            "graph_replay": {"calls_per_graph": calls, "ms_per_call": graph_ms, "matrices_per_s": w.batch / (graph_ms * 1e-3)},
             "batch_x64": {"batch": big, "ms_per_step": big_ms, "matrices_per_s": big / (big_ms * 1e-3),
                           "hbm_gbs": nbytes / (big_ms * 1e-3) / 1e9, "hbm_frac": nbytes / (big_ms * 1e-3) / 1e9 / PEAK["hbm"]}}
 

@@ -83,6 +83,11 @@ int expm_select(const void *A, int n, int batch, int dtype, double tol,
  * `stream` until the selection stage has finished (one 256-byte read-back), enqueues
  * the remaining rounds and returns without waiting for them.
  *
+ * Stream capture: a call on the fused path only enqueues kernels (no read-back, no memset) and may be
+ * recorded into a HIP graph, provided the workspace was reserved before the capture (expm_reserve, or an
+ * earlier call of the same size) -- the recorded kernels hold its address, so a later call that makes the
+ * workspace grow invalidates such graphs.  A call on the larger-n path waits on the stream and cannot be captured.
+ *
  * Returns 0 or an error (< 0).  Warnings are returned when they are known at return
  * time (the larger-n path); after any call expm_get_stats() reports them.
  * Ownership: caller owns A and out and must keep them alive until `stream` has
@@ -147,7 +152,9 @@ int expm_ex(const void *A, int n, int batch, int dtype, double tol, int scheme, 
  *   m_out  HOST, int32[batch].
  * expm_lowrank_select is synchronous (null stream) and returns the warning; expm_lowrank is asynchronous on
  * `stream` and returns 0 or an error, its warnings surface through expm_get_stats() (n of the statistics is t,
- * products counts the t x t products of the core series).  Both use the cached workspace.
+ * products counts the t x t products of the core series).  Both use the cached workspace.  expm_lowrank only
+ * enqueues kernels: once a call of the same shape has sized the workspace it may be recorded into a HIP graph
+ * (same condition as for expm: the workspace must not grow while such a graph is in use).
  */
 int expm_lowrank_select(const void *A1, const void *A2, int n, int t, int batch, int dtype, double tol,
                         int32_t *m_out);
