@@ -51,6 +51,7 @@ struct GemmParams {
     int tiles;   // tiles per dimension
     int round;   // <= 0 power round (0: W2 = W*W, -1: W3 = W2*W, -2: W4 = W3*W), >= 1 chain round
     int total;   // workgroups in the grid
+    int slot0, slot_step;  // chain rounds: this launch covers the sorted matrices slot0, slot0 + slot_step, ...
     int scheme;  // kSchemeSastre or kSchemePS
     int norm_inf;  // power rounds: emit row abs-sums (infinity-norm) instead of column abs-sums
 };
@@ -141,7 +142,7 @@ __global__ __launch_bounds__(kThreads, WT == 4 ? 2 : 4) void gemm_round_kernel(G
         st.acc_scale = (T)1; st.nsrc = 0; st.nout = 1;
         st.dst[0] = p.round == 0 ? BUF_W2 : (p.round == -1 ? BUF_W3 : BUF_W4);
     } else {
-        b = p.order[slot];
+        b = p.order[p.slot0 + slot * p.slot_step];
         const MatInfo mi = p.info[b];
         if constexpr (FIRST) {
             first_m = mi.m;
@@ -631,6 +632,8 @@ GemmParams make_params(const GeneralBuffers &gb, int n, int round, int matrices,
     p.tiles = (n + 32 * wt - 1) / (32 * wt);
     p.round = round;
     p.total = matrices * p.tiles * p.tiles;
+    p.slot0 = 0;
+    p.slot_step = 1;
     return p;
 }
 
@@ -767,10 +770,14 @@ hipError_t launch_prepare(const GeneralBuffers &gb, int n, int batch, int dtype,
     return hipGetLastError();
 }
 
+// `active` matrices of the sorted list, starting at `first` and `step` apart (1: a contiguous range)
 hipError_t launch_chain_round(const GeneralBuffers &gb, int n, int active, int round, int dtype, int wt, int scheme,
-                              hipStream_t stream)
+                              hipStream_t stream, int first, int step)
 {
-    return launch_gemm(make_params(gb, n, round, active, wt, scheme), dtype, wt, gb.ptr_align16, stream);
+    GemmParams p = make_params(gb, n, round, active, wt, scheme);
+    p.slot0 = first;
+    p.slot_step = step;
+    return launch_gemm(p, dtype, wt, gb.ptr_align16, stream);
 }
 
 }  // namespace expmk

@@ -438,6 +438,6 @@ int rect_gemm_slices(int M, int N, int K, int batch, int dtype);
 bool first_round_is_self_contained(int n, int scheme);
 hipError_t launch_first_round(const GeneralBuffers &gb, int n, int batch, int dtype, hipStream_t stream);
 hipError_t launch_chain_round(const GeneralBuffers &gb, int n, int active, int round, int dtype, int wt, int scheme,
-                              hipStream_t stream);
+                              hipStream_t stream, int first = 0, int step = 1);
 
 }  // namespace expmk
