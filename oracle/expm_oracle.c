@@ -304,6 +304,20 @@ int oracle_expm(const double *W, int n, double eps, double *X, int *m, int *s,
     return 0;
 }
 
+/* Threads the OpenMP runtime offered when the library was first asked: a batch call with an explicit thread count
+ * changes the runtime's own default, so "all threads" must not be read back from it afterwards. */
+static int all_threads(void)
+{
+#ifdef _OPENMP
+    static int offered = 0;
+    if (offered <= 0)
+        offered = omp_get_max_threads();
+    return offered;
+#else
+    return 1;
+#endif
+}
+
 /*
  * Batch driver, also the timed CPU baseline.  threads <= 0 means "all the
  * OpenMP runtime offers".  Matrices of order < 256 are spread over threads
@@ -318,7 +332,7 @@ int oracle_expm_batch(const double *W, int n, int batch, double eps, double *X,
     int used = 1;
 #ifdef _OPENMP
     if (threads <= 0)
-        threads = omp_get_max_threads();
+        threads = all_threads();
     used = threads;
     omp_set_num_threads(threads);
 #else
@@ -500,7 +514,7 @@ int oracle_expm_ps_batch(const double *W, int n, int batch, double eps, double *
     int used = 1;
 #ifdef _OPENMP
     if (threads <= 0)
-        threads = omp_get_max_threads();
+        threads = all_threads();
     used = threads;
     omp_set_num_threads(threads);
 #else
@@ -603,7 +617,7 @@ int oracle_expm_baseline_batch(const double *W, int n, int batch, double eps, do
     int used = 1;
 #ifdef _OPENMP
     if (threads <= 0)
-        threads = omp_get_max_threads();
+        threads = all_threads();
     used = threads;
     omp_set_num_threads(threads);
 #else
@@ -736,7 +750,7 @@ int oracle_lowrank_batch(const double *A1, const double *A2, int n, int t, int b
     int used = 1;
 #ifdef _OPENMP
     if (threads <= 0)
-        threads = omp_get_max_threads();
+        threads = all_threads();
     used = threads;
     omp_set_num_threads(threads);
 #else
@@ -764,9 +778,5 @@ int oracle_lowrank_batch(const double *A1, const double *A2, int n, int t, int b
 
 int oracle_max_threads(void)
 {
-#ifdef _OPENMP
-    return omp_get_max_threads();
-#else
-    return 1;
-#endif
+    return all_threads();
 }

@@ -5,6 +5,7 @@
 
 #include <algorithm>
 #include <cmath>
+#include <cstdlib>
 #include <cstring>
 #include <vector>
 
@@ -436,8 +437,14 @@ int expm_ex(const void *A, int n, int batch, int dtype, double tol, int scheme, 
     // workgroups towards its end, the other's fills the compute units (a single chain leaves them idle there,
     // 8 % of the call for 32 matrices of 512 x 512).  With the per-class timers on, one chain on the caller's
     // stream, so that launches do not overlap and each is timed by itself.
+    // profiling aid: EXPM_CHAINS=1 keeps one chain (read once), so that a kernel trace shows launches that do not overlap
+    static const int chain_limit = [] {
+        const char *e = getenv("EXPM_CHAINS");
+        const int v = e ? atoi(e) : 0;
+        return v >= 1 && v <= kChains ? v : kChains;
+    }();
     int chains = 1;
-    if (!g_profile && n < 1024 && longest >= 2 && g_side_stream != nullptr) chains = std::min(kChains, g_ws.host_summary[4]);
+    if (!g_profile && n < 1024 && longest >= 2 && g_side_stream != nullptr) chains = std::min(chain_limit, g_ws.host_summary[4]);
     if (chains > 1) {
         EXPM_TRY(hipEventRecord(g_fork, stream));
         for (int c = 1; c < chains; ++c) {

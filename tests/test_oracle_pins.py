@@ -430,3 +430,15 @@ def test_fp32_inputs_are_widened_exactly():
     X32, i32 = oracle_expm(W32, U32)
     X64, i64 = oracle_expm(W32.astype(np.float64), U32)
     assert np.array_equal(X32, X64) and i32 == i64
+
+
+def test_oracle_default_thread_count_survives_an_explicit_one():
+    """A batch call with threads=1 must not turn later "all threads" calls into one-thread calls (the benchmark
+    times the oracle both ways in one process)."""
+    from oracle import oracle_expm_batch, oracle_max_threads
+    a = np.random.default_rng(77).standard_normal((8, 6, 6)) * 0.2
+    _, first = oracle_expm_batch(a, 1e-8)
+    _, one = oracle_expm_batch(a, 1e-8, threads=1)
+    _, again = oracle_expm_batch(a, 1e-8)
+    assert one["threads"] == 1
+    assert first["threads"] == again["threads"] == oracle_max_threads()
