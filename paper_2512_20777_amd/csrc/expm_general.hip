@@ -37,9 +37,9 @@ template <> struct Tile<float> {
     using vec_t = float4;
 };
 
-template <typename T, int WT> constexpr int stage_bytes()
+template <typename T, int WT> constexpr int stage_bytes(bool dma = false)
 {
-    return 32 * WT * kAPitch + Tile<T>::BK * 32 * WT * (int)sizeof(T);
+    return 32 * WT * (dma ? 128 : kAPitch) + Tile<T>::BK * 32 * WT * (int)sizeof(T);
 }
 
 struct GemmParams {
@@ -63,7 +63,12 @@ __device__ __forceinline__ double pow2neg(int e)
 
 // How a product kernel may touch its operands: element by element with bounds checks, 16-byte vectors with
 // bounds checks, or 16-byte vectors with none (n a multiple of the tile and of the k-block: every tile full).
-constexpr int kAccessScalar = 0, kAccessVector = 1, kAccessFull = 2;
+constexpr int kAccessScalar = 0, kAccessVector = 1, kAccessFull = 2, kAccessDma = 3;
+// kAccessDma: as kAccessFull, and the operand tiles go from global memory straight into LDS (16 bytes per lane,
+// global_load_lds): no staging registers, no LDS store instructions, and the loads of the next k-block stay in
+// flight for the whole multiply phase.  A lane's 16 bytes land at (wave-uniform base) + 16 * lane, so the tile
+// layouts are made of whole 16-byte slots in slot order and the permutation that keeps the fragment reads off
+// one bank is applied on the global side: the lane that owns a slot fetches the vector that belongs there.
 
 // grouped tile order: 8 tile-rows at a time, column by column
 __device__ __forceinline__ void tile_position(int tile, int tiles, int &tm, int &tn)
@@ -83,7 +88,7 @@ __device__ __forceinline__ typename Tile<T>::vec_t load_vec(const T *__restrict_
 {
     using V = typename Tile<T>::vec_t;
     constexpr int VN = Tile<T>::VN;
-    if constexpr (ALIGNED == kAccessFull) return *reinterpret_cast<const V *>(p + (size_t)row * n + col);
+    if constexpr (ALIGNED >= kAccessFull) return *reinterpret_cast<const V *>(p + (size_t)row * n + col);
     V v;
     T *e = reinterpret_cast<T *>(&v);
     if (ALIGNED) {
@@ -115,7 +120,10 @@ __global__ __launch_bounds__(kThreads, WT == 4 ? 2 : 4) void gemm_round_kernel(G
     constexpr int KQ = BK / 4;                    // k values each 16-lane group owns per k-block
     constexpr int VPR = BN / VN;                  // 16-byte vectors per B row
     constexpr int BSTEP = kThreads / VPR;         // B rows covered by one pass of the workgroup
-    constexpr int STAGE = stage_bytes<T, WT>();
+    constexpr bool DMA = ALIGNED == kAccessDma;
+    static_assert(!(DMA && FIRST), "the combined operand of the first round is formed in registers");
+    constexpr int APitch = DMA ? 128 : kAPitch;   // DMA: unpadded rows, 16-byte slots swizzled instead
+    constexpr int STAGE = stage_bytes<T, WT>(DMA);
     constexpr int kRot = 16 * (int)sizeof(T);     // rotation of a B row per k-group, in bytes
     static_assert(BK / BSTEP == WT && BM / 32 == WT, "WT staged vectors per thread and operand");
     extern __shared__ __align__(16) unsigned char smem[];
@@ -199,8 +207,8 @@ __global__ __launch_bounds__(kThreads, WT == 4 ? 2 : 4) void gemm_round_kernel(G
     // fragment read hit different banks.
     const int a_row0 = tid >> 3, a_col = (tid & 7) * VN;
     const int b_row0 = tid / VPR, b_col = (tid % VPR) * VN;
-    const int a_lds = a_row0 * kAPitch + (tid & 7) * 16;
-    const int b_lds = BM * kAPitch + b_row0 * BPitch;
+    const int a_lds = a_row0 * APitch + (tid & 7) * 16;
+    const int b_lds = BM * APitch + b_row0 * BPitch;
     const int b_vcol = (tid % VPR) * 16;  // byte offset of this thread's vector inside an unrotated row
     // LDS byte offset of staged B vector i (recomputed where used: two instructions, no register held)
     auto b_wr = [&](int i) -> int {
@@ -244,26 +252,64 @@ __global__ __launch_bounds__(kThreads, WT == 4 ? 2 : 4) void gemm_round_kernel(G
             }
         }
     };
+    // DMA staging: pass i of the workgroup covers the 256 slots i*256 .. i*256+255 of a tile, one per thread.
+    //   left tile:  slot (row, v') with row = tid/8 + 32 i holds k-vector v' ^ ((row / 2) & 7) of the row (rows two
+    //               apart differ in the swizzle, odd and even rows in the bank half: 16 rows of a fragment read
+    //               hit 16 different 16-byte bank groups)
+    //   right tile: slot (row, v') holds column vector v' - rot(row) of the row, rot = the rotation per k-group
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+    const int a_kv = ((tid & 7) ^ ((tid >> 4) & 7)) * VN;  // ((row / 2) & 7) does not depend on the pass
+    auto dma = [&](int k0, unsigned char *stage) {
+        if constexpr (DMA) {
+#pragma unroll
+            for (int i = 0; i < WT; ++i) {
+                const T *ga = Lp + (size_t)(row0 + a_row0 + 32 * i) * n + k0 + a_kv;
+                const int brow = b_row0 + BSTEP * i;
+                const int bv = ((tid % VPR) - (kRot / 16) * (brow / KQ)) & (VPR - 1);
+                const T *gb = Rp + (size_t)(k0 + brow) * n + col0 + bv * VN;
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)ga,
+                                                 (__attribute__((address_space(3))) void *)(stage + (i * 256 + wave_u * 64) * 16),
+                                                 16, 0, 0);
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)gb,
+                                                 (__attribute__((address_space(3))) void *)(stage + BM * APitch +
+                                                                                           (i * 256 + wave_u * 64) * 16),
+                                                 16, 0, 0);
+            }
+        }
+    };
+    // all of this wave's global-to-LDS loads have landed (vmcnt(0)): must hold before the barrier that lets the
+    // other waves read them
+    auto dma_done = [&]() {
+        if constexpr (DMA) __builtin_amdgcn_s_waitcnt(0x0F70);
+    };
+
     // prologue: first k-block into stage 0
+    if constexpr (DMA) {
+        dma(0, smem);
+        dma_done();
+    } else {
 #pragma unroll
-    for (int i = 0; i < WT; ++i) {
-        ra[i] = load_vec<T, ALIGNED>(Lp, row0 + a_row0 + 32 * i, a_col, n);
-        rb[i] = load_vec<T, ALIGNED>(Rp, b_row0 + BSTEP * i, col0 + b_col, n);
-    }
-    fetch_x(0);
-    combine(0);
+        for (int i = 0; i < WT; ++i) {
+            ra[i] = load_vec<T, ALIGNED>(Lp, row0 + a_row0 + 32 * i, a_col, n);
+            rb[i] = load_vec<T, ALIGNED>(Rp, b_row0 + BSTEP * i, col0 + b_col, n);
+        }
+        fetch_x(0);
+        combine(0);
 #pragma unroll
-    for (int i = 0; i < WT; ++i) {
-        *reinterpret_cast<V *>(smem + a_lds + 32 * i * kAPitch) = ra[i];
-        *reinterpret_cast<V *>(smem + b_wr(i)) = rb[i];
+        for (int i = 0; i < WT; ++i) {
+            *reinterpret_cast<V *>(smem + a_lds + 32 * i * APitch) = ra[i];
+            *reinterpret_cast<V *>(smem + b_wr(i)) = rb[i];
+        }
     }
     __syncthreads();
 
     // per-lane LDS read offsets (bytes) inside a stage
-    //   A: row (wm*16*WT + 16*ti + lj), k values lg*KQ .. lg*KQ+KQ-1  -> two 16-byte reads
+    //   A: row (wm*16*WT + 16*ti + lj), k values lg*KQ .. lg*KQ+KQ-1  -> two 16-byte reads (h = 0, 1)
     //   B: row (lg*KQ + kk), column (wn*16*WT + 16*tj + lj) rotated by 16*lg elements
-    const int a_rd = (wm * 16 * WT + lj) * kAPitch + lg * 32;
-    const int b_rd = BM * kAPitch + (lg * KQ) * BPitch + lj * (int)sizeof(T);
+    const int a_row_rd = (wm * 16 * WT + lj) * APitch;
+    const int a_rd0 = a_row_rd + (DMA ? ((2 * lg) ^ ((lj >> 1) & 7)) * 16 : lg * 32);
+    const int a_rd1 = a_row_rd + (DMA ? ((2 * lg + 1) ^ ((lj >> 1) & 7)) * 16 : lg * 32 + 16);
+    const int b_rd = BM * APitch + (lg * KQ) * BPitch + lj * (int)sizeof(T);
     const int b_rc0 = (wn * 16 * WT + 16 * lg) * (int)sizeof(T);  // rotated column of tile column 0, before wrap
 
     for (int kb = 0; kb < kblocks; ++kb) {
@@ -272,12 +318,16 @@ __global__ __launch_bounds__(kThreads, WT == 4 ? 2 : 4) void gemm_round_kernel(G
         const bool more = kb + 1 < kblocks;
         if (more) {
             const int k0 = (kb + 1) * BK;
+            if constexpr (DMA) {
+                dma(k0, nxt);
+            } else {
 #pragma unroll
-            for (int i = 0; i < WT; ++i) {
-                ra[i] = load_vec<T, ALIGNED>(Lp, row0 + a_row0 + 32 * i, k0 + a_col, n);
-                rb[i] = load_vec<T, ALIGNED>(Rp, k0 + b_row0 + BSTEP * i, col0 + b_col, n);
+                for (int i = 0; i < WT; ++i) {
+                    ra[i] = load_vec<T, ALIGNED>(Lp, row0 + a_row0 + 32 * i, k0 + a_col, n);
+                    rb[i] = load_vec<T, ALIGNED>(Rp, k0 + b_row0 + BSTEP * i, col0 + b_col, n);
+                }
+                fetch_x(k0);
             }
-            fetch_x(k0);
         }
         // A fragments: each lane's KQ k-values of a row are two 16-byte halves; one half (VN k-steps) at a
         // time keeps the live registers low, the co-resident waves cover the LDS latency
@@ -286,7 +336,7 @@ __global__ __launch_bounds__(kThreads, WT == 4 ? 2 : 4) void gemm_round_kernel(G
             V af[WT];
 #pragma unroll
             for (int ti = 0; ti < WT; ++ti)
-                af[ti] = *reinterpret_cast<const V *>(cur + a_rd + ti * 16 * kAPitch + 16 * h);
+                af[ti] = *reinterpret_cast<const V *>(cur + (h ? a_rd1 : a_rd0) + ti * 16 * APitch);
 #pragma unroll
             for (int q = 0; q < VN; ++q) {
                 const int kk = h * VN + q;
@@ -302,11 +352,13 @@ __global__ __launch_bounds__(kThreads, WT == 4 ? 2 : 4) void gemm_round_kernel(G
                 }
             }
         }
-        if (more) {
+        if constexpr (DMA) {
+            dma_done();
+        } else if (more) {
             combine((kb + 1) * BK);
 #pragma unroll
             for (int i = 0; i < WT; ++i) {
-                *reinterpret_cast<V *>(nxt + a_lds + 32 * i * kAPitch) = ra[i];
+                *reinterpret_cast<V *>(nxt + a_lds + 32 * i * APitch) = ra[i];
                 *reinterpret_cast<V *>(nxt + b_wr(i)) = rb[i];
             }
         }
@@ -327,7 +379,7 @@ __global__ __launch_bounds__(kThreads, WT == 4 ? 2 : 4) void gemm_round_kernel(G
 #pragma unroll
                 for (int tj = 0; tj < WT; ++tj) {
                     const int col = ec + 16 * tj;
-                    if (ALIGNED == kAccessFull || (row < n && col < n)) D[(size_t)row * n + col] = acc[ti][tj][v];
+                    if (ALIGNED >= kAccessFull || (row < n && col < n)) D[(size_t)row * n + col] = acc[ti][tj][v];
                 }
             }
     } else {
@@ -346,7 +398,7 @@ __global__ __launch_bounds__(kThreads, WT == 4 ? 2 : 4) void gemm_round_kernel(G
 #pragma unroll
                 for (int tj = 0; tj < WT; ++tj) {
                     const int col = ec + 16 * tj;
-                    if (ALIGNED == kAccessFull || (row < n && col < n)) {
+                    if (ALIGNED >= kAccessFull || (row < n && col < n)) {
                         const size_t idx = (size_t)row * n + col;
                         T sv[4];
 #pragma unroll
@@ -608,7 +660,7 @@ template <typename T, int WT, int ALIGNED, bool FIRST = false>
 hipError_t launch_gemm_t(const GemmParams &p, hipStream_t stream)
 {
     static bool attr_done = false;
-    const int lds = 2 * stage_bytes<T, WT>();
+    const int lds = 2 * stage_bytes<T, WT>(ALIGNED == kAccessDma);
     if (!attr_done) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_round_kernel<T, WT, ALIGNED, FIRST>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, lds);
@@ -640,11 +692,10 @@ GemmParams make_params(const GeneralBuffers &gb, int n, int round, int matrices,
 template <typename T, int WT>
 hipError_t launch_gemm_a(const GemmParams &p, bool aligned, hipStream_t stream)
 {
-    // The unchecked variant pays off for the 64x64 tile (about 5% on 512x512 fp64 products); the 128x128 kernels
-    // are register-bound and gain nothing from it (the fp64 one loses), so they keep the checked loads.
-    if constexpr (WT == 2) {
-        if (aligned && p.n % (32 * WT) == 0 && p.n % Tile<T>::BK == 0) return launch_gemm_t<T, WT, kAccessFull>(p, stream);
-    }
+    // Full tiles and 16-byte aligned rows: operands go straight from global memory into LDS.  Measured against the
+    // register-staged kernels: 4096x4096 fp64 products 6.5 % faster (the 128x128 fp64 kernel no longer spills),
+    // fp32 1.7 %, 512x512 fp64 (64x64 tiles) 0.7 %.
+    if (aligned && p.n % (32 * WT) == 0 && p.n % Tile<T>::BK == 0) return launch_gemm_t<T, WT, kAccessDma>(p, stream);
     return aligned ? launch_gemm_t<T, WT, kAccessVector>(p, stream) : launch_gemm_t<T, WT, kAccessScalar>(p, stream);
 }
 
