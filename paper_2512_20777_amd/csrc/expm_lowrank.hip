@@ -30,10 +30,16 @@ template <> struct RectTile<float> {
     using vec_t = float4;
 };
 
-template <typename T, int WT> constexpr int rect_stage_bytes()
+template <typename T, int WT> constexpr int rect_stage_bytes(bool dma)
 {
-    return 32 * WT * kLeftPitch + RectTile<T>::BK * 32 * WT * (int)sizeof(T);
+    return 32 * WT * (dma ? 128 : kLeftPitch) + RectTile<T>::BK * 32 * WT * (int)sizeof(T);
 }
+
+// How the operands are fetched: element by element, as 16-byte vectors through registers (both bounds-checked),
+// or -- every tile full, every slice a whole number of k-blocks -- as 16-byte vectors straight into LDS
+// (global_load_lds: lane l of a wave writes its 16 bytes at a wave-uniform base + 16 l, so a tile is a sequence of
+// 16-byte slots and the lane that owns a slot fetches the vector that belongs there).
+constexpr int kRectScalar = 0, kRectVector = 1, kRectDma = 2;
 
 struct RectParams {
     const void *A, *B;
@@ -74,9 +80,11 @@ __device__ __forceinline__ typename RectTile<T>::vec_t rect_load(const T *__rest
     return v;
 }
 
-template <typename T, int WT, bool VEC>
+template <typename T, int WT, int MODE>
 __global__ __launch_bounds__(kRectThreads, WT == 4 ? 2 : 4) void rect_gemm_kernel(RectParams p)
 {
+    constexpr bool VEC = MODE >= kRectVector, DMA = MODE == kRectDma;
+    constexpr int APitch = DMA ? 128 : kLeftPitch;  // DMA: unpadded rows, 16-byte slots swizzled instead
     using V = typename RectTile<T>::vec_t;
     using acc_t = typename Mfma<T>::acc_t;
     constexpr int BM = 32 * WT, BN = 32 * WT;
@@ -85,7 +93,7 @@ __global__ __launch_bounds__(kRectThreads, WT == 4 ? 2 : 4) void rect_gemm_kerne
     constexpr int KQ = BK / 4;
     constexpr int VPR = BN / VN;
     constexpr int BSTEP = kRectThreads / VPR;
-    constexpr int STAGE = rect_stage_bytes<T, WT>();
+    constexpr int STAGE = rect_stage_bytes<T, WT>(DMA);
     constexpr int kRot = 16 * (int)sizeof(T);
     static_assert(BK / BSTEP == WT, "WT staged vectors per thread and operand");
     extern __shared__ __align__(16) unsigned char smem[];
@@ -110,8 +118,8 @@ __global__ __launch_bounds__(kRectThreads, WT == 4 ? 2 : 4) void rect_gemm_kerne
     // staging maps: left tile BM rows x 8 vectors, right tile BK rows x VPR vectors, WT vectors per thread each
     const int a_row0 = tid >> 3, a_col = (tid & 7) * VN;
     const int b_row0 = tid / VPR, b_col = (tid % VPR) * VN;
-    const int a_lds = a_row0 * kLeftPitch + (tid & 7) * 16;
-    const int b_lds = BM * kLeftPitch + b_row0 * BPitch;
+    const int a_lds = a_row0 * APitch + (tid & 7) * 16;
+    const int b_lds = BM * APitch + b_row0 * BPitch;
     const int b_vcol = (tid % VPR) * 16;
     auto b_wr = [&](int i) -> int {
         return b_lds + BSTEP * i * BPitch + ((b_vcol + kRot * ((b_row0 + BSTEP * i) / KQ)) & (BPitch - 1));
@@ -148,9 +156,40 @@ __global__ __launch_bounds__(kRectThreads, WT == 4 ? 2 : 4) void rect_gemm_kerne
     auto stash = [&](unsigned char *stage) {
 #pragma unroll
         for (int i = 0; i < WT; ++i) {
-            *reinterpret_cast<V *>(stage + a_lds + 32 * i * kLeftPitch) = ra[i];
+            *reinterpret_cast<V *>(stage + a_lds + 32 * i * APitch) = ra[i];
             *reinterpret_cast<V *>(stage + b_wr(i)) = rb[i];
         }
+    };
+    // DMA: pass i covers the slots i*256 .. i*256+255 of a tile, one per thread.  Left tile: slot (row, v') holds
+    // k-vector v' ^ ((row / 2) & 7) of the row; right tile: slot (row, v') holds column vector v' - rot(row).
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+    const int a_kv = ((tid & 7) ^ ((tid >> 4) & 7)) * VN;
+    auto dma = [&](unsigned char *stage) {
+        if constexpr (DMA) {
+            const int k0 = kbeg + f_kb * BK, col0 = f_ct * BN;
+#pragma unroll
+            for (int i = 0; i < WT; ++i) {
+                const T *ga = Lp + (size_t)(row0 + a_row0 + 32 * i) * p.lda + k0 + a_kv;
+                const int brow = b_row0 + BSTEP * i;
+                const int bv = ((tid % VPR) - (kRot / 16) * (brow / KQ)) & (VPR - 1);
+                const T *gb = Rp + (size_t)(k0 + brow) * p.ldb + col0 + bv * VN;
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)ga,
+                                                 (__attribute__((address_space(3))) void *)(stage + (i * 256 + wave_u * 64) * 16),
+                                                 16, 0, 0);
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)gb,
+                                                 (__attribute__((address_space(3))) void *)(stage + BM * APitch +
+                                                                                           (i * 256 + wave_u * 64) * 16),
+                                                 16, 0, 0);
+            }
+            if (++f_kb == kblocks) {
+                f_kb = 0;
+                ++f_ct;
+            }
+        }
+    };
+    // this wave's global-to-LDS loads have landed (vmcnt(0)); must hold before the barrier that lets others read them
+    auto dma_done = [&]() {
+        if constexpr (DMA) __builtin_amdgcn_s_waitcnt(0x0F70);
     };
     // lane holds C[row0 + wm*16*WT + 16*ti + Mfma<T>::row(lg, v)][ct*BN + wn*16*WT + 16*tj + lj]
     auto store_tile = [&](int ct) {
@@ -197,12 +236,19 @@ __global__ __launch_bounds__(kRectThreads, WT == 4 ? 2 : 4) void rect_gemm_kerne
         for (int i = 0; i < nct; ++i) store_tile(ct0 + i);
         return;
     }
-    fetch();
-    stash(smem);
+    if constexpr (DMA) {
+        dma(smem);
+        dma_done();
+    } else {
+        fetch();
+        stash(smem);
+    }
     __syncthreads();
 
-    const int a_rd = (wm * 16 * WT + lj) * kLeftPitch + lg * 32;
-    const int b_rd = BM * kLeftPitch + (lg * KQ) * BPitch + lj * (int)sizeof(T);
+    const int a_row_rd = (wm * 16 * WT + lj) * APitch;
+    const int a_rd0 = a_row_rd + (DMA ? ((2 * lg) ^ ((lj >> 1) & 7)) * 16 : lg * 32);
+    const int a_rd1 = a_row_rd + (DMA ? ((2 * lg + 1) ^ ((lj >> 1) & 7)) * 16 : lg * 32 + 16);
+    const int b_rd = BM * APitch + (lg * KQ) * BPitch + lj * (int)sizeof(T);
     const int b_rc0 = (wn * 16 * WT + 16 * lg) * (int)sizeof(T);
 
     auto multiply = [&](const unsigned char *cur) {
@@ -210,7 +256,7 @@ __global__ __launch_bounds__(kRectThreads, WT == 4 ? 2 : 4) void rect_gemm_kerne
         for (int h = 0; h < 2; ++h) {
             V af[WT];
 #pragma unroll
-            for (int ti = 0; ti < WT; ++ti) af[ti] = *reinterpret_cast<const V *>(cur + a_rd + ti * 16 * kLeftPitch + 16 * h);
+            for (int ti = 0; ti < WT; ++ti) af[ti] = *reinterpret_cast<const V *>(cur + (h ? a_rd1 : a_rd0) + ti * 16 * APitch);
 #pragma unroll
             for (int q = 0; q < VN; ++q) {
                 const int kk = h * VN + q;
@@ -237,9 +283,15 @@ __global__ __launch_bounds__(kRectThreads, WT == 4 ? 2 : 4) void rect_gemm_kerne
             store_tile(c_ct - 1);
             clear();
         }
-        if (more) fetch();
-        multiply(cur);
-        if (more) stash(nxt);
+        if constexpr (DMA) {
+            if (more) dma(nxt);
+            multiply(cur);
+            dma_done();
+        } else {
+            if (more) fetch();
+            multiply(cur);
+            if (more) stash(nxt);
+        }
         __syncthreads();
         if (++c_kb == kblocks) {
             c_kb = 0;
@@ -261,17 +313,18 @@ __global__ __launch_bounds__(256) void slice_sum_kernel(const T *__restrict__ P,
     C[(size_t)blockIdx.y * elems + e] = sum;
 }
 
-template <typename T, int WT, bool VEC>
-hipError_t launch_rect_v(const RectParams &p, dim3 grid, int lds, hipStream_t stream)
+template <typename T, int WT, int MODE>
+hipError_t launch_rect_v(const RectParams &p, dim3 grid, hipStream_t stream)
 {
+    const int lds = 2 * rect_stage_bytes<T, WT>(MODE == kRectDma);
     static bool attr_done = false;  // the 128x128 tile needs more dynamic LDS than the default limit
     if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(rect_gemm_kernel<T, WT, VEC>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(rect_gemm_kernel<T, WT, MODE>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, lds);
         if (e != hipSuccess) return e;
         attr_done = true;
     }
-    hipLaunchKernelGGL((rect_gemm_kernel<T, WT, VEC>), grid, dim3(kRectThreads), lds, stream, p);
+    hipLaunchKernelGGL((rect_gemm_kernel<T, WT, MODE>), grid, dim3(kRectThreads), lds, stream, p);
     return hipGetLastError();
 }
 
@@ -279,7 +332,6 @@ template <typename T, int WT>
 hipError_t launch_rect_t(const RectParams &p, int batch, bool vec, hipStream_t stream)
 {
     constexpr int BT = 32 * WT;
-    const int lds = 2 * rect_stage_bytes<T, WT>();
     // several column tiles per workgroup hide the first fetch and the last store of a tile behind its neighbours;
     // keep at least kRectMinGroups workgroups so that the chip stays covered and the last round stays short
     const int tn = (p.N + BT - 1) / BT, tm = (p.M + BT - 1) / BT;
@@ -294,8 +346,10 @@ hipError_t launch_rect_t(const RectParams &p, int batch, bool vec, hipStream_t s
     if (total > 0x7fffffffL) return hipErrorInvalidValue;
     q.total = (int)total;
     const dim3 grid((unsigned)total);
-    if (vec) return launch_rect_v<T, WT, true>(q, grid, lds, stream);
-    return launch_rect_v<T, WT, false>(q, grid, lds, stream);
+    constexpr int bk = RectTile<T>::BK;
+    if (vec && p.M % BT == 0 && p.N % BT == 0 && p.K % bk == 0) return launch_rect_v<T, WT, kRectDma>(q, grid, stream);
+    if (vec) return launch_rect_v<T, WT, kRectVector>(q, grid, stream);
+    return launch_rect_v<T, WT, kRectScalar>(q, grid, stream);
 }
 
 }  // namespace
