@@ -42,6 +42,14 @@ template <typename T, int WT> constexpr int stage_bytes(bool dma = false)
     return 32 * WT * (dma ? 128 : kAPitch) + Tile<T>::BK * 32 * WT * (int)sizeof(T);
 }
 
+// G neighbouring columns per lane: the 16 columns of MFMA tile tj of a wave do not stand for columns 16 tj .. 16 tj + 15
+// of the wave's span but, in groups of G tiles, for columns (tj / G) * 16 G + G * lj + tj % G (lj = lane % 16).  A lane's
+// right-operand fragments for the G tiles of a group are then G neighbouring elements of an LDS row (one 8- or 16-byte
+// read instead of G reads), and its results for them are G neighbouring elements of an output row (one vector access
+// per source and destination in the epilogue).  G = 16 bytes' worth of elements, at most the tiles per wave.
+template <typename T, int WT> constexpr int col_group() { return WT < 16 / (int)sizeof(T) ? WT : 16 / (int)sizeof(T); }
+template <typename T, int N> struct VecOfN { typedef T type __attribute__((ext_vector_type(N))); };
+
 struct GemmParams {
     void *base[BUF_COUNT];
     const MatInfo *info;
@@ -120,6 +128,8 @@ __global__ __launch_bounds__(kThreads, WT == 4 ? 2 : 4) void gemm_round_kernel(G
     constexpr int KQ = BK / 4;                    // k values each 16-lane group owns per k-block
     constexpr int VPR = BN / VN;                  // 16-byte vectors per B row
     constexpr int BSTEP = kThreads / VPR;         // B rows covered by one pass of the workgroup
+    constexpr int G = col_group<T, WT>();         // neighbouring columns per lane (see col_group)
+    using GV = typename VecOfN<T, G>::type;
     constexpr bool DMA = ALIGNED == kAccessDma;
     static_assert(!(DMA && FIRST), "the combined operand of the first round is formed in registers");
     constexpr int APitch = DMA ? 128 : kAPitch;   // DMA: unpadded rows, 16-byte slots swizzled instead
@@ -309,8 +319,8 @@ __global__ __launch_bounds__(kThreads, WT == 4 ? 2 : 4) void gemm_round_kernel(G
     const int a_row_rd = (wm * 16 * WT + lj) * APitch;
     const int a_rd0 = a_row_rd + (DMA ? ((2 * lg) ^ ((lj >> 1) & 7)) * 16 : lg * 32);
     const int a_rd1 = a_row_rd + (DMA ? ((2 * lg + 1) ^ ((lj >> 1) & 7)) * 16 : lg * 32 + 16);
-    const int b_rd = BM * APitch + (lg * KQ) * BPitch + lj * (int)sizeof(T);
-    const int b_rc0 = (wn * 16 * WT + 16 * lg) * (int)sizeof(T);  // rotated column of tile column 0, before wrap
+    const int b_rd = BM * APitch + (lg * KQ) * BPitch;
+    const int b_rc0 = (wn * 16 * WT + G * lj + 16 * lg) * (int)sizeof(T);  // rotated column of this lane's first group, before wrap
 
     for (int kb = 0; kb < kblocks; ++kb) {
         const unsigned char *cur = smem + (kb & 1) * STAGE;
@@ -342,8 +352,12 @@ __global__ __launch_bounds__(kThreads, WT == 4 ? 2 : 4) void gemm_round_kernel(G
                 const int kk = h * VN + q;
                 T bf[WT];
 #pragma unroll
-                for (int tj = 0; tj < WT; ++tj)
-                    bf[tj] = *reinterpret_cast<const T *>(cur + b_rd + kk * BPitch + ((b_rc0 + tj * kRot) & (BPitch - 1)));
+                for (int g = 0; g < WT / G; ++g) {
+                    const GV x = *reinterpret_cast<const GV *>(cur + b_rd + kk * BPitch +
+                                                                ((b_rc0 + g * 16 * G * (int)sizeof(T)) & (BPitch - 1)));
+#pragma unroll
+                    for (int e = 0; e < G; ++e) bf[g * G + e] = x[e];
+                }
 #pragma unroll
                 for (int ti = 0; ti < WT; ++ti) {
                     const T a = reinterpret_cast<const T *>(&af[ti])[q];
@@ -366,9 +380,11 @@ __global__ __launch_bounds__(kThreads, WT == 4 ? 2 : 4) void gemm_round_kernel(G
     }
 
     // ---- epilogue -----------------------------------------------------------------------------
-    // lane holds C[row0 + wm*16*WT + 16*ti + Mfma<T>::row(lg, v)][col0 + wn*16*WT + 16*tj + lj]
+    // lane holds C[row0 + wm*16*WT + 16*ti + Mfma<T>::row(lg, v)][col0 + wn*16*WT + (tj/G)*16*G + G*lj + tj%G]:
+    // for every (ti, v) and every group of G tiles, G neighbouring elements of one row
     const int er = row0 + wm * 16 * WT;
-    const int ec = col0 + wn * 16 * WT + lj;
+    const int ec = col0 + wn * 16 * WT + G * lj;
+    constexpr bool kVecIO = ALIGNED != kAccessScalar;  // rows are 16-byte aligned and n is a multiple of G
     if (st.nsrc == 0 && st.nout == 1) {
         T *D = reinterpret_cast<T *>(p.base[st.dst[0]]) + moff;
 #pragma unroll
@@ -377,9 +393,20 @@ __global__ __launch_bounds__(kThreads, WT == 4 ? 2 : 4) void gemm_round_kernel(G
             for (int v = 0; v < 4; ++v) {
                 const int row = er + 16 * ti + Mfma<T>::row(lg, v);
 #pragma unroll
-                for (int tj = 0; tj < WT; ++tj) {
-                    const int col = ec + 16 * tj;
-                    if (ALIGNED >= kAccessFull || (row < n && col < n)) D[(size_t)row * n + col] = acc[ti][tj][v];
+                for (int g = 0; g < WT / G; ++g) {
+                    const int col = ec + g * 16 * G;
+                    if constexpr (kVecIO) {
+                        if (ALIGNED >= kAccessFull || (row < n && col < n)) {
+                            GV o;
+#pragma unroll
+                            for (int e = 0; e < G; ++e) o[e] = acc[ti][g * G + e][v];
+                            *reinterpret_cast<GV *>(D + (size_t)row * n + col) = o;
+                        }
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < G; ++e)
+                            if (row < n && col + e < n) D[(size_t)row * n + col + e] = acc[ti][g * G + e][v];
+                    }
                 }
             }
     } else {
@@ -396,25 +423,42 @@ __global__ __launch_bounds__(kThreads, WT == 4 ? 2 : 4) void gemm_round_kernel(G
             for (int v = 0; v < 4; ++v) {
                 const int row = er + 16 * ti + Mfma<T>::row(lg, v);
 #pragma unroll
-                for (int tj = 0; tj < WT; ++tj) {
-                    const int col = ec + 16 * tj;
-                    if (ALIGNED >= kAccessFull || (row < n && col < n)) {
-                        const size_t idx = (size_t)row * n + col;
-                        T sv[4];
+                for (int g = 0; g < WT / G; ++g) {
+                    const int col = ec + g * 16 * G;
+                    const size_t idx = (size_t)row * n + col;
+                    if (kVecIO ? (ALIGNED >= kAccessFull || (row < n && col < n)) : row < n) {
+                        GV sv[4];
 #pragma unroll
-                        for (int i = 0; i < 4; ++i) sv[i] = i < st.nsrc ? S[i][idx] : (T)0;
-                        T t = st.acc_scale * acc[ti][tj][v];
+                        for (int i = 0; i < 4; ++i) {
+                            if constexpr (kVecIO) {
+                                sv[i] = i < st.nsrc ? *reinterpret_cast<const GV *>(S[i] + idx) : (GV)(0);
+                            } else {
+#pragma unroll
+                                for (int e = 0; e < G; ++e) sv[i][e] = (i < st.nsrc && col + e < n) ? S[i][idx + e] : (T)0;
+                            }
+                        }
+                        GV t;
+#pragma unroll
+                        for (int e = 0; e < G; ++e) t[e] = st.acc_scale * acc[ti][g * G + e][v];
 #pragma unroll
                         for (int i = 0; i < 4; ++i) t += st.g[i] * sv[i];
-                        const T dg = row == col ? (T)1 : (T)0;
+                        GV dg;
+#pragma unroll
+                        for (int e = 0; e < G; ++e) dg[e] = row == col + e ? (T)1 : (T)0;
 #pragma unroll
                         for (int j = 0; j < 4; ++j) {
                             if (j < st.nout) {
-                                T o = st.a[j] * t;
+                                GV o = st.a[j] * t;
 #pragma unroll
                                 for (int i = 0; i < 4; ++i) o += st.b[j][i] * sv[i];
                                 o += st.d[j] * dg;
-                                D[j][idx] = o;
+                                if constexpr (kVecIO) {
+                                    *reinterpret_cast<GV *>(D[j] + idx) = o;
+                                } else {
+#pragma unroll
+                                    for (int e = 0; e < G; ++e)
+                                        if (col + e < n) D[j][idx + e] = o[e];
+                                }
                             }
                         }
                     }
@@ -434,7 +478,7 @@ __global__ __launch_bounds__(kThreads, WT == 4 ? 2 : 4) void gemm_round_kernel(G
                 for (int v = 0; v < 4; ++v) cs += fabs((double)acc[ti][tj][v]);
             cs += __shfl_xor(cs, 16);
             cs += __shfl_xor(cs, 32);
-            if (lg == 0) red[wm * BN + wn * 16 * WT + 16 * tj + lj] = cs;
+            if (lg == 0) red[wm * BN + wn * 16 * WT + (tj / G) * 16 * G + G * lj + tj % G] = cs;
         }
         __syncthreads();
         if (tid < BN) {
