@@ -15,6 +15,8 @@
 // 128 bytes per row.
 #include "expm_internal.h"
 
+#include <utility>
+
 #include <cstdlib>
 
 namespace expmk {
@@ -49,6 +51,11 @@ template <typename T, int WT> constexpr int stage_bytes(bool dma = false)
 // per source and destination in the epilogue).  G = 16 bytes' worth of elements, at most the tiles per wave.
 template <typename T, int WT> constexpr int col_group() { return WT < 16 / (int)sizeof(T) ? WT : 16 / (int)sizeof(T); }
 template <typename T, int N> struct VecOfN { typedef T type __attribute__((ext_vector_type(N))); };
+
+template <int... I, class F> __device__ __forceinline__ void static_for(std::integer_sequence<int, I...>, F &&f)
+{
+    (f(std::integral_constant<int, I>{}), ...);
+}
 
 struct GemmParams {
     void *base[BUF_COUNT];
@@ -131,6 +138,7 @@ __global__ __launch_bounds__(kThreads, WT == 4 ? 2 : 4) void gemm_round_kernel(G
     constexpr int G = col_group<T, WT>();         // neighbouring columns per lane (see col_group)
     using GV = typename VecOfN<T, G>::type;
     constexpr bool DMA = ALIGNED == kAccessDma;
+    constexpr bool kPipe = DMA && sizeof(T) == 4;  // fragment reads one k-step ahead (fp32: registers to spare; fp64 loses)
     static_assert(!(DMA && FIRST), "the combined operand of the first round is formed in registers");
     constexpr int APitch = DMA ? 128 : kAPitch;   // DMA: unpadded rows, 16-byte slots swizzled instead
     constexpr int STAGE = stage_bytes<T, WT>(DMA);
@@ -339,30 +347,64 @@ __global__ __launch_bounds__(kThreads, WT == 4 ? 2 : 4) void gemm_round_kernel(G
                 fetch_x(k0);
             }
         }
-        // A fragments: each lane's KQ k-values of a row are two 16-byte halves; one half (VN k-steps) at a
-        // time keeps the live registers low, the co-resident waves cover the LDS latency
+        // A fragments: each lane's KQ k-values of a row are two 16-byte halves (h = 0, 1), VN k-steps each.
+        if constexpr (kPipe) {
+            // Fragment registers in two sets: the reads for k-step kk + 1 (and, at the end of a half, for the next
+            // half of the left rows) are issued ahead of the 16 MFMAs of k-step kk and land while those run.
+            V af[2][WT];
+            GV bv[2][WT / G];
+            auto read_a = [&](int h) {
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            V af[WT];
+                for (int ti = 0; ti < WT; ++ti)
+                    af[h & 1][ti] = *reinterpret_cast<const V *>(cur + (h ? a_rd1 : a_rd0) + ti * 16 * APitch);
+            };
+            auto read_b = [&](int kk) {
 #pragma unroll
-            for (int ti = 0; ti < WT; ++ti)
-                af[ti] = *reinterpret_cast<const V *>(cur + (h ? a_rd1 : a_rd0) + ti * 16 * APitch);
-#pragma unroll
-            for (int q = 0; q < VN; ++q) {
-                const int kk = h * VN + q;
-                T bf[WT];
-#pragma unroll
-                for (int g = 0; g < WT / G; ++g) {
-                    const GV x = *reinterpret_cast<const GV *>(cur + b_rd + kk * BPitch +
-                                                                ((b_rc0 + g * 16 * G * (int)sizeof(T)) & (BPitch - 1)));
-#pragma unroll
-                    for (int e = 0; e < G; ++e) bf[g * G + e] = x[e];
-                }
+                for (int g = 0; g < WT / G; ++g)
+                    bv[kk & 1][g] = *reinterpret_cast<const GV *>(cur + b_rd + kk * BPitch +
+                                                                   ((b_rc0 + g * 16 * G * (int)sizeof(T)) & (BPitch - 1)));
+            };
+            read_a(0);
+            read_b(0);
+            static_for(std::make_integer_sequence<int, 2 * VN>{}, [&](auto KK) {
+                constexpr int kk = decltype(KK)::value, h = kk / VN, q = kk % VN;
+                constexpr bool more_b = kk + 1 < 2 * VN, more_a = more_b && q == VN - 1;
+                if constexpr (more_b) read_b(kk + 1);
+                if constexpr (more_a) read_a(h + 1);
 #pragma unroll
                 for (int ti = 0; ti < WT; ++ti) {
-                    const T a = reinterpret_cast<const T *>(&af[ti])[q];
+                    const T a = reinterpret_cast<const T *>(&af[h & 1][ti])[q];
 #pragma unroll
-                    for (int tj = 0; tj < WT; ++tj) acc[ti][tj] = Mfma<T>::run(a, bf[tj], acc[ti][tj]);
+                    for (int tj = 0; tj < WT; ++tj) acc[ti][tj] = Mfma<T>::run(a, bv[kk & 1][tj / G][tj % G], acc[ti][tj]);
+                }
+                // keep this order in the schedule: the reads first, then the MFMAs that do not depend on them
+                if constexpr (more_b) __builtin_amdgcn_sched_group_barrier(0x100, WT / G + (more_a ? WT : 0), 0);
+                __builtin_amdgcn_sched_group_barrier(0x008, WT * WT, 0);
+            });
+        } else {
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                V af[WT];
+#pragma unroll
+                for (int ti = 0; ti < WT; ++ti)
+                    af[ti] = *reinterpret_cast<const V *>(cur + (h ? a_rd1 : a_rd0) + ti * 16 * APitch);
+#pragma unroll
+                for (int q = 0; q < VN; ++q) {
+                    const int kk = h * VN + q;
+                    T bf[WT];
+#pragma unroll
+                    for (int g = 0; g < WT / G; ++g) {
+                        const GV x = *reinterpret_cast<const GV *>(cur + b_rd + kk * BPitch +
+                                                                    ((b_rc0 + g * 16 * G * (int)sizeof(T)) & (BPitch - 1)));
+#pragma unroll
+                        for (int e = 0; e < G; ++e) bf[g * G + e] = x[e];
+                    }
+#pragma unroll
+                    for (int ti = 0; ti < WT; ++ti) {
+                        const T a = reinterpret_cast<const T *>(&af[ti])[q];
+#pragma unroll
+                        for (int tj = 0; tj < WT; ++tj) acc[ti][tj] = Mfma<T>::run(a, bf[tj], acc[ti][tj]);
+                    }
                 }
             }
         }
