@@ -127,6 +127,17 @@ def test_rounds_fp32_sizes(ex, n, batch):
     assert stats["fused_path"] == 0
 
 
+@pytest.mark.parametrize("n,dtype", [(1030, np.float64), (1027, np.float64), (1028, np.float32), (1030, np.float32),
+                                     (1152, np.float32)])
+def test_rounds_128_tiles_ragged_and_full(ex, n, dtype):
+    """From n = 1024 on the products run in 128x128 tiles: sizes that are not a multiple of the tile (vector loads
+    with bounds checks where rows are 16-byte aligned, element-wise loads where they are not) and one that is."""
+    from paper_2512_20777_amd import workloads
+    a = workloads.random_stack(500 + n, 2, n, dtype, 0.3, 6.0)
+    _, m, s, info, stats = _run_and_check(ex, a, label="rounds 128-tiles n=%d %s" % (n, np.dtype(dtype).name))
+    assert stats["fused_path"] == 0
+
+
 @pytest.mark.parametrize("dtype", [np.float64, np.float32])
 def test_rounds_all_orders_in_one_batch(ex, dtype):
     """Norms from 1e-10 to 300 in one batch: every order 0,1,2,4,8,15+ and several scalings at once."""
