@@ -183,9 +183,14 @@ __global__ __launch_bounds__(256) void fused_expm_kernel(const T *__restrict__ A
             }
             const int bad = !(line <= 1.7976931348623157e308);
             double mx = bad ? 0.0 : line;
-            mx = row16_allreduce(mx, mxop);
-            mx = mxop(mx, __shfl_xor(mx, 16));
-            mx = mxop(mx, __shfl_xor(mx, 32));
+            if (!norm_inf) {
+                // a column sum is the same in all four 16-lane groups: the maximum over one group is the norm
+                mx = row16_allreduce(mx, mxop);
+            } else {
+                // a lane's maximum over its four rows is the same in all lanes of a group: combine the four groups
+                mx = mxop(mx, __shfl_xor(mx, 16));
+                mx = mxop(mx, __shfl_xor(mx, 32));
+            }
             return __any(bad) ? __longlong_as_double(0x7ff8000000000000LL) : mx;
         }
         sync();  // red[] free to overwrite
