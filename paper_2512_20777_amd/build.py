@@ -18,6 +18,9 @@ HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     # no hand-written or compiler-generated packed-fp32 instructions
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # MFMA results in ordinary vector registers (no kernel here needs the accumulator file's extra capacity; the
+    # copies between the two files cost the small kernels up to 15 %)
+    "-mllvm", "-amdgpu-mfma-vgpr-form=1",
     "-fno-gpu-rdc", "-Wall", "-Wno-unused-function",
 ]
 
