@@ -25,6 +25,7 @@ namespace {
 
 constexpr int kThreads = 256;
 constexpr int kAPitch = 144;    // bytes per A row in LDS: 128 data + 16 pad (conflict-free 16-byte reads)
+constexpr int kThinGroups = 384;    // launches of at most this many 64x64 tiles switch to 32x32 tiles
 constexpr int kColChunk = 32;   // rows per column-abs-sum partial of the input matrix
 
 template <typename T> struct Tile;
@@ -790,9 +791,11 @@ hipError_t launch_gemm(const GemmParams &p, int dtype, int wt, bool ptr_align16,
     if (p.total <= 0) return hipSuccess;
     if (dtype == 1) {
         const bool al = ptr_align16 && p.n % 2 == 0;
+        if (wt == 1) return launch_gemm_a<double, 1>(p, al, stream);
         return wt == 4 ? launch_gemm_a<double, 4>(p, al, stream) : launch_gemm_a<double, 2>(p, al, stream);
     }
     const bool al = ptr_align16 && p.n % 4 == 0;
+    if (wt == 1) return launch_gemm_a<float, 1>(p, al, stream);
     return wt == 4 ? launch_gemm_a<float, 4>(p, al, stream) : launch_gemm_a<float, 2>(p, al, stream);
 }
 
@@ -811,7 +814,7 @@ hipError_t launch_gemm_first(const GemmParams &p, bool aligned, hipStream_t stre
 // register-bound 128x128 kernels have no room for the extra vectors.)
 bool first_round_is_self_contained(int n, int scheme)
 {
-    return scheme == kSchemeSastre && n < 1024 && choose_tile_shape(n, 1) == 2;
+    return scheme == kSchemeSastre && n < 1024;  // the sizes whose first round (whole batch) runs in 64x64 tiles
 }
 
 hipError_t launch_first_round(const GeneralBuffers &gb, int n, int batch, int dtype, hipStream_t stream)
@@ -838,7 +841,12 @@ int choose_tile_shape(int n, int matrices)
     if (forced) return forced;
     // Measured on MI355X: up to n of several hundred the 64x64 shape is as fast per product and, with
     // four workgroups per compute unit out of phase, hides the fused epilogues' memory traffic better.
-    if (n < 1024) return 2;
+    if (n < 1024) {
+        // thin launches (late rounds, few matrices left): a compute unit that holds a single 64x64 workgroup runs one
+        // wave per SIMD and nothing covers its latencies; 32x32 tiles give four times the workgroups
+        const long long t64 = (long long)matrices * ((n + 63) / 64) * ((n + 63) / 64);
+        return t64 <= kThinGroups ? 1 : 2;
+    }
     const long long cus = 256;
     const long long t4 = (long long)matrices * ((n + 127) / 128) * ((n + 127) / 128);
     const long long t2 = (long long)matrices * ((n + 63) / 64) * ((n + 63) / 64);

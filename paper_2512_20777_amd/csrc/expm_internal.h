@@ -424,7 +424,7 @@ hipError_t launch_small(const void *A, void *out, int n, int batch, int dtype, d
 // larger-n path
 int general_colchunks(int n);   // row chunks of the column abs-sum pass over the input
 int general_colblocks(int n);   // 256-column blocks: per-block maxima make up n1 / n2
-int choose_tile_shape(int n, int matrices);  // 4 -> 128x128 tiles, 2 -> 64x64 tiles
+int choose_tile_shape(int n, int matrices);  // 4 -> 128x128 tiles, 2 -> 64x64 tiles, 1 -> 32x32 tiles
 hipError_t launch_colabs(const GeneralBuffers &gb, int n, int batch, int dtype, hipStream_t stream);
 hipError_t launch_colmax(const GeneralBuffers &gb, int n, int batch, int which, int chunks, hipStream_t stream);
 hipError_t launch_power_round(const GeneralBuffers &gb, int n, int batch, int dtype, int wt, int which,
