@@ -839,17 +839,16 @@ int choose_tile_shape(int n, int matrices)
         return (v == 2 || v == 4) ? v : 0;
     }();
     if (forced) return forced;
+    // Thin launches (late rounds with few matrices left, small batches): a compute unit that holds a single workgroup
+    // runs one wave per SIMD and nothing covers its latencies; a smaller tile gives four times the workgroups.
+    const long long t2 = (long long)matrices * ((n + 63) / 64) * ((n + 63) / 64);
+    if (t2 <= kThinGroups) return 1;
     // Measured on MI355X: up to n of several hundred the 64x64 shape is as fast per product and, with
     // four workgroups per compute unit out of phase, hides the fused epilogues' memory traffic better.
-    if (n < 1024) {
-        // thin launches (late rounds, few matrices left): a compute unit that holds a single 64x64 workgroup runs one
-        // wave per SIMD and nothing covers its latencies; 32x32 tiles give four times the workgroups
-        const long long t64 = (long long)matrices * ((n + 63) / 64) * ((n + 63) / 64);
-        return t64 <= kThinGroups ? 1 : 2;
-    }
+    if (n < 1024) return 2;
     const long long cus = 256;
     const long long t4 = (long long)matrices * ((n + 127) / 128) * ((n + 127) / 128);
-    const long long t2 = (long long)matrices * ((n + 63) / 64) * ((n + 63) / 64);
+    if (t4 < 2 * cus) return 2;  // fewer than two 128x128 workgroups per compute unit: the same, one size up
     const double cost4 = (double)((t4 + cus - 1) / cus);
     const double cost2 = (double)((t2 + cus - 1) / cus) * 0.25 / 0.9;
     return cost2 < cost4 ? 2 : 4;

@@ -133,7 +133,8 @@ def test_rounds_128_tiles_ragged_and_full(ex, n, dtype):
     """From n = 1024 on the products run in 128x128 tiles: sizes that are not a multiple of the tile (vector loads
     with bounds checks where rows are 16-byte aligned, element-wise loads where they are not) and one that is."""
     from paper_2512_20777_amd import workloads
-    a = workloads.random_stack(500 + n, 2, n, dtype, 0.3, 6.0)
+    # seven matrices: a launch switches to 128x128 tiles only when it has at least two such workgroups per compute unit
+    a = workloads.random_stack(500 + n, 7, n, dtype, 0.3, 6.0)
     _, m, s, info, stats = _run_and_check(ex, a, label="rounds 128-tiles n=%d %s" % (n, np.dtype(dtype).name))
     assert stats["fused_path"] == 0
 
