@@ -10,9 +10,10 @@
 //                            every linear combination the next round needs (Sec. 3.1 formulas)
 //
 // The product kernel computes a (32*WT)x(32*WT) tile per workgroup of 256 threads (2x2 waves, each
-// WT x WT MFMA 16x16x4 tiles in the matrix dtype); WT = 4 is the main shape, WT = 2 serves rounds with
-// too few tiles to fill the chip.  Operands are staged through double-buffered LDS in k-blocks of
-// 128 bytes per row.
+// WT x WT MFMA 16x16x4 tiles in the matrix dtype); WT = 4 for large matrices, WT = 2 below n = 1024 and for
+// launches with too few tiles to give every compute unit two workgroups, WT = 1 for thin launches.
+// Operands are staged through double-buffered LDS in k-blocks of 128 bytes per row: straight from global
+// memory into LDS when tiles are full and rows 16-byte aligned, through registers otherwise.
 #include "expm_internal.h"
 
 #include <utility>
@@ -826,7 +827,8 @@ hipError_t launch_first_round(const GeneralBuffers &gb, int n, int batch, int dt
 }
 
 // Tile shape for a round with `matrices` active matrices of order n: 128x128 tiles (WT = 4) for large
-// matrices unless they would leave compute units idle or poorly balanced, 64x64 tiles (WT = 2) otherwise.
+// matrices unless they would leave compute units idle or poorly balanced, 64x64 tiles (WT = 2) otherwise,
+// 32x32 tiles (WT = 1) for thin launches.
 // Cost model for n >= 1024, in units of one 128x128 tile on one compute unit: a compute unit works
 // through its tiles one after another (co-resident tiles share the matrix pipe); a 64x64 tile costs a
 // quarter of the work at roughly 0.9 of the efficiency.
