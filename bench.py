@@ -449,7 +449,7 @@ def main():
         per.sort(key=lambda r: r["workload"])
     note = workloads.LOWRANK_WORKLOADS[head]["note"] if lowrank_head else workloads.WORKLOADS[head].note
     line = {
-        "metric": "matrix exponentials/sec (+ achieved TFLOP/s and fraction of MFMA/HBM roofline per workload)",
+        "metric": "matrix exponentials/sec + achieved TFLOP/s (% of MFMA peak) per (n,batch,dtype)",
         "value": main_res["matrices_per_s"], "unit": "matrices/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
         "ms_per_step": main_res["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": main_res["dtype"], "data": "synthetic",
