@@ -40,6 +40,15 @@
  * (W = A1 A2, the series in V = A2 A1, no scaling), pinned in tests/test_lowrank.py by the full-size
  * exponential of A1 A2, the rank-one closed form, a nilpotent pair and exact-rational checks of the order.
  *
+ * Entry points that take (m, s) -- or the order of the low-rank series -- as given evaluate the same polynomial
+ * through the same routine as the selecting calls (oracle_expm_forced, oracle_lowrank_forced); the parity tests use
+ * them for matrices whose norms sit within 1e-6 of a switch point, where the device may take the other admissible
+ * choice.  Pinned in tests/test_oracle_forced_pins.py: bit-equal to the selecting calls for the pair those select,
+ * the closed form (sum_{k<=m} (x/2^s)^k/k! [+ b16 (x/2^s)^16])^(2^s) on 1 x 1 input in exact rationals, and the
+ * rank-one closed form; the same file pins the row-parallel products of the batch drivers (order >= 256) by
+ * bit-equality with the sequential ones, and the `near` flags of Algorithm 3 and of the baseline at hand-placed
+ * switch points.
+ *
  * Pins (tests/test_oracle_pins.py): the two worked selection examples of the
  * paper (Remark 1; Sec. 4.2, normal matrix of norm 12.8), closed forms
  * (diagonal, nilpotent, rotation, Remark-1 matrix), det/trace and inverse
@@ -241,19 +250,30 @@ int oracle_select(const double *W, int n, double eps, int *m, int *s,
     return 0;
 }
 
+/* Threads the OpenMP runtime offered when the library was first asked: a batch call with an explicit thread count
+ * changes the runtime's own default, so "all threads" must not be read back from it afterwards. */
+static int all_threads(void)
+{
+#ifdef _OPENMP
+    static int offered = 0;
+    if (offered <= 0)
+        offered = omp_get_max_threads();
+    return offered;
+#else
+    return 1;
+#endif
+}
+
 /*
- * Algorithm 2 for one matrix: select (m,s), A = W/2^s, X = polynomial by
- * direct summation, s squarings.  `work` holds 4*n*n doubles.
+ * Evaluation half of Algorithm 2 with the order and the scaling given: A = W/2^s,
+ * X = sum_{k=0..m} A^k/k! by direct summation (term_k = term_{k-1} * A / k), plus
+ * b16 * A^16 when `plus16` is set (the 15+ approximant, Sec. 3.1: y22 = T15 + b16 A^16),
+ * then s squarings.  `work` holds 3*n*n doubles.
  */
-static void expm_matrix(const double *W, int n, double eps, double *X, double *work, int par,
-                        int *m_out, int *s_out, double *n1, double *n2, int *near)
+static void taylor_then_square(const double *W, int n, int m, int s, int plus16, double *X, double *work, int par)
 {
     const size_t nn = (size_t)n * n;
-    double *A = work, *term = work + nn, *next = work + 2 * nn, *W2 = work + 3 * nn;
-    int m, s;
-    select_matrix(W, n, eps, W2, par, &m, &s, n1, n2, near);
-    *m_out = m;
-    *s_out = s;
+    double *A = work, *term = work + nn, *next = work + 2 * nn;
 
     const double scale = ldexp(1.0, -s); /* exact power of two */
     for (size_t t = 0; t < nn; ++t)
@@ -279,8 +299,8 @@ static void expm_matrix(const double *W, int n, double eps, double *X, double *w
         for (size_t t = 0; t < nn; ++t)
             X[t] += term[t];
     }
-    if (m == 15) {
-        /* 15+ : add b16 * A^16 = (b16 * 16!) * (A^16/16!) */
+    if (plus16) {
+        /* 15+ : add b16 * A^16 = (b16 * 16!) * (A^16/16!); term holds A^15/15! here */
         matmul_impl(term, A, next, n, par);
         const double w = oracle_b16() * factorial(16);
         for (size_t t = 0; t < nn; ++t)
@@ -293,6 +313,45 @@ static void expm_matrix(const double *W, int n, double eps, double *X, double *w
     }
 }
 
+/*
+ * Algorithm 2 for one matrix: select (m,s), A = W/2^s, X = polynomial by
+ * direct summation, s squarings.  `work` holds 4*n*n doubles.
+ */
+static void expm_matrix(const double *W, int n, double eps, double *X, double *work, int par,
+                        int *m_out, int *s_out, double *n1, double *n2, int *near)
+{
+    const size_t nn = (size_t)n * n;
+    int m, s;
+    select_matrix(W, n, eps, work + 3 * nn, par, &m, &s, n1, n2, near);
+    *m_out = m;
+    *s_out = s;
+    taylor_then_square(W, n, m, s, m == 15, X, work, par);
+}
+
+/*
+ * The same evaluation with (m, s) handed in instead of selected: what Algorithm 2 computes once
+ * Algorithm 3 or 4 has returned this pair.  Used by the parity tests for matrices whose norms sit
+ * within 1e-6 of a switch point, where the device may rightly take the neighbouring choice.
+ * plus16 != 0 adds the b16 A^16 term of the 15+ approximant (only meaningful with m == 15).
+ * threads <= 0: all; the rows of every product are spread over the threads when n >= 256.
+ */
+int oracle_expm_forced(const double *W, int n, int m, int s, int plus16, double *X, int threads)
+{
+    if (m < 0 || s < 0 || (plus16 && m != 15))
+        return -1;
+    double *work = (double *)malloc(sizeof(double) * 3 * (size_t)n * n + 8);
+    if (!work)
+        return -3;
+#ifdef _OPENMP
+    omp_set_num_threads(threads <= 0 ? all_threads() : threads);
+#else
+    (void)threads;
+#endif
+    taylor_then_square(W, n, m, s, plus16, X, work, n >= 256);
+    free(work);
+    return 0;
+}
+
 int oracle_expm(const double *W, int n, double eps, double *X, int *m, int *s,
                 double *n1, double *n2, int *near)
 {
@@ -302,20 +361,6 @@ int oracle_expm(const double *W, int n, double eps, double *X, int *m, int *s,
     expm_matrix(W, n, eps, X, work, 0, m, s, n1, n2, near);
     free(work);
     return 0;
-}
-
-/* Threads the OpenMP runtime offered when the library was first asked: a batch call with an explicit thread count
- * changes the runtime's own default, so "all threads" must not be read back from it afterwards. */
-static int all_threads(void)
-{
-#ifdef _OPENMP
-    static int offered = 0;
-    if (offered <= 0)
-        offered = omp_get_max_threads();
-    return offered;
-#else
-    return 1;
-#endif
 }
 
 /*
@@ -477,33 +522,11 @@ static void expm_ps_matrix(const double *W, int n, double eps, double *X, double
                            int *m_out, int *s_out, double norms[4], int *near)
 {
     const size_t nn = (size_t)n * n;
-    double *A = work, *term = work + nn, *next = work + 2 * nn;
     int m, s;
     select_ps_matrix(W, n, eps, work + 3 * nn, par, &m, &s, norms, near);
     *m_out = m;
     *s_out = s;
-    const double scale = ldexp(1.0, -s);
-    for (size_t t = 0; t < nn; ++t)
-        A[t] = W[t] * scale;
-    memset(X, 0, sizeof(double) * nn);
-    for (int i = 0; i < n; ++i)
-        X[(size_t)i * n + i] = 1.0;
-    for (int k = 1; k <= m; ++k) {
-        if (k == 1) {
-            memcpy(term, A, sizeof(double) * nn);
-        } else {
-            matmul_impl(term, A, next, n, par);
-            const double inv = (double)k;
-            for (size_t t = 0; t < nn; ++t)
-                term[t] = next[t] / inv;
-        }
-        for (size_t t = 0; t < nn; ++t)
-            X[t] += term[t];
-    }
-    for (int q = 0; q < s; ++q) {
-        matmul_impl(X, X, next, n, par);
-        memcpy(X, next, sizeof(double) * nn);
-    }
+    taylor_then_square(W, n, m, s, 0, X, work, par);
 }
 
 /* Batch driver of the Paterson-Stockmeyer variant; norms is [batch][4]. */
@@ -696,12 +719,39 @@ static void matmul_rect(const double *A, const double *B, double *C, int p, int 
     }
 }
 
+/* X = I + A1 (sum_{i=0..m} V^i/(i+1)!) A2 for a given order m >= 0; V = A2 A1 (t x t) is handed in.
+ * work: 2*t*t + max(t*n, t*t) doubles. */
+static void lowrank_eval(const double *A1, const double *A2, const double *V, int n, int t, int m, double *X, double *work)
+{
+    const size_t tt = (size_t)t * t;
+    double *Phi = work, *term = work + tt, *PA2 = work + 2 * tt; /* PA2: t x n */
+    /* Phi = sum_{i=0..m} V^i / (i+1)!, term by term: term_0 = I, term_i = term_{i-1} V / (i+1) */
+    memset(Phi, 0, sizeof(double) * tt);
+    memset(term, 0, sizeof(double) * tt);
+    for (int i = 0; i < t; ++i) {
+        Phi[(size_t)i * t + i] = 1.0;
+        term[(size_t)i * t + i] = 1.0;
+    }
+    for (int i = 1; i <= m; ++i) {
+        double *next = PA2; /* the last scratch area holds at least t*t doubles */
+        matmul_rect(term, V, next, t, t, t);
+        for (size_t e = 0; e < tt; ++e) {
+            term[e] = next[e] / (double)(i + 1);
+            Phi[e] += term[e];
+        }
+    }
+    matmul_rect(Phi, A2, PA2, t, t, n);
+    matmul_rect(A1, PA2, X, n, t, n);
+    for (int i = 0; i < n; ++i)
+        X[(size_t)i * n + i] += 1.0;
+}
+
 /* One pair (A1, A2).  work: 3*t*t + max(t*n, t*t) doubles.  X: n x n. */
 static void lowrank_matrix(const double *A1, const double *A2, int n, int t, double eps, double *X, double *work,
                            int *m_out, int *flag_out, double *v1_out, int *near)
 {
     const size_t tt = (size_t)t * t;
-    double *V = work, *Phi = work + tt, *term = work + 2 * tt, *PA2 = work + 3 * tt; /* PA2: t x n */
+    double *V = work;
     matmul_rect(A2, A1, V, t, n, t);
     const double v1 = oracle_norm1(V, t);
     int m, flag;
@@ -722,25 +772,22 @@ static void lowrank_matrix(const double *A1, const double *A2, int n, int t, dou
             X[e] = NAN;
         return;
     }
-    /* Phi = sum_{i=0..m} V^i / (i+1)!, term by term: term_0 = I, term_i = term_{i-1} V / (i+1) */
-    memset(Phi, 0, sizeof(double) * tt);
-    memset(term, 0, sizeof(double) * tt);
-    for (int i = 0; i < t; ++i) {
-        Phi[(size_t)i * t + i] = 1.0;
-        term[(size_t)i * t + i] = 1.0;
-    }
-    for (int i = 1; i <= m; ++i) {
-        double *next = PA2; /* the last scratch area holds at least t*t doubles */
-        matmul_rect(term, V, next, t, t, t);
-        for (size_t e = 0; e < tt; ++e) {
-            term[e] = next[e] / (double)(i + 1);
-            Phi[e] += term[e];
-        }
-    }
-    matmul_rect(Phi, A2, PA2, t, t, n);
-    matmul_rect(A1, PA2, X, n, t, n);
-    for (int i = 0; i < n; ++i)
-        X[(size_t)i * n + i] += 1.0;
+    lowrank_eval(A1, A2, V, n, t, m, X, work + tt);
+}
+
+/* The same with the order handed in (for pairs whose ||V|| sits within 1e-6 of a switch point). */
+int oracle_lowrank_forced(const double *A1, const double *A2, int n, int t, int m, double *X)
+{
+    if (m < 0)
+        return -1;
+    const size_t tt = (size_t)t * t, tn = (size_t)t * n;
+    double *work = (double *)malloc(sizeof(double) * (3 * tt + (tn > tt ? tn : tt)) + 8);
+    if (!work)
+        return -3;
+    matmul_rect(A2, A1, work, t, n, t);
+    lowrank_eval(A1, A2, work, n, t, m, X, work + tt);
+    free(work);
+    return 0;
 }
 
 /* Batch: A1 [batch][n][t], A2 [batch][t][n], X [batch][n][n]; returns threads used or -3. */
@@ -779,4 +826,22 @@ int oracle_lowrank_batch(const double *A1, const double *A2, int n, int t, int b
 int oracle_max_threads(void)
 {
     return all_threads();
+}
+
+/* One product with its rows spread over the threads, exactly as the batch drivers run products of matrices of
+ * order >= 256 (same loop, same summation order per element).  Exported so that the benchmark can time a single
+ * product at a size whose whole exponential takes many minutes.  Returns the thread count used. */
+int oracle_matmul_threads(const double *A, const double *B, double *C, int n, int threads)
+{
+    int used = 1;
+#ifdef _OPENMP
+    if (threads <= 0)
+        threads = all_threads();
+    used = threads;
+    omp_set_num_threads(threads);
+#else
+    (void)threads;
+#endif
+    matmul_impl(A, B, C, n, 1);
+    return used;
 }

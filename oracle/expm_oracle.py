@@ -69,6 +69,12 @@ def _load():
                                              ip, ip, dp, ip, ctypes.c_int]
         lib.oracle_max_threads.restype = ctypes.c_int
         lib.oracle_max_threads.argtypes = []
+        lib.oracle_expm_forced.restype = ctypes.c_int
+        lib.oracle_expm_forced.argtypes = [dp, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, dp, ctypes.c_int]
+        lib.oracle_lowrank_forced.restype = ctypes.c_int
+        lib.oracle_lowrank_forced.argtypes = [dp, dp, ctypes.c_int, ctypes.c_int, ctypes.c_int, dp]
+        lib.oracle_matmul_threads.restype = ctypes.c_int
+        lib.oracle_matmul_threads.argtypes = [dp, dp, dp, ctypes.c_int, ctypes.c_int]
         _lib = lib
     return _lib
 
@@ -255,6 +261,44 @@ def oracle_lowrank_batch(A1, A2, tol: float, threads: int = 0):
         if used < 0:
             raise MemoryError("oracle_lowrank_batch")
     return X, dict(m=m, flag=flag, v1=v1, near=near.astype(bool), threads=used)
+
+
+def oracle_expm_forced(W, m: int, s: int, plus16=None, threads: int = 0) -> np.ndarray:
+    """Algorithm 2 with the order and scaling given: sum_{k<=m} A^k/k! (+ b16 A^16 for the 15+ approximant), A = W/2^s,
+    then s squarings.  plus16 defaults to (m == 15), the main scheme's meaning of order 15; pass False for the plain
+    Taylor polynomial of the Paterson-Stockmeyer variant and of the baseline."""
+    a = _as_f64(W)
+    n = a.shape[0]
+    assert a.shape == (n, n)
+    X = np.empty((n, n), dtype=np.float64)
+    p16 = (int(m) == 15) if plus16 is None else bool(plus16)
+    rc = _load().oracle_expm_forced(_dptr(a), n, int(m), int(s), int(p16), _dptr(X), int(threads))
+    if rc != 0:
+        raise ValueError("oracle_expm_forced: status %d" % rc)
+    return X
+
+
+def oracle_lowrank_forced(A1, A2, m: int) -> np.ndarray:
+    """I + A1 (sum_{i<=m} V^i/(i+1)!) A2, V = A2 A1, with the order m given."""
+    a1 = np.ascontiguousarray(np.asarray(A1, dtype=np.float64))
+    a2 = np.ascontiguousarray(np.asarray(A2, dtype=np.float64))
+    n, t = a1.shape
+    assert a2.shape == (t, n)
+    X = np.empty((n, n), dtype=np.float64)
+    rc = _load().oracle_lowrank_forced(_dptr(a1), _dptr(a2), n, t, int(m), _dptr(X))
+    if rc != 0:
+        raise ValueError("oracle_lowrank_forced: status %d" % rc)
+    return X
+
+
+def oracle_matmul_threads(A, B, threads: int = 0):
+    """One triple-loop product with rows spread over the threads -> (C, threads used)."""
+    a, b = _as_f64(A), _as_f64(B)
+    n = a.shape[0]
+    assert a.shape == (n, n) and b.shape == (n, n)
+    c = np.empty((n, n), dtype=np.float64)
+    used = _load().oracle_matmul_threads(_dptr(a), _dptr(b), _dptr(c), n, int(threads))
+    return c, int(used)
 
 
 def oracle_max_threads() -> int:
