@@ -1,11 +1,12 @@
 #!/usr/bin/env python3
 """Benchmark of the batched matrix exponential on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C2] [--no-others] [--no-cpu] [--no-extras]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C5f64] [--no-others] [--no-cpu] [--no-extras]
 
 A step is one expm() call over one synthetic batch that is already resident in HBM: norms,
 selection of (m, s), polynomial evaluation, squarings and the store of the result.  Prints one
-JSON line: the headline workload plus, under "per_config", the same figures for all workloads.
+JSON line: the headline workload (by default the largest one, 4 matrices of order 4096 in fp64) plus, under
+"per_config", the same figures for all workloads.
 """
 import argparse
 import json
@@ -17,8 +18,8 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 PEAK = {"hbm": 8000.0, "mfma_f32": 157.3, "mfma_f64": 78.6}  # GB/s, TFLOP/s (MI355X published)
-DEFAULT_STEPS = {"F1": 1000, "C1": 1000, "C2": 1000, "C3": 100, "C4": 60, "C5f64": 4, "C5f32": 6, "L1": 100}
-DEFAULT_WARMUP = {"F1": 500, "C1": 500, "C2": 500, "C3": 20, "C4": 15, "C5f64": 2, "C5f32": 2, "L1": 10}
+DEFAULT_STEPS = {"F1": 1000, "C1": 1000, "C2": 1000, "C3": 100, "C4": 60, "C5f64": 20, "C5f32": 20, "L1": 100}
+DEFAULT_WARMUP = {"F1": 500, "C1": 500, "C2": 500, "C3": 20, "C4": 15, "C5f64": 3, "C5f32": 3, "L1": 10}
 
 
 def source_sha1():
@@ -216,23 +217,37 @@ def run_lowrank_workload(name, steps, warmup, with_cpu):
     return res
 
 
-def cpu_baseline(name, a, tol, workloads):
-    """The oracle, as it stands, on the host cores: whole batch when that takes seconds, else recorded."""
+def cpu_baseline(name, a, tol, workloads, ms=None):
+    """The oracle, as it stands, on the host cores, timed in this run: the whole batch when that takes seconds; for the
+    4096 x 4096 workloads (whose whole run takes more than ten minutes) one of its products, timed here, times the
+    number of products the oracle spends on the batch.  `ms` = (m, s) per matrix as the device selected them."""
     import numpy as np
-    from oracle import oracle_expm_batch, oracle_max_threads
+    from oracle import oracle_expm_batch, oracle_matmul_threads
     w = workloads.WORKLOADS[name]
     if name.startswith("C5"):
+        # The oracle forms W^2 for the selection, then sums the series term by term from A (m - 1 products, one more
+        # for the b16 A^16 term of 15+) and squares s times: per matrix 1 + (m - 1) + [m = 15] + s products of
+        # 2 n^3 flops, everything else is O(n^2).
+        m, sc = ms
+        counts = [1 + max(int(mm) - 1, 0) + (1 if mm == 15 else 0) + int(ss) for mm, ss in zip(m, sc)]
+        x = np.ascontiguousarray(a[-1], dtype=np.float64)
+        t0 = time.perf_counter()
+        _, used = oracle_matmul_threads(x, x)
+        sec = time.perf_counter() - t0
+        total = sec * sum(counts)
+        res = {"value": w.batch / total, "unit": "matrices/s", "cores": int(used), "kind": "oracle",
+               "sample": "one 4096^3 product of the oracle (W*W of the last matrix, rows over %d threads) timed in this "
+                         "run: %.2f s; times the %d products the oracle spends on this batch (1 + (m-1) + [m=15] + s "
+                         "per matrix) = %.0f s for the batch, extrapolated" % (used, sec, sum(counts), total)}
         path = os.path.join(ROOT, "tests", "golden", "c5_samples_%s.npz" % w.dtype)
-        if not os.path.exists(path):
-            return None
-        g = np.load(path)
-        sec = float(g["oracle_seconds"][0])
-        return {"value": w.batch / sec, "unit": "matrices/s", "cores": int(g["oracle_threads"][0]), "kind": "oracle",
-                "sample": "whole batch, %.0f s, recorded when tests/golden/make_c5_samples.py wrote the stored "
-                          "samples (not re-timed in this run)" % sec}
-    reps = {"F1": 50, "C1": 200, "C2": 50, "C3": 5, "C4": 1}[name]
+        if os.path.exists(path):
+            g = np.load(path)
+            res["whole_batch_recorded"] = {"seconds": float(g["oracle_seconds"][0]), "cores": int(g["oracle_threads"][0]),
+                                           "note": "the oracle's full run when tests/golden/make_c5_samples.py wrote the "
+                                                   "stored samples, on another machine"}
+        return res
+    reps = {"F1": 50, "C1": 200, "C2": 50, "C3": 5, "C4": 3}[name]
     if w.norm == "inf":  # infinity-norm selection of W = 1-norm selection of its transpose (same work for the oracle)
-        import numpy as np
         a = np.ascontiguousarray(np.swapaxes(a, -1, -2))
     oracle_expm_batch(a[: max(1, min(4, a.shape[0]))], tol)  # load the library, warm caches
     t0 = time.perf_counter()
@@ -242,7 +257,7 @@ def cpu_baseline(name, a, tol, workloads):
         used = info["threads"]
     sec = (time.perf_counter() - t0) / reps
     res = {"value": a.shape[0] / sec, "unit": "matrices/s", "cores": int(used), "kind": "oracle",
-           "sample": "whole batch of %d, mean of %d runs, %.4f s per batch" % (a.shape[0], reps, sec)}
+           "sample": "whole batch of %d, mean of %d runs in this run, %.4f s per batch" % (a.shape[0], reps, sec)}
     if name in ("C1", "C2", "F1"):
         # the small workloads also on one core (a threaded run of so little work mostly measures the thread team)
         r1 = max(1, reps // 5)
@@ -361,7 +376,11 @@ def run_workload(name, steps, warmup, with_cpu, extras=False, compare_ps=False):
     if extras and stats["fused_path"] and res["roofline"]["bound"] == "hbm":
         res["context"] = small_matrix_context(ex, torch, workloads, name, d, out, norm)
     if with_cpu:
-        res["cpu_baseline"] = cpu_baseline(name, a, w.tol, workloads)
+        ms = None
+        if name.startswith("C5"):
+            m_sel, s_sel, _ = ex.expm_select(d, w.tol, norm=norm)
+            ms = (m_sel, s_sel)
+        res["cpu_baseline"] = cpu_baseline(name, a, w.tol, workloads, ms)
     del d, out
     torch.cuda.empty_cache()
     return res
@@ -399,7 +418,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=0)
     ap.add_argument("--warmup", type=int, default=-1)
-    ap.add_argument("--workload", default="C2")
+    ap.add_argument("--workload", default="C5f64")
     ap.add_argument("--no-others", action="store_true", help="only the headline workload")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
     ap.add_argument("--pmc-pass", action="store_true", help="short run for hardware-counter collection: a few "
