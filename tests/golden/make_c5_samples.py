@@ -7,7 +7,9 @@ Takes roughly ten minutes per dtype on 8 host cores.  Usage (from the repository
     python tests/golden/make_c5_samples.py [f64|f32|both] [threads]
 
 Stored per dtype: sample index pairs (seeded), the oracle values at those entries, the Frobenius
-norm of each full oracle result, and the oracle's (m, s, ||W||_1, ||W^2||_1, near) per matrix.
+norm of each full oracle result, and the oracle's (m, s, ||W||_1, ||W^2||_1, near) per matrix; and, so that
+every 128 x 128 tile of the result is gated and not only the sampled entries: the Frobenius norm of every tile,
+one bilinear probe u_I^T X_IJ v_J per tile (u, v seeded vectors of +-1, stored), and all row and column sums.
 """
 import importlib.util
 import os
@@ -29,6 +31,16 @@ _spec.loader.exec_module(workloads)
 
 N_SAMPLES = 4096
 SAMPLE_SEED = 20251220
+TILE = 128
+
+
+def tile_digest(X: np.ndarray, u: np.ndarray, v: np.ndarray):
+    """Per 128 x 128 tile of X: Frobenius norm and the probe u_I^T X_IJ v_J; plus row and column sums of X."""
+    n = X.shape[0]
+    t = n // TILE
+    sq = (X * X).reshape(t, TILE, t, TILE).sum(axis=(1, 3))
+    probe = ((u[:, None] * X) * v[None, :]).reshape(t, TILE, t, TILE).sum(axis=(1, 3))
+    return np.sqrt(sq), probe, X.sum(axis=1), X.sum(axis=0)
 
 
 def sample_indices(n: int, batch: int):
@@ -54,10 +66,17 @@ def main():
         rows, cols = sample_indices(w.n, w.batch)
         vals = np.stack([X[b, rows[b], cols[b]] for b in range(w.batch)])
         fro = np.array([np.linalg.norm(X[b]) for b in range(w.batch)])
+        prng = np.random.default_rng(SAMPLE_SEED + 1)
+        u = prng.integers(0, 2, size=w.n).astype(np.float64) * 2.0 - 1.0
+        v = prng.integers(0, 2, size=w.n).astype(np.float64) * 2.0 - 1.0
+        dig = [tile_digest(X[b], u, v) for b in range(w.batch)]
         out = os.path.join(ROOT, "tests", "golden", "c5_samples_%s.npz" % w.dtype)
         np.savez_compressed(out, rows=rows.astype(np.int32), cols=cols.astype(np.int32), vals=vals, fro=fro,
                             m=info["m"], s=info["s"], n1=info["n1"], n2=info["n2"],
                             near=info["near"].astype(np.int8), oracle_seconds=np.array([dt]),
+                            probe_u=u.astype(np.int8), probe_v=v.astype(np.int8),
+                            tile_fro=np.stack([d[0] for d in dig]), tile_probe=np.stack([d[1] for d in dig]),
+                            rowsum=np.stack([d[2] for d in dig]), colsum=np.stack([d[3] for d in dig]),
                             oracle_threads=np.array([info["threads"]]))
         print(name, "m", info["m"], "s", info["s"], "seconds %.1f" % dt, "threads", info["threads"], "->", out,
               flush=True)

@@ -81,13 +81,16 @@ def _run(ex, a, tol, label, gate):
     m, s, _ = ex.expm_select(d, tol, scheme=ex.SCHEME_BASELINE)
     worst, skipped = 0.0, 0
     for b in range(a.shape[0]):
+        ref = X[b]
         if (m[b], s[b]) != (info["m"][b], info["s"][b]):
-            # the term loop stops on ||Y|| <= eps: only a norm within rounding of eps may stop one term apart
+            # the term loop stops on ||Y|| <= eps: only a norm within rounding of eps may stop one term apart (in
+            # fp32 the terms' norms carry the rounding of the fp32 products, about 1e-6 relative)
             assert info["near"][b] or a.dtype == np.float32, (label, b, (m[b], s[b]), (info["m"][b], info["s"][b]))
             assert s[b] == info["s"][b] and abs(int(m[b]) - int(info["m"][b])) <= 1
             skipped += 1
-            continue
-        err = np.linalg.norm(got[b] - X[b]) / np.linalg.norm(X[b])
+            from oracle import oracle_expm_forced   # the degree the device stopped at: that Taylor polynomial, same s
+            ref = oracle_expm_forced(a[b], int(m[b]), int(s[b]), plus16=False)
+        err = np.linalg.norm(got[b] - ref) / np.linalg.norm(ref)
         worst = max(worst, err)
         assert err <= gate, (label, b, err)
     assert skipped <= max(1, a.shape[0] // 50)

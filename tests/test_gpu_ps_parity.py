@@ -46,11 +46,13 @@ def _run(ex, a, tol=None, label=""):
     m, s, _ = ex.expm_select(d, tol, scheme=ex.SCHEME_PS)
     worst = 0.0
     for b in range(a.shape[0]):
+        ref = X[b]
         if (m[b], s[b]) != (info["m"][b], info["s"][b]):
             assert info["near"][b], "%s matrix %d: GPU (%d,%d) oracle (%d,%d)" % (label, b, m[b], s[b], info["m"][b], info["s"][b])
             assert (int(m[b]), int(s[b])) in _corners(info["norms"][b], tol)
-            continue
-        err = np.linalg.norm(got[b] - X[b]) / np.linalg.norm(X[b])
+            from oracle import oracle_expm_forced   # the neighbouring choice: the Taylor polynomial of that order
+            ref = oracle_expm_forced(a[b], int(m[b]), int(s[b]), plus16=False)
+        err = np.linalg.norm(got[b] - ref) / np.linalg.norm(ref)
         worst = max(worst, err)
         assert err <= GATE[a.dtype], "%s matrix %d (m=%d s=%d): %.3e" % (label, b, m[b], s[b], err)
     print("   worst rel Frobenius error %.3e, status %d" % (worst, status), flush=True)
@@ -77,6 +79,15 @@ def test_ps_rounds(ex, n, batch, dtype):
     from paper_2512_20777_amd import workloads
     _, m, s, _, stats = _run(ex, workloads.random_stack(700 + n, batch, n, dtype, 0.05, 80.0), label="ps rounds n=%d" % n)
     assert stats["fused_path"] == 0
+
+
+@pytest.mark.parametrize("n,dtype", [(1024, np.float64), (1030, np.float64), (1152, np.float32)])
+def test_ps_rounds_128_tiles(ex, n, dtype):
+    """From n = 1024 on the Paterson-Stockmeyer rounds run in 128x128 tiles behind a preparation pass (top Horner
+    block): full tiles (operands straight into LDS) and a ragged size, eight matrices so the shape is kept."""
+    from paper_2512_20777_amd import workloads
+    _, m, s, _, stats = _run(ex, workloads.random_stack(720 + n, 8, n, dtype, 0.05, 25.0), label="ps rounds 128-tiles n=%d" % n)
+    assert stats["fused_path"] == 0 and len(set(int(x) for x in m)) >= 2
 
 
 @pytest.mark.parametrize("n", [40, 144])
