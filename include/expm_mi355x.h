@@ -15,9 +15,11 @@
  * Every pointer is labelled HOST or DEVICE below.  Nothing is thrown across
  * this boundary; every entry point returns a status code.
  *
- * Threading: the library keeps one cached device workspace per process, so
- * calls must not overlap in time (neither from several host threads nor on
- * several streams).
+ * Threading and streams: the library keeps one cached device workspace per device.  Entry points are
+ * serialised by a lock, and a call on another stream than the previous call's is ordered on the device
+ * behind everything queued on that stream so far, so calls from several host threads or on several
+ * streams are safe; they run one after another, not side by side.  Exception: calls recorded into a HIP
+ * graph are not ordered against other calls (see expm).
  */
 #ifndef EXPM_MI355X_H
 #define EXPM_MI355X_H
@@ -36,12 +38,13 @@ extern "C" {
 /* status codes: 0 success, > 0 warning (results delivered), < 0 error (nothing delivered) */
 #define EXPM_OK                 0
 #define EXPM_WARN_NONFINITE     1  /* some matrix holds NaN/Inf (or its square overflows): its (m,s) is (-1,-1), its result all NaN */
-#define EXPM_WARN_SCALING_CAP   2  /* some matrix reached the cap s = 20 of Algorithm 4: tolerance not guaranteed for it */
+#define EXPM_WARN_SCALING_CAP   2  /* some matrix asked for more than the cap s = 20 of Algorithm 4 and was clipped to it: tolerance not guaranteed for it */
 #define EXPM_ERR_INVALID_ARG   -1  /* null pointer, n < 0, batch < 0, unknown dtype, out overlapping A, size overflow */
 #define EXPM_ERR_TOLERANCE     -2  /* tol negative, NaN, or 0 < tol < unit roundoff of dtype (Sec. 3.2 requires eps >= u) */
 #define EXPM_ERR_ALLOC         -3  /* device or pinned-host allocation failed */
 #define EXPM_ERR_HIP           -4  /* a HIP call failed; expm_last_hip_error() returns its hipError_t */
 #define EXPM_ERR_UNSUPPORTED   -5  /* the scheme asked for is not available for this matrix size */
+#define EXPM_ERR_WORKSPACE     -6  /* the cached workspace would have to grow inside a stream capture (expm_reserve first) */
 
 #define EXPM_S_CAP 20  /* largest scaling Algorithm 4 returns */
 
@@ -79,17 +82,21 @@ int expm_select(const void *A, int n, int batch, int dtype, double tol,
  *
  * Ordering / blocking: for matrices that fit a compute unit's LDS (n <= 128 in fp32, n <= 96 in fp64) the
  * whole call is one fused kernel and returns without waiting for the device.  For
- * larger n the number of product rounds depends on the data, so the call waits on
+ * larger n the number of product rounds depends on the data.  By default the call waits on
  * `stream` until the selection stage has finished (one 256-byte read-back), enqueues
- * the remaining rounds and returns without waiting for them.
+ * exactly the rounds needed and returns without waiting for them.  With EXPM_PLAN=device in the environment, and
+ * always while `stream` is being captured, the rounds are planned on the device instead: the call enqueues the
+ * selection and every round a matrix can need (3 + EXPM_S_CAP), workgroups of rounds a matrix does not need leave
+ * at once, and nothing waits.
  *
- * Stream capture: a call on the fused path only enqueues kernels (no read-back, no memset) and may be
- * recorded into a HIP graph, provided the workspace was reserved before the capture (expm_reserve, or an
- * earlier call of the same size) -- the recorded kernels hold its address, so a later call that makes the
- * workspace grow invalidates such graphs.  A call on the larger-n path waits on the stream and cannot be captured.
+ * Stream capture: while `stream` is being captured a call only enqueues kernels on that stream (no read-back, no
+ * memset, no other stream) and may be recorded into a HIP graph for any n, provided the workspace was reserved
+ * before the capture (expm_reserve, or an earlier call of the same size; otherwise EXPM_ERR_WORKSPACE) -- the
+ * recorded kernels hold its address, so a later call that makes the workspace grow invalidates such graphs, and
+ * replays must not overlap other calls of the library.
  *
  * Returns 0 or an error (< 0).  Warnings are returned when they are known at return
- * time (the larger-n path); after any call expm_get_stats() reports them.
+ * time (the larger-n path planned on the host); after any call expm_get_stats() reports them.
  * Ownership: caller owns A and out and must keep them alive until `stream` has
  * finished the call; the library owns its workspace (see expm_workspace_bytes).
  */
@@ -124,7 +131,7 @@ int expm_scheme(const void *A, int n, int batch, int dtype, double tol, int sche
 /*
  * Same again with the norm of the selection as an argument.  The printed algorithms use the 1-norm
  * (EXPM_NORM_ONE: largest column abs-sum, what every call above uses); the paper's PyTorch runs use the
- * infinity-norm "for consistency with the baseline" (Sec. 4.2): EXPM_NORM_INF takes the largest row abs-sum
+ * infinity-norm, as their baseline does (Sec. 4.2): EXPM_NORM_INF takes the largest row abs-sum
  * of W and of its powers instead.  Only the selection changes; with EXPM_NORM_INF the result equals the
  * transpose of what EXPM_NORM_ONE gives for the transposed batch.
  */
@@ -184,12 +191,14 @@ struct expm_stats {
     int32_t n;             /* matrix order                                        */
     int32_t dtype;
     int32_t rounds;        /* product rounds launched after the W^2 round (0 on the fused path) */
-    int32_t warning;       /* 0, EXPM_WARN_NONFINITE, EXPM_WARN_SCALING_CAP (larger wins) */
+    int32_t warning;       /* 0, EXPM_WARN_NONFINITE or EXPM_WARN_SCALING_CAP (non-finite wins; warning_bits has both) */
     int32_t fused_path;    /* 1 if the single-kernel on-chip path ran             */
     int32_t scheme;        /* EXPM_SCHEME_* of the call                           */
     int64_t hist_m[17];    /* matrices with order m, indexed by m = 0..16 (baseline degrees above 16 in the last bin) */
     int64_t hist_s[21];    /* matrices with s = 0..20                             */
     int64_t nonfinite;     /* matrices flagged (-1,-1)                            */
+    int32_t warning_bits;  /* bit 0: some matrix non-finite; bit 1: some matrix asked for more than the cap s = 20 */
+    int32_t reserved;
 };
 int expm_get_stats(struct expm_stats *st /* HOST */);
 

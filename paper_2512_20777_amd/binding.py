@@ -36,7 +36,7 @@ class _Stats(ctypes.Structure):
         ("matrices", ctypes.c_int64), ("products", ctypes.c_int64), ("n", ctypes.c_int32), ("dtype", ctypes.c_int32),
         ("rounds", ctypes.c_int32), ("warning", ctypes.c_int32), ("fused_path", ctypes.c_int32),
         ("scheme", ctypes.c_int32), ("hist_m", ctypes.c_int64 * 17), ("hist_s", ctypes.c_int64 * 21),
-        ("nonfinite", ctypes.c_int64),
+        ("nonfinite", ctypes.c_int64), ("warning_bits", ctypes.c_int32), ("reserved", ctypes.c_int32),
     ]
 
 
@@ -238,7 +238,8 @@ def expm_get_stats() -> dict:
     st = _Stats()
     _check(load_library().expm_get_stats(ctypes.byref(st)))
     return dict(matrices=st.matrices, products=st.products, n=st.n, dtype=st.dtype, rounds=st.rounds,
-                warning=st.warning, fused_path=st.fused_path, scheme=st.scheme, nonfinite=st.nonfinite,
+                warning=st.warning, warning_bits=st.warning_bits, fused_path=st.fused_path, scheme=st.scheme,
+                nonfinite=st.nonfinite,
                 hist_m={m: int(c) for m, c in enumerate(st.hist_m)}, hist_s=list(st.hist_s))
 
 

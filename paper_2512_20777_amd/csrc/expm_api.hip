@@ -7,26 +7,38 @@
 #include <cmath>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <vector>
 
 namespace {
 
 using namespace expmk;
 
-struct Workspace {
-    void *dev = nullptr;      // one device block
+// Everything the library keeps between calls is kept per device: the cached workspace block, the pinned mirror of
+// the plan summary, and the side streams and events of the round-based path.
+constexpr int kMaxDevices = 16;
+constexpr int kChains = 2;                        // chains of rounds that run side by side below n = 1024
+
+struct DeviceState {
+    void *dev = nullptr;      // one device block (workspace), grown on demand
     size_t bytes = 0;
     int *host_summary = nullptr;  // pinned, 64 ints
-    MatInfo *host_info = nullptr; // pageable mirror for stats / select
-    size_t host_info_cap = 0;
+    hipEvent_t summary_ready = nullptr;
+    hipStream_t side_stream = nullptr;          // norm of W beside the W^2 round (default priority)
+    hipEvent_t fork = nullptr, join = nullptr;
+    hipStream_t chain_stream[kChains] = {};     // [0] unused (the caller's stream), [1] = side_stream, rest their own
+    hipEvent_t chain_join[kChains] = {};
+    hipEvent_t order_event = nullptr;           // orders a call behind the previous one when the stream changes
 };
 
 struct LastCall {
     bool valid = false;
     int n = 0, batch = 0, dtype = 0;
-    int rounds = 0;
+    int rounds = 0;           // -1: the rounds were planned on the device; the statistics derive them from the records
     int fused = 0;
     int scheme = 0;
+    int device = 0;
+    bool stream_usable = false;  // false after a call made under stream capture (the stream cannot be waited on)
     hipStream_t stream = nullptr;
     MatInfo *info_dev = nullptr;
     int *summary_dev = nullptr;
@@ -38,18 +50,15 @@ struct ProfEvent {
     double flops, bytes;
 };
 
-Workspace g_ws;
+DeviceState g_dev[kMaxDevices];
+std::vector<MatInfo> g_host_info;   // pageable mirror of the per-matrix records for stats / select
+std::mutex g_mutex;                 // entry points that touch the state above run one at a time
 LastCall g_last;
 int g_last_hip_error = 0;
 bool g_profile = false;
+bool g_brackets = false;            // per call: g_profile, except in calls that must not create events
 std::vector<ProfEvent> g_events;
 std::vector<hipEvent_t> g_event_pool;
-hipEvent_t g_summary_ready = nullptr;
-hipStream_t g_side_stream = nullptr;          // norm of W beside the W^2 round (default priority)
-hipEvent_t g_fork = nullptr, g_join = nullptr;
-constexpr int kChains = 2;                        // chains of rounds that run side by side below n = 1024
-hipStream_t g_chain_stream[kChains] = {};        // [0] unused (the caller's stream), [1] = g_side_stream, rest their own
-hipEvent_t g_chain_join[kChains] = {};
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
@@ -90,7 +99,7 @@ Layout make_layout(int n, int batch, int dtype)
     L.colpart_w = off;
     L.mats = off;
     if (!small_path_supported(n, dtype)) {
-        // column-sum partials: 32-row chunks for W, one per tile row (>= 64 rows) for the powers
+        // column-sum partials: 32-row chunks for W, one per tile row (>= 32 rows) for the powers
         off = align_up(off + (size_t)batch * general_colchunks(n) * n * sizeof(double), 256);
         L.colpart_w = off;
         off = align_up(off + (size_t)batch * general_colchunks(n) * n * sizeof(double), 256);
@@ -102,33 +111,64 @@ Layout make_layout(int n, int batch, int dtype)
     return L;
 }
 
-int ensure_workspace(size_t bytes, int batch)
+// State of the device that is current on this thread.
+int current_device(DeviceState **ds, int *index = nullptr)
 {
-    if (!g_ws.host_summary) {
-        hipError_t e = hipHostMalloc(reinterpret_cast<void **>(&g_ws.host_summary), 64 * sizeof(int), hipHostMallocDefault);
-        if (e != hipSuccess) { g_last_hip_error = (int)e; (void)hipGetLastError(); return EXPM_ERR_ALLOC; }
-    }
-    if ((size_t)batch > g_ws.host_info_cap) {
-        MatInfo *p = static_cast<MatInfo *>(realloc(g_ws.host_info, (size_t)batch * sizeof(MatInfo)));
-        if (!p) return EXPM_ERR_ALLOC;
-        g_ws.host_info = p;
-        g_ws.host_info_cap = (size_t)batch;
-    }
-    if (bytes <= g_ws.bytes) return EXPM_OK;
-    if (g_ws.dev) {
+    int dev = 0;
+    EXPM_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return EXPM_ERR_INVALID_ARG;
+    *ds = &g_dev[dev];
+    if (index) *index = dev;
+    return EXPM_OK;
+}
+
+int ensure_workspace(DeviceState *ds, size_t bytes)
+{
+    if (bytes <= ds->bytes) return EXPM_OK;
+    if (ds->dev) {
         // earlier calls may still be using the old block
         hipError_t e = hipDeviceSynchronize();
         if (e != hipSuccess) return hip_fail(e);
-        (void)hipFree(g_ws.dev);
-        g_ws.dev = nullptr;
-        g_ws.bytes = 0;
+        (void)hipFree(ds->dev);
+        ds->dev = nullptr;
+        ds->bytes = 0;
         g_last.valid = false;
     }
     void *p = nullptr;
     hipError_t e = hipMalloc(&p, bytes);
     if (e != hipSuccess) { g_last_hip_error = (int)e; (void)hipGetLastError(); return EXPM_ERR_ALLOC; }
-    g_ws.dev = p;
-    g_ws.bytes = bytes;
+    ds->dev = p;
+    ds->bytes = bytes;
+    return EXPM_OK;
+}
+
+int ensure_host_summary(DeviceState *ds)
+{
+    if (ds->host_summary) return EXPM_OK;
+    hipError_t e = hipHostMalloc(reinterpret_cast<void **>(&ds->host_summary), 64 * sizeof(int), hipHostMallocDefault);
+    if (e != hipSuccess) { g_last_hip_error = (int)e; (void)hipGetLastError(); return EXPM_ERR_ALLOC; }
+    return EXPM_OK;
+}
+
+bool stream_is_capturing(hipStream_t stream)
+{
+    hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(stream, &cs) != hipSuccess) { (void)hipGetLastError(); return false; }
+    return cs == hipStreamCaptureStatusActive;
+}
+
+// All calls on one device share that device's workspace.  A call on another stream than the previous call's is
+// therefore ordered behind everything queued on that stream so far (an event recorded there now, waited for here):
+// calls on several streams then run one after another instead of overwriting each other's intermediates.
+int order_behind_last_call(DeviceState *ds, int dev, hipStream_t stream)
+{
+    if (!g_last.valid || !g_last.stream_usable || g_last.device != dev || g_last.stream == stream) return EXPM_OK;
+    if (!ds->order_event) EXPM_TRY(hipEventCreateWithFlags(&ds->order_event, hipEventDisableTiming));
+    if (hipEventRecord(ds->order_event, g_last.stream) != hipSuccess) {
+        (void)hipGetLastError();   // the caller has destroyed that stream: its work was finished or abandoned with it
+        return EXPM_OK;
+    }
+    EXPM_TRY(hipStreamWaitEvent(stream, ds->order_event, 0));
     return EXPM_OK;
 }
 
@@ -141,7 +181,7 @@ int check_args(const void *A, int n, int batch, int dtype, double &tol)
     if ((double)batch * (double)n * (double)n > 9.0e15) return EXPM_ERR_INVALID_ARG;
     if (!small_path_supported(n, dtype)) {
         // round-based path: the batch is a grid dimension and (matrices x tiles) must fit an int
-        const double tiles = (double)((n + 63) / 64);
+        const double tiles = (double)((n + 31) / 32);
         if (batch > 65535 || (double)batch * tiles * tiles > 2.0e9) return EXPM_ERR_INVALID_ARG;
     }
     const double u = dtype == EXPM_DTYPE_F64 ? ldexp(1.0, -53) : ldexp(1.0, -24);
@@ -168,7 +208,7 @@ struct Bracket {
     hipStream_t stream;
     ProfEvent ev{};
     bool on;
-    Bracket(hipStream_t s, int kclass, double flops, double bytes) : stream(s), on(g_profile)
+    Bracket(hipStream_t s, int kclass, double flops, double bytes) : stream(s), on(g_brackets)
     {
         if (!on) return;
         ev.start = get_event();
@@ -187,10 +227,12 @@ struct Bracket {
     }
 };
 
+// Warnings are independent bits; the status code can carry one: a non-finite matrix (results missing) outranks a
+// scaling that hit the cap (results delivered, tolerance not guaranteed).  expm_stats.warning_bits carries both.
 int warning_from_flags(int flags)
 {
-    if (flags & 2) return EXPM_WARN_SCALING_CAP;
     if (flags & 1) return EXPM_WARN_NONFINITE;
+    if (flags & 2) return EXPM_WARN_SCALING_CAP;
     return EXPM_OK;
 }
 
@@ -199,12 +241,11 @@ struct Bound {
     Layout L;
 };
 
-Bound bind(const void *A, void *out, int n, int batch, int dtype, int norm_kind)
+Bound bind(unsigned char *base, const void *A, void *out, int n, int batch, int dtype, int norm_kind)
 {
     Bound B;
     B.gb.norm_inf = norm_kind == EXPM_NORM_INF ? 1 : 0;
     B.L = make_layout(n, batch, dtype);
-    unsigned char *base = static_cast<unsigned char *>(g_ws.dev);
     B.gb.summary = reinterpret_cast<int *>(base + B.L.summary);
     B.gb.info = reinterpret_cast<MatInfo *>(base + B.L.info);
     B.gb.order = reinterpret_cast<int *>(base + B.L.order);
@@ -221,8 +262,10 @@ Bound bind(const void *A, void *out, int n, int batch, int dtype, int norm_kind)
     return B;
 }
 
-// Selection stage of the round-based path: norms, W2, (m,s), plan; leaves the summary in pinned memory.
-int run_selection_general(const Bound &B, int n, int batch, int dtype, double tol, int scheme, hipStream_t stream)
+// Selection stage of the round-based path: norms, W2, (m,s), plan.  With `readback` the plan summary also travels
+// to pinned host memory (the caller waits on summary_ready); without it the stage only enqueues kernels on `stream`.
+int run_selection_general(DeviceState *ds, const Bound &B, int n, int batch, int dtype, double tol, int scheme,
+                          hipStream_t stream, bool readback)
 {
     const double w = dtype == EXPM_DTYPE_F64 ? 8.0 : 4.0;
     const double nn = (double)n * n;
@@ -231,23 +274,23 @@ int run_selection_general(const Bound &B, int n, int batch, int dtype, double to
     // per-class timers on, everything stays on the caller's stream so that each class is timed by itself.
     // (only for matrices below 1024: beyond that the pass is a fraction of a percent of the call, and its reads
     // beside the start of a long product round cost that round more than they save)
-    const bool side = !g_profile && n < 1024;
+    const bool side = readback && !g_brackets && n < 1024;
     if (side) {
-        if (!g_side_stream) {
-            EXPM_TRY(hipStreamCreateWithFlags(&g_side_stream, hipStreamNonBlocking));
-            EXPM_TRY(hipEventCreateWithFlags(&g_fork, hipEventDisableTiming));
-            EXPM_TRY(hipEventCreateWithFlags(&g_join, hipEventDisableTiming));
+        if (!ds->side_stream) {
+            EXPM_TRY(hipStreamCreateWithFlags(&ds->side_stream, hipStreamNonBlocking));
+            EXPM_TRY(hipEventCreateWithFlags(&ds->fork, hipEventDisableTiming));
+            EXPM_TRY(hipEventCreateWithFlags(&ds->join, hipEventDisableTiming));
         }
-        EXPM_TRY(hipEventRecord(g_fork, stream));
-        EXPM_TRY(hipStreamWaitEvent(g_side_stream, g_fork, 0));
+        EXPM_TRY(hipEventRecord(ds->fork, stream));
+        EXPM_TRY(hipStreamWaitEvent(ds->side_stream, ds->fork, 0));
     }
     {
-        hipStream_t ns = side ? g_side_stream : stream;
+        hipStream_t ns = side ? ds->side_stream : stream;
         Bracket br(stream, EXPM_KCLASS_NORM, 0.0, batch * nn * w);
         EXPM_TRY(launch_colabs(B.gb, n, batch, dtype, ns));
         EXPM_TRY(launch_colmax(B.gb, n, batch, 1, B.gb.norm_inf ? 1 : general_colchunks(n), ns));
     }
-    if (side) EXPM_TRY(hipEventRecord(g_join, g_side_stream));
+    if (side) EXPM_TRY(hipEventRecord(ds->join, ds->side_stream));
     const int wt0 = choose_tile_shape(n, batch);
     {
         Bracket br(stream, EXPM_KCLASS_GEMM, 2.0 * nn * n * batch, 2.0 * batch * nn * w);
@@ -268,27 +311,209 @@ int run_selection_general(const Bound &B, int n, int batch, int dtype, double to
             EXPM_TRY(launch_colmax(B.gb, n, batch, which, (n + 32 * wt0 - 1) / (32 * wt0), stream));
         }
     }
-    if (side) EXPM_TRY(hipStreamWaitEvent(stream, g_join, 0));
+    if (side) EXPM_TRY(hipStreamWaitEvent(stream, ds->join, 0));
     {
         Bracket br(stream, EXPM_KCLASS_SELECT, 0.0, 0.0);
         EXPM_TRY(launch_select_plan(B.gb, n, batch, tol, scheme, stream));
     }
-    // the plan summary travels to pinned host memory; g_summary_ready marks the copy, so that the
-    // caller can queue more work behind it before waiting
-    EXPM_TRY(hipMemcpyAsync(g_ws.host_summary, B.gb.summary, 64 * sizeof(int), hipMemcpyDeviceToHost, stream));
-    if (!g_summary_ready) EXPM_TRY(hipEventCreateWithFlags(&g_summary_ready, hipEventDisableTiming));
-    EXPM_TRY(hipEventRecord(g_summary_ready, stream));
+    if (readback) {
+        // the plan summary travels to pinned host memory; summary_ready marks the copy, so that the
+        // caller can queue more work behind it before waiting
+        EXPM_TRY(hipMemcpyAsync(ds->host_summary, B.gb.summary, 64 * sizeof(int), hipMemcpyDeviceToHost, stream));
+        if (!ds->summary_ready) EXPM_TRY(hipEventCreateWithFlags(&ds->summary_ready, hipEventDisableTiming));
+        EXPM_TRY(hipEventRecord(ds->summary_ready, stream));
+    }
     return EXPM_OK;
 }
 
-void remember(int n, int batch, int dtype, int rounds, int fused, int scheme, hipStream_t stream, const Bound &B)
+void remember(int n, int batch, int dtype, int rounds, int fused, int scheme, int dev, hipStream_t stream, bool usable,
+              MatInfo *info, int *summary)
 {
     g_last.valid = true;
     g_last.scheme = scheme;
     g_last.n = n; g_last.batch = batch; g_last.dtype = dtype;
     g_last.rounds = rounds; g_last.fused = fused; g_last.stream = stream;
-    g_last.info_dev = B.gb.info;
-    g_last.summary_dev = B.gb.summary;
+    g_last.device = dev;
+    g_last.stream_usable = usable;
+    g_last.info_dev = info;
+    g_last.summary_dev = summary;
+}
+
+// Profiling aids read once from the environment: EXPM_CHAINS=1 keeps one chain of rounds (a kernel trace then
+// shows launches that do not overlap); EXPM_PLAN=device|host forces where the rounds are planned.
+int env_chain_limit()
+{
+    static const int v = [] {
+        const char *e = getenv("EXPM_CHAINS");
+        const int x = e ? atoi(e) : 0;
+        return x >= 1 && x <= kChains ? x : kChains;
+    }();
+    return v;
+}
+int env_plan()   // 0: library's choice, 1: on the device, 2: on the host
+{
+    static const int v = [] {
+        const char *e = getenv("EXPM_PLAN");
+        if (!e) return 0;
+        return strcmp(e, "device") == 0 ? 1 : (strcmp(e, "host") == 0 ? 2 : 0);
+    }();
+    return v;
+}
+
+// Where the rounds of a call on the round-based path are planned when the caller leaves the choice to the library.
+// Planning on the device never blocks the host but launches every possible round (workgroups of rounds a matrix
+// does not need leave at once: about 2.6 us per such launch); planning on the host waits once for 256 bytes and
+// launches exactly the rounds needed, each with the tile shape that suits the matrices still active.
+bool plan_on_device_by_default(int n, int batch)
+{
+    (void)n; (void)batch;
+    return false;
+}
+
+// The rounds of one call on the round-based path.  plan_on_device: only kernels are enqueued, on `stream` alone.
+int run_rounds(DeviceState *ds, const Bound &B, int n, int batch, int dtype, double tol, int scheme, hipStream_t stream,
+               bool plan_on_device, int *rounds_out, int *warning_out)
+{
+    const double w = dtype == EXPM_DTYPE_F64 ? 8.0 : 4.0;
+    const double nn = (double)n * n;
+    *warning_out = EXPM_OK;
+    if (!plan_on_device) {
+        int rc = ensure_host_summary(ds);
+        if (rc != EXPM_OK) return rc;
+    }
+    int rc = run_selection_general(ds, B, n, batch, dtype, tol, scheme, stream, !plan_on_device);
+    if (rc != EXPM_OK) return rc;
+    // Work that does not need the host's view of the plan is queued before the wait, so the device
+    // stays busy while the summary is read: operand preparation, and the first chain round over the
+    // whole batch (workgroups of matrices that need no product leave at once).
+    if (first_round_is_self_contained(n, scheme)) {
+        // no preparation pass: round 1 combines W^2 and W while it stages its tiles and finishes orders <= 2 itself
+        Bracket br(stream, EXPM_KCLASS_GEMM, 0.0, 0.0);  // its work is filled in once the plan is known
+        EXPM_TRY(launch_first_round(B.gb, n, batch, dtype, stream));
+    } else {
+        {
+            Bracket br(stream, EXPM_KCLASS_SELECT, 0.0, 0.0);
+            EXPM_TRY(launch_prepare(B.gb, n, batch, dtype, scheme, stream));
+        }
+        Bracket br(stream, EXPM_KCLASS_GEMM, 0.0, 0.0);  // its work is filled in once the plan is known
+        EXPM_TRY(launch_chain_round(B.gb, n, batch, 1, dtype, choose_tile_shape(n, batch), scheme, stream));
+    }
+    if (plan_on_device) {
+        // Every round a matrix can need (3 + 20 for both schemes), each over the whole sorted list: a workgroup looks
+        // up its matrix's chain length and leaves if the round is beyond it.
+        const int wt = choose_tile_shape(n, batch);
+        for (int r = 2; r <= kMaxRounds; ++r)
+            EXPM_TRY(launch_chain_round(B.gb, n, batch, r, dtype, wt, scheme, stream, 0, 1, true));
+        *rounds_out = -1;
+        return EXPM_OK;
+    }
+    const size_t round1_event = g_events.size();
+    EXPM_TRY(hipEventSynchronize(ds->summary_ready));
+    const int longest = ds->host_summary[0];
+    const int flags = ds->host_summary[1];
+    if (g_brackets && round1_event > 0) {
+        const int active1 = longest >= 1 ? ds->host_summary[3] : 0;
+        g_events[round1_event - 1].flops = 2.0 * nn * n * active1;
+        g_events[round1_event - 1].bytes = 2.0 * active1 * nn * w;
+    }
+    // Rounds 2.. : a matrix's round r needs only its own round r-1.  Below n = 1024 the sorted matrices are dealt
+    // alternately to kChains streams, each with its own chain of rounds: while one chain's launch runs out of
+    // workgroups towards its end, the other's fills the compute units (a single chain leaves them idle there,
+    // 8 % of the call for 32 matrices of 512 x 512).  With the per-class timers on, one chain on the caller's
+    // stream, so that launches do not overlap and each is timed by itself.
+    int chains = 1;
+    if (!g_brackets && n < 1024 && longest >= 2 && ds->side_stream != nullptr) chains = std::min(env_chain_limit(), ds->host_summary[4]);
+    if (chains > 1) {
+        EXPM_TRY(hipEventRecord(ds->fork, stream));
+        for (int c = 1; c < chains; ++c) {
+            if (!ds->chain_stream[c]) {
+                if (c == 1) ds->chain_stream[c] = ds->side_stream;
+                else EXPM_TRY(hipStreamCreateWithFlags(&ds->chain_stream[c], hipStreamNonBlocking));
+                EXPM_TRY(hipEventCreateWithFlags(&ds->chain_join[c], hipEventDisableTiming));
+            }
+            EXPM_TRY(hipStreamWaitEvent(ds->chain_stream[c], ds->fork, 0));
+        }
+    }
+    for (int r = 2; r <= longest && r <= kMaxRounds; ++r) {
+        const int active = ds->host_summary[2 + r];
+        if (active <= 0) break;
+        if (chains > 1) {
+            for (int c = 0; c < chains; ++c) {
+                const int mine = (active - c + chains - 1) / chains;  // sorted matrices c, c + chains, ... below active
+                if (mine <= 0) break;
+                EXPM_TRY(launch_chain_round(B.gb, n, mine, r, dtype, choose_tile_shape(n, mine), scheme,
+                                            c == 0 ? stream : ds->chain_stream[c], c, chains));
+            }
+            continue;
+        }
+        Bracket br(stream, EXPM_KCLASS_GEMM, 2.0 * nn * n * active, 2.0 * active * nn * w);
+        EXPM_TRY(launch_chain_round(B.gb, n, active, r, dtype, choose_tile_shape(n, active), scheme, stream));
+    }
+    for (int c = 1; c < chains; ++c) {
+        EXPM_TRY(hipEventRecord(ds->chain_join[c], ds->chain_stream[c]));
+        EXPM_TRY(hipStreamWaitEvent(stream, ds->chain_join[c], 0));
+    }
+    *rounds_out = longest;
+    *warning_out = warning_from_flags(flags);
+    return EXPM_OK;
+}
+
+int expm_impl(const void *A, int n, int batch, int dtype, double tol, int scheme, int norm_kind, void *out, void *stream_v)
+{
+    if (scheme != EXPM_SCHEME_SASTRE && scheme != EXPM_SCHEME_PS && scheme != EXPM_SCHEME_BASELINE)
+        return EXPM_ERR_INVALID_ARG;
+    if (norm_kind != EXPM_NORM_ONE && norm_kind != EXPM_NORM_INF) return EXPM_ERR_INVALID_ARG;
+    int rc = check_args(A, n, batch, dtype, tol);
+    if (rc != EXPM_OK) return rc;
+    if (n == 0 || batch == 0) return EXPM_OK;
+    if (out == nullptr) return EXPM_ERR_INVALID_ARG;
+    if (scheme == EXPM_SCHEME_BASELINE && !small_path_supported(n, dtype)) return EXPM_ERR_UNSUPPORTED;
+    {
+        const size_t bytes = (size_t)batch * n * n * (dtype == EXPM_DTYPE_F64 ? 8 : 4);
+        const uintptr_t a0 = (uintptr_t)A, o0 = (uintptr_t)out;
+        if (a0 < o0 + bytes && o0 < a0 + bytes) return EXPM_ERR_INVALID_ARG;  // overlap
+        if ((a0 | o0) % (dtype == EXPM_DTYPE_F64 ? 8 : 4)) return EXPM_ERR_INVALID_ARG;
+    }
+    hipStream_t stream = static_cast<hipStream_t>(stream_v);
+    const Layout L = make_layout(n, batch, dtype);
+    std::lock_guard<std::mutex> lock(g_mutex);
+    DeviceState *ds = nullptr;
+    int dev = 0;
+    rc = current_device(&ds, &dev);
+    if (rc != EXPM_OK) return rc;
+    const bool capturing = stream_is_capturing(stream);
+    unsigned char *base = nullptr;
+    {
+        if (capturing && L.total > ds->bytes) return EXPM_ERR_WORKSPACE;   // a capture cannot allocate: expm_reserve first
+        rc = ensure_workspace(ds, L.total);
+        if (rc != EXPM_OK) return rc;
+        base = static_cast<unsigned char *>(ds->dev);
+        if (!capturing) {
+            rc = order_behind_last_call(ds, dev, stream);
+            if (rc != EXPM_OK) return rc;
+        }
+    }
+    g_brackets = g_profile && !capturing;
+    const Bound B = bind(base, A, out, n, batch, dtype, norm_kind);
+    const double w = dtype == EXPM_DTYPE_F64 ? 8.0 : 4.0;
+    const double nn = (double)n * n;
+
+    if (small_path_supported(n, dtype)) {
+        // one kernel, nothing read back: warnings of this path surface through expm_get_stats()
+        {
+            Bracket br(stream, EXPM_KCLASS_FUSED, 0.0, 2.0 * batch * nn * w);
+            EXPM_TRY(launch_small(A, out, n, batch, dtype, tol, 0, scheme, B.gb.norm_inf, B.gb.info, stream));
+        }
+        remember(n, batch, dtype, 0, 1, scheme, dev, stream, !capturing, B.gb.info, B.gb.summary);
+        return EXPM_OK;
+    }
+    bool on_device = capturing;
+    if (!on_device) on_device = env_plan() == 1 || (env_plan() == 0 && plan_on_device_by_default(n, batch));
+    int rounds = 0, warning = EXPM_OK;
+    rc = run_rounds(ds, B, n, batch, dtype, tol, scheme, stream, on_device, &rounds, &warning);
+    if (rc != EXPM_OK) return rc;
+    remember(n, batch, dtype, rounds, 0, scheme, dev, stream, !capturing, B.gb.info, B.gb.summary);
+    return warning;
 }
 
 }  // namespace
@@ -311,7 +536,11 @@ int expm_reserve(int n, int batch, int dtype)
     int rc = check_args(&dummy, n, batch, dtype, tol);
     if (rc != EXPM_OK) return rc;
     if (n == 0 || batch == 0) return EXPM_OK;
-    return ensure_workspace(make_layout(n, batch, dtype).total, batch);
+    std::lock_guard<std::mutex> lock(g_mutex);
+    DeviceState *ds = nullptr;
+    rc = current_device(&ds);
+    if (rc != EXPM_OK) return rc;
+    return ensure_workspace(ds, make_layout(n, batch, dtype).total);
 }
 
 int expm_select(const void *A, int n, int batch, int dtype, double tol, int32_t *m_out, int32_t *s_out)
@@ -339,144 +568,51 @@ int expm_select_ex(const void *A, int n, int batch, int dtype, double tol, int s
         for (int b = 0; b < batch; ++b) { m_out[b] = 0; s_out[b] = 0; }
         return EXPM_OK;
     }
-    rc = ensure_workspace(make_layout(n, batch, dtype).total, batch);
+    std::lock_guard<std::mutex> lock(g_mutex);
+    DeviceState *ds = nullptr;
+    int dev = 0;
+    rc = current_device(&ds, &dev);
+    if (rc != EXPM_OK) return rc;
+    rc = ensure_workspace(ds, make_layout(n, batch, dtype).total);
     if (rc != EXPM_OK) return rc;
     hipStream_t stream = nullptr;
-    const Bound B = bind(A, nullptr, n, batch, dtype, norm_kind);
+    rc = order_behind_last_call(ds, dev, stream);
+    if (rc != EXPM_OK) return rc;
+    g_brackets = false;
+    const Bound B = bind(static_cast<unsigned char *>(ds->dev), A, nullptr, n, batch, dtype, norm_kind);
     int flags = 0;
     if (small_path_supported(n, dtype)) {
         EXPM_TRY(launch_small(A, nullptr, n, batch, dtype, tol, 1, scheme, B.gb.norm_inf, B.gb.info, stream));
-        remember(n, batch, dtype, 0, 1, scheme, stream, B);
+        remember(n, batch, dtype, 0, 1, scheme, dev, stream, true, B.gb.info, B.gb.summary);
     } else {
-        rc = run_selection_general(B, n, batch, dtype, tol, scheme, stream);
+        rc = run_selection_general(ds, B, n, batch, dtype, tol, scheme, stream, false);
         if (rc != EXPM_OK) return rc;
-        EXPM_TRY(hipEventSynchronize(g_summary_ready));
-        remember(n, batch, dtype, 0, 0, scheme, stream, B);
+        remember(n, batch, dtype, 0, 0, scheme, dev, stream, true, B.gb.info, B.gb.summary);
     }
-    EXPM_TRY(hipMemcpyAsync(g_ws.host_info, B.gb.info, (size_t)batch * sizeof(MatInfo), hipMemcpyDeviceToHost, stream));
+    g_host_info.resize((size_t)batch);
+    EXPM_TRY(hipMemcpyAsync(g_host_info.data(), B.gb.info, (size_t)batch * sizeof(MatInfo), hipMemcpyDeviceToHost, stream));
     EXPM_TRY(hipStreamSynchronize(stream));
     for (int b = 0; b < batch; ++b) {
-        m_out[b] = g_ws.host_info[b].m;
-        s_out[b] = g_ws.host_info[b].s;
-        flags |= g_ws.host_info[b].flags;
+        m_out[b] = g_host_info[b].m;
+        s_out[b] = g_host_info[b].s;
+        flags |= g_host_info[b].flags;
     }
     return warning_from_flags(flags);
 }
 
 int expm(const void *A, int n, int batch, int dtype, double tol, void *out, void *stream_v)
 {
-    return expm_scheme(A, n, batch, dtype, tol, EXPM_SCHEME_SASTRE, out, stream_v);
+    return expm_impl(A, n, batch, dtype, tol, EXPM_SCHEME_SASTRE, EXPM_NORM_ONE, out, stream_v);
 }
 
 int expm_scheme(const void *A, int n, int batch, int dtype, double tol, int scheme, void *out, void *stream_v)
 {
-    return expm_ex(A, n, batch, dtype, tol, scheme, EXPM_NORM_ONE, out, stream_v);
+    return expm_impl(A, n, batch, dtype, tol, scheme, EXPM_NORM_ONE, out, stream_v);
 }
 
 int expm_ex(const void *A, int n, int batch, int dtype, double tol, int scheme, int norm_kind, void *out, void *stream_v)
 {
-    if (scheme != EXPM_SCHEME_SASTRE && scheme != EXPM_SCHEME_PS && scheme != EXPM_SCHEME_BASELINE)
-        return EXPM_ERR_INVALID_ARG;
-    if (norm_kind != EXPM_NORM_ONE && norm_kind != EXPM_NORM_INF) return EXPM_ERR_INVALID_ARG;
-    int rc = check_args(A, n, batch, dtype, tol);
-    if (rc != EXPM_OK) return rc;
-    if (n == 0 || batch == 0) return EXPM_OK;
-    if (out == nullptr) return EXPM_ERR_INVALID_ARG;
-    if (scheme == EXPM_SCHEME_BASELINE && !small_path_supported(n, dtype)) return EXPM_ERR_UNSUPPORTED;
-    {
-        const size_t bytes = (size_t)batch * n * n * (dtype == EXPM_DTYPE_F64 ? 8 : 4);
-        const uintptr_t a0 = (uintptr_t)A, o0 = (uintptr_t)out;
-        if (a0 < o0 + bytes && o0 < a0 + bytes) return EXPM_ERR_INVALID_ARG;  // overlap
-        if ((a0 | o0) % (dtype == EXPM_DTYPE_F64 ? 8 : 4)) return EXPM_ERR_INVALID_ARG;
-    }
-    hipStream_t stream = static_cast<hipStream_t>(stream_v);
-    rc = ensure_workspace(make_layout(n, batch, dtype).total, batch);
-    if (rc != EXPM_OK) return rc;
-    const Bound B = bind(A, out, n, batch, dtype, norm_kind);
-    const double w = dtype == EXPM_DTYPE_F64 ? 8.0 : 4.0;
-    const double nn = (double)n * n;
-
-    if (small_path_supported(n, dtype)) {
-        // one kernel, nothing read back: warnings of this path surface through expm_get_stats()
-        {
-            Bracket br(stream, EXPM_KCLASS_FUSED, 0.0, 2.0 * batch * nn * w);
-            EXPM_TRY(launch_small(A, out, n, batch, dtype, tol, 0, scheme, B.gb.norm_inf, B.gb.info, stream));
-        }
-        remember(n, batch, dtype, 0, 1, scheme, stream, B);
-        return EXPM_OK;
-    }
-
-    rc = run_selection_general(B, n, batch, dtype, tol, scheme, stream);
-    if (rc != EXPM_OK) return rc;
-    // Work that does not need the host's view of the plan is queued before the wait, so the device
-    // stays busy while the summary is read: operand preparation, and the first chain round over the
-    // whole batch (workgroups of matrices that need no product leave at once).
-    if (first_round_is_self_contained(n, scheme)) {
-        // no preparation pass: round 1 combines W^2 and W while it stages its tiles and finishes orders <= 2 itself
-        Bracket br(stream, EXPM_KCLASS_GEMM, 0.0, 0.0);  // its work is filled in once the plan is known
-        EXPM_TRY(launch_first_round(B.gb, n, batch, dtype, stream));
-    } else {
-        {
-            Bracket br(stream, EXPM_KCLASS_SELECT, 0.0, 0.0);
-            EXPM_TRY(launch_prepare(B.gb, n, batch, dtype, scheme, stream));
-        }
-        Bracket br(stream, EXPM_KCLASS_GEMM, 0.0, 0.0);  // its work is filled in once the plan is known
-        EXPM_TRY(launch_chain_round(B.gb, n, batch, 1, dtype, choose_tile_shape(n, batch), scheme, stream));
-    }
-    const size_t round1_event = g_events.size();
-    EXPM_TRY(hipEventSynchronize(g_summary_ready));
-    const int longest = g_ws.host_summary[0];
-    const int flags = g_ws.host_summary[1];
-    if (g_profile && round1_event > 0) {
-        const int active1 = longest >= 1 ? g_ws.host_summary[3] : 0;
-        g_events[round1_event - 1].flops = 2.0 * nn * n * active1;
-        g_events[round1_event - 1].bytes = 2.0 * active1 * nn * w;
-    }
-    // Rounds 2.. : a matrix's round r needs only its own round r-1.  Below n = 1024 the sorted matrices are dealt
-    // alternately to kChains streams, each with its own chain of rounds: while one chain's launch runs out of
-    // workgroups towards its end, the other's fills the compute units (a single chain leaves them idle there,
-    // 8 % of the call for 32 matrices of 512 x 512).  With the per-class timers on, one chain on the caller's
-    // stream, so that launches do not overlap and each is timed by itself.
-    // profiling aid: EXPM_CHAINS=1 keeps one chain (read once), so that a kernel trace shows launches that do not overlap
-    static const int chain_limit = [] {
-        const char *e = getenv("EXPM_CHAINS");
-        const int v = e ? atoi(e) : 0;
-        return v >= 1 && v <= kChains ? v : kChains;
-    }();
-    int chains = 1;
-    if (!g_profile && n < 1024 && longest >= 2 && g_side_stream != nullptr) chains = std::min(chain_limit, g_ws.host_summary[4]);
-    if (chains > 1) {
-        EXPM_TRY(hipEventRecord(g_fork, stream));
-        for (int c = 1; c < chains; ++c) {
-            if (!g_chain_stream[c]) {
-                if (c == 1) g_chain_stream[c] = g_side_stream;
-                else EXPM_TRY(hipStreamCreateWithFlags(&g_chain_stream[c], hipStreamNonBlocking));
-                EXPM_TRY(hipEventCreateWithFlags(&g_chain_join[c], hipEventDisableTiming));
-            }
-            EXPM_TRY(hipStreamWaitEvent(g_chain_stream[c], g_fork, 0));
-        }
-    }
-    for (int r = 2; r <= longest && r <= kMaxRounds; ++r) {
-        const int active = g_ws.host_summary[2 + r];
-        if (active <= 0) break;
-        if (chains > 1) {
-            for (int c = 0; c < chains; ++c) {
-                const int mine = (active - c + chains - 1) / chains;  // sorted matrices c, c + chains, ... below active
-                if (mine <= 0) break;
-                EXPM_TRY(launch_chain_round(B.gb, n, mine, r, dtype, choose_tile_shape(n, mine), scheme,
-                                            c == 0 ? stream : g_chain_stream[c], c, chains));
-            }
-            continue;
-        }
-        Bracket br(stream, EXPM_KCLASS_GEMM, 2.0 * nn * n * active, 2.0 * active * nn * w);
-        EXPM_TRY(launch_chain_round(B.gb, n, active, r, dtype, choose_tile_shape(n, active), scheme, stream));
-    }
-    for (int c = 1; c < chains; ++c) {
-        EXPM_TRY(hipEventRecord(g_chain_join[c], g_chain_stream[c]));
-        EXPM_TRY(hipStreamWaitEvent(stream, g_chain_join[c], 0));
-    }
-    remember(n, batch, dtype, longest, 0, scheme, stream, B);
-    return warning_from_flags(flags);
+    return expm_impl(A, n, batch, dtype, tol, scheme, norm_kind, out, stream_v);
 }
 
 // ---- low-rank variant (Sec. 2.2): e^(A1 A2) = I + A1 phi(A2 A1) A2 ------------------------------------------
@@ -520,10 +656,9 @@ int check_lowrank_args(const void *A1, const void *A2, int n, int t, int batch, 
 }
 
 // V = A2 A1 and, unless select_only, Phi = series of V; leaves the per-matrix records (m, flags) in the workspace
-int run_lowrank_core(const void *A1, const void *A2, int n, int t, int batch, int dtype, double tol, int select_only,
-                     const LowrankLayout &L, hipStream_t stream)
+int run_lowrank_core(unsigned char *base, const void *A1, const void *A2, int n, int t, int batch, int dtype, double tol,
+                     int select_only, const LowrankLayout &L, hipStream_t stream)
 {
-    unsigned char *base = static_cast<unsigned char *>(g_ws.dev);
     const double w = dtype == EXPM_DTYPE_F64 ? 8.0 : 4.0;
     {
         Bracket br(stream, EXPM_KCLASS_GEMM, 2.0 * t * (double)t * n * batch, ((2.0 * n * t) + (double)t * t) * batch * w);
@@ -536,14 +671,11 @@ int run_lowrank_core(const void *A1, const void *A2, int n, int t, int batch, in
     return EXPM_OK;
 }
 
-void remember_lowrank(int t, int batch, int dtype, hipStream_t stream, const LowrankLayout &L)
+void remember_lowrank(unsigned char *base, int t, int batch, int dtype, int dev, hipStream_t stream, bool usable,
+                      const LowrankLayout &L)
 {
-    g_last.valid = true;
-    g_last.scheme = kSchemePhi;
-    g_last.n = t; g_last.batch = batch; g_last.dtype = dtype;
-    g_last.rounds = 0; g_last.fused = 1; g_last.stream = stream;
-    g_last.info_dev = reinterpret_cast<MatInfo *>(static_cast<unsigned char *>(g_ws.dev) + L.ctl.info);
-    g_last.summary_dev = reinterpret_cast<int *>(static_cast<unsigned char *>(g_ws.dev) + L.ctl.summary);
+    remember(t, batch, dtype, 0, 1, kSchemePhi, dev, stream, usable, reinterpret_cast<MatInfo *>(base + L.ctl.info),
+             reinterpret_cast<int *>(base + L.ctl.summary));
 }
 
 }  // namespace
@@ -558,19 +690,29 @@ int expm_lowrank_select(const void *A1, const void *A2, int n, int t, int batch,
         for (int b = 0; b < batch; ++b) m_out[b] = 0;
         return EXPM_OK;
     }
+    std::lock_guard<std::mutex> lock(g_mutex);
+    DeviceState *ds = nullptr;
+    int dev = 0;
+    rc = current_device(&ds, &dev);
+    if (rc != EXPM_OK) return rc;
     const LowrankLayout L = make_lowrank_layout(n, t, batch, dtype);
-    rc = ensure_workspace(L.total, batch);
+    rc = ensure_workspace(ds, L.total);
     if (rc != EXPM_OK) return rc;
     hipStream_t stream = nullptr;
-    rc = run_lowrank_core(A1, A2, n, t, batch, dtype, tol, 1, L, stream);
+    rc = order_behind_last_call(ds, dev, stream);
     if (rc != EXPM_OK) return rc;
-    remember_lowrank(t, batch, dtype, stream, L);
-    EXPM_TRY(hipMemcpyAsync(g_ws.host_info, g_last.info_dev, (size_t)batch * sizeof(MatInfo), hipMemcpyDeviceToHost, stream));
+    g_brackets = false;
+    unsigned char *base = static_cast<unsigned char *>(ds->dev);
+    rc = run_lowrank_core(base, A1, A2, n, t, batch, dtype, tol, 1, L, stream);
+    if (rc != EXPM_OK) return rc;
+    remember_lowrank(base, t, batch, dtype, dev, stream, true, L);
+    g_host_info.resize((size_t)batch);
+    EXPM_TRY(hipMemcpyAsync(g_host_info.data(), g_last.info_dev, (size_t)batch * sizeof(MatInfo), hipMemcpyDeviceToHost, stream));
     EXPM_TRY(hipStreamSynchronize(stream));
     int flags = 0;
     for (int b = 0; b < batch; ++b) {
-        m_out[b] = g_ws.host_info[b].m;
-        flags |= g_ws.host_info[b].flags;
+        m_out[b] = g_host_info[b].m;
+        flags |= g_host_info[b].flags;
     }
     return warning_from_flags(flags);
 }
@@ -589,12 +731,24 @@ int expm_lowrank(const void *A1, const void *A2, int n, int t, int batch, int dt
         if ((o0 | (t > 0 ? (a1 | a2) : 0)) % w) return EXPM_ERR_INVALID_ARG;
     }
     hipStream_t stream = static_cast<hipStream_t>(stream_v);
-    const LowrankLayout L = make_lowrank_layout(n, t, batch, dtype);
-    rc = ensure_workspace(L.total, batch);
+    std::lock_guard<std::mutex> lock(g_mutex);
+    DeviceState *ds = nullptr;
+    int dev = 0;
+    rc = current_device(&ds, &dev);
     if (rc != EXPM_OK) return rc;
-    unsigned char *base = static_cast<unsigned char *>(g_ws.dev);
+    const LowrankLayout L = make_lowrank_layout(n, t, batch, dtype);
+    const bool capturing = stream_is_capturing(stream);
+    if (capturing && L.total > ds->bytes) return EXPM_ERR_WORKSPACE;
+    rc = ensure_workspace(ds, L.total);
+    if (rc != EXPM_OK) return rc;
+    if (!capturing) {
+        rc = order_behind_last_call(ds, dev, stream);
+        if (rc != EXPM_OK) return rc;
+    }
+    g_brackets = g_profile && !capturing;
+    unsigned char *base = static_cast<unsigned char *>(ds->dev);
     if (t > 0) {
-        rc = run_lowrank_core(A1, A2, n, t, batch, dtype, tol, 0, L, stream);
+        rc = run_lowrank_core(base, A1, A2, n, t, batch, dtype, tol, 0, L, stream);
         if (rc != EXPM_OK) return rc;
         // U = A1 Phi
         Bracket br(stream, EXPM_KCLASS_GEMM, 2.0 * n * (double)t * t * batch, (2.0 * n * t + (double)t * t) * batch * (double)w);
@@ -607,7 +761,7 @@ int expm_lowrank(const void *A1, const void *A2, int n, int t, int batch, int dt
         EXPM_TRY(launch_rect_gemm(base + L.U, A2, out, n, n, t, t, n, n, (size_t)n * t, (size_t)t * n, (size_t)n * n, batch,
                                   dtype, 1, 1, nullptr, stream));
     }
-    if (t > 0) remember_lowrank(t, batch, dtype, stream, L);
+    if (t > 0) remember_lowrank(base, t, batch, dtype, dev, stream, !capturing, L);
     else g_last.valid = false;
     return EXPM_OK;
 }
@@ -616,19 +770,28 @@ int expm_get_stats(struct expm_stats *st)
 {
     if (!st) return EXPM_ERR_INVALID_ARG;
     std::memset(st, 0, sizeof(*st));
+    std::lock_guard<std::mutex> lock(g_mutex);
     if (!g_last.valid) return EXPM_OK;
-    EXPM_TRY(hipMemcpyAsync(g_ws.host_info, g_last.info_dev, (size_t)g_last.batch * sizeof(MatInfo),
-                            hipMemcpyDeviceToHost, g_last.stream));
-    EXPM_TRY(hipStreamSynchronize(g_last.stream));
+    // the records are read on the stream of the call (after a call recorded into a graph: on the null stream, which
+    // waits for whatever replays of that graph have been launched so far on blocking streams)
+    hipStream_t rs = g_last.stream_usable ? g_last.stream : nullptr;
+    g_host_info.resize((size_t)g_last.batch);
+    int prev = 0;
+    EXPM_TRY(hipGetDevice(&prev));
+    if (prev != g_last.device) EXPM_TRY(hipSetDevice(g_last.device));
+    hipError_t e = hipMemcpyAsync(g_host_info.data(), g_last.info_dev, (size_t)g_last.batch * sizeof(MatInfo),
+                                  hipMemcpyDeviceToHost, rs);
+    if (e == hipSuccess) e = hipStreamSynchronize(rs);
+    if (prev != g_last.device) (void)hipSetDevice(prev);
+    if (e != hipSuccess) return hip_fail(e);
     st->matrices = g_last.batch;
     st->n = g_last.n;
     st->dtype = g_last.dtype;
-    st->rounds = g_last.rounds;
     st->fused_path = g_last.fused;
     st->scheme = g_last.scheme;
-    int flags = 0;
+    int flags = 0, longest = 0;
     for (int b = 0; b < g_last.batch; ++b) {
-        const MatInfo &mi = g_ws.host_info[b];
+        const MatInfo &mi = g_host_info[b];
         flags |= mi.flags;
         if (mi.m < 0) { st->nonfinite++; continue; }
         // products the method spends: Sec. 3.1 formulas 0,0,1,2,3,4 for m = 0,1,2,4,8,15; Paterson-Stockmeyer
@@ -646,19 +809,25 @@ int expm_get_stats(struct expm_stats *st)
         st->hist_m[mi.m > 16 ? 16 : mi.m]++;   // the baseline may exceed degree 16: counted in the last bin
         if (mi.s >= 0 && mi.s <= EXPM_S_CAP) st->hist_s[mi.s]++;
         st->products += pi + mi.s;
+        if (mi.len > longest) longest = mi.len;
     }
+    // rounds planned on the device: the longest chain among the records is what the host would have launched
+    st->rounds = g_last.rounds >= 0 ? g_last.rounds : longest;
     st->warning = warning_from_flags(flags);
+    st->warning_bits = flags & 3;
     return EXPM_OK;
 }
 
 int expm_profile_enable(int on)
 {
+    std::lock_guard<std::mutex> lock(g_mutex);
     g_profile = on != 0;
     return EXPM_OK;
 }
 
 int expm_profile_reset(void)
 {
+    std::lock_guard<std::mutex> lock(g_mutex);
     for (auto &e : g_events) {
         g_event_pool.push_back(e.start);
         g_event_pool.push_back(e.stop);
@@ -671,6 +840,7 @@ int expm_profile_read(struct expm_profile *p)
 {
     if (!p) return EXPM_ERR_INVALID_ARG;
     std::memset(p, 0, sizeof(*p));
+    std::lock_guard<std::mutex> lock(g_mutex);
     for (auto &e : g_events) {
         EXPM_TRY(hipEventSynchronize(e.stop));
         float ms = 0.f;
@@ -686,24 +856,36 @@ int expm_profile_read(struct expm_profile *p)
 int expm_shutdown(void)
 {
     expm_profile_reset();
+    std::lock_guard<std::mutex> lock(g_mutex);
     for (auto e : g_event_pool) (void)hipEventDestroy(e);
     g_event_pool.clear();
-    if (g_ws.dev) {
-        (void)hipDeviceSynchronize();
-        (void)hipFree(g_ws.dev);
+    int prev = 0;
+    const bool have_prev = hipGetDevice(&prev) == hipSuccess;
+    for (int d = 0; d < kMaxDevices; ++d) {
+        DeviceState &ds = g_dev[d];
+        const bool used = ds.dev || ds.host_summary || ds.summary_ready || ds.fork || ds.side_stream || ds.order_event;
+        if (!used) { ds = DeviceState{}; continue; }
+        (void)hipSetDevice(d);
+        if (ds.dev) {
+            (void)hipDeviceSynchronize();
+            (void)hipFree(ds.dev);
+        }
+        if (ds.host_summary) (void)hipHostFree(ds.host_summary);
+        if (ds.summary_ready) (void)hipEventDestroy(ds.summary_ready);
+        if (ds.fork) (void)hipEventDestroy(ds.fork);
+        if (ds.join) (void)hipEventDestroy(ds.join);
+        if (ds.order_event) (void)hipEventDestroy(ds.order_event);
+        for (int c = 1; c < kChains; ++c) {
+            if (ds.chain_join[c]) (void)hipEventDestroy(ds.chain_join[c]);
+            if (c > 1 && ds.chain_stream[c]) (void)hipStreamDestroy(ds.chain_stream[c]);
+        }
+        if (ds.side_stream) (void)hipStreamDestroy(ds.side_stream);
+        ds = DeviceState{};
     }
-    if (g_ws.host_summary) (void)hipHostFree(g_ws.host_summary);
-    if (g_summary_ready) { (void)hipEventDestroy(g_summary_ready); g_summary_ready = nullptr; }
-    if (g_fork) { (void)hipEventDestroy(g_fork); g_fork = nullptr; }
-    if (g_join) { (void)hipEventDestroy(g_join); g_join = nullptr; }
-    for (int c = 1; c < kChains; ++c) {
-        if (g_chain_join[c]) { (void)hipEventDestroy(g_chain_join[c]); g_chain_join[c] = nullptr; }
-        if (c > 1 && g_chain_stream[c]) (void)hipStreamDestroy(g_chain_stream[c]);
-        g_chain_stream[c] = nullptr;
-    }
-    if (g_side_stream) { (void)hipStreamDestroy(g_side_stream); g_side_stream = nullptr; }
-    free(g_ws.host_info);
-    g_ws = Workspace{};
+    if (have_prev) (void)hipSetDevice(prev);
+    (void)hipGetLastError();
+    g_host_info.clear();
+    g_host_info.shrink_to_fit();
     g_last = LastCall{};
     return EXPM_OK;
 }
@@ -721,6 +903,7 @@ const char *expm_status_string(int status)
     case EXPM_ERR_ALLOC: return "error: allocation failed";
     case EXPM_ERR_HIP: return "error: a HIP call failed (see expm_last_hip_error)";
     case EXPM_ERR_UNSUPPORTED: return "error: this scheme is not available for this matrix size";
+    case EXPM_ERR_WORKSPACE: return "error: the workspace would have to grow inside a stream capture (reserve it first)";
     default: return "unknown status";
     }
 }

@@ -951,13 +951,12 @@ hipError_t launch_fused_t(const void *A, void *out, int n, int batch, double eps
                           MatInfo *info, hipStream_t stream)
 {
     using C = FusedCfg<T, NT>;
-    static bool attr_done = false;
-    if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(fused_expm_kernel<T, NT, SCHEME>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, C::kLds);
-        if (e != hipSuccess) return e;
-        attr_done = true;
-    }
+    static PerDeviceOnce lds_limit;
+    hipError_t e = lds_limit([] {
+        return hipFuncSetAttribute(reinterpret_cast<const void *>(fused_expm_kernel<T, NT, SCHEME>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, C::kLds);
+    });
+    if (e != hipSuccess) return e;
     hipLaunchKernelGGL((fused_expm_kernel<T, NT, SCHEME>), dim3((batch + C::kMPW - 1) / C::kMPW), dim3(C::kBlock), C::kLds,
                        stream, reinterpret_cast<const T *>(A), reinterpret_cast<T *>(out), n, batch, eps, select_only,
                        norm_inf, info);

@@ -71,6 +71,7 @@ struct GemmParams {
     int slot0, slot_step;  // chain rounds: this launch covers the sorted matrices slot0, slot0 + slot_step, ...
     int scheme;  // kSchemeSastre or kSchemePS
     int norm_inf;  // power rounds: emit row abs-sums (infinity-norm) instead of column abs-sums
+    const int *active;  // rounds planned on the device: &summary[2], active[r] = matrices still active in round r; else null
 };
 
 __device__ __forceinline__ double pow2neg(int e)
@@ -156,7 +157,14 @@ __global__ __launch_bounds__(kThreads, WT == 4 ? 2 : 4) void gemm_round_kernel(G
 
     // ---- which (matrix, tile) ---------------------------------------------------------------
     const int tiles2 = p.tiles * p.tiles;
-    const int wid = xcd_remap(blockIdx.x, p.total);
+    // Rounds planned on the device are launched over the whole batch: the workgroups beyond this round's active
+    // prefix of the sorted list leave, and the others spread over the XCDs as a launch of exactly that size would.
+    int total = p.total;
+    if (p.active != nullptr) {
+        total = min(total, p.active[p.round] * tiles2);
+        if ((int)blockIdx.x >= total) return;
+    }
+    const int wid = xcd_remap(blockIdx.x, total);
     const int slot = wid / tiles2;
     const int tile = wid - slot * tiles2;
     int b;
@@ -747,14 +755,13 @@ __global__ __launch_bounds__(256) void prepare_kernel(GemmParams p)
 template <typename T, int WT, int ALIGNED, bool FIRST = false>
 hipError_t launch_gemm_t(const GemmParams &p, hipStream_t stream)
 {
-    static bool attr_done = false;
+    static PerDeviceOnce lds_limit;
     const int lds = 2 * stage_bytes<T, WT>(ALIGNED == kAccessDma);
-    if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_round_kernel<T, WT, ALIGNED, FIRST>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-        if (e != hipSuccess) return e;
-        attr_done = true;
-    }
+    hipError_t e = lds_limit([] {
+        return hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_round_kernel<T, WT, ALIGNED, FIRST>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    });
+    if (e != hipSuccess) return e;
     hipLaunchKernelGGL((gemm_round_kernel<T, WT, ALIGNED, FIRST>), dim3(p.total), dim3(kThreads), lds, stream, p);
     return hipGetLastError();
 }
@@ -774,6 +781,7 @@ GemmParams make_params(const GeneralBuffers &gb, int n, int round, int matrices,
     p.total = matrices * p.tiles * p.tiles;
     p.slot0 = 0;
     p.slot_step = 1;
+    p.active = nullptr;
     return p;
 }
 
@@ -918,11 +926,12 @@ hipError_t launch_prepare(const GeneralBuffers &gb, int n, int batch, int dtype,
 
 // `active` matrices of the sorted list, starting at `first` and `step` apart (1: a contiguous range)
 hipError_t launch_chain_round(const GeneralBuffers &gb, int n, int active, int round, int dtype, int wt, int scheme,
-                              hipStream_t stream, int first, int step)
+                              hipStream_t stream, int first, int step, bool device_plan)
 {
     GemmParams p = make_params(gb, n, round, active, wt, scheme);
     p.slot0 = first;
     p.slot_step = step;
+    if (device_plan) p.active = gb.summary + 2;   // `active` is then the whole batch
     return launch_gemm(p, dtype, wt, gb.ptr_align16, stream);
 }
 

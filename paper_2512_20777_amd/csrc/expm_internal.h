@@ -50,22 +50,22 @@ struct MatInfo {
 };
 
 // Scaling that one error term asks for (last steps of Algorithms 3 and 4): the smallest s >= 0 with
-// e / 2^(w s) <= eps, i.e. ceil(log2(e / eps) / w) clipped to [0, cap].  Found from the binary exponents of e
-// and eps and one exact comparison against eps * 2^(w s) instead of a division and a logarithm: with
-// e = fe 2^xe and eps = fp 2^xp (fe, fp in [1/2, 1)) the ratio lies in (2^(d-1), 2^(d+1)), d = xe - xp, so
-// s is floor((d-1)/w) + 1 or one more.
+// e / 2^(w s) <= eps, i.e. ceil(log2(e / eps) / w), or cap + 1 if that exceeds the cap (or e is not finite): the
+// caller clips to the cap and flags the matrix.  Found from the binary exponents of e and eps and one exact
+// comparison against eps * 2^(w s) instead of a division and a logarithm: with e = fe 2^xe and eps = fp 2^xp
+// (fe, fp in [1/2, 1)) the ratio lies in (2^(d-1), 2^(d+1)), d = xe - xp, so s is floor((d-1)/w) + 1 or one more.
 __host__ __device__ inline int scaling_for_term(double e, double eps, int w)
 {
-    if (!(e <= 1.7976931348623157e308)) return kSCap;
+    if (!(e <= 1.7976931348623157e308)) return kSCap + 1;
     if (e <= eps) return 0;  // also e <= 0
     int xe, xp;
     (void)frexp(e, &xe);
     (void)frexp(eps, &xp);
     const int d = xe - xp;  // >= 0 here
     int s1 = d >= 1 ? (d - 1) / w + 1 : 0;
-    if (s1 > kSCap) return kSCap;
+    if (s1 > kSCap) return kSCap + 1;
     if (e > ldexp(eps, w * s1)) ++s1;
-    return s1 > kSCap ? kSCap : s1;
+    return s1 > kSCap ? kSCap + 1 : s1;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -115,7 +115,7 @@ __host__ __device__ inline void select_order_scaling(double n1, double n2, doubl
     // scaling from each of the two terms alone, the larger wins (Sec. 3.2, last paragraph)
     const int sa = scaling_for_term(e1, eps, 16), sb = scaling_for_term(e2, eps, 17);
     s = sa > sb ? sa : sb;
-    if (s >= kSCap) { s = kSCap; flags |= 2; }
+    if (s > kSCap) { s = kSCap; flags |= 2; }  // Algorithm clips only when more than the cap is asked for
 }
 
 // Rounds after the W^2 product: T4 needs 1 more product, T8 2, 15+ 3, plus one per squaring.
@@ -174,7 +174,7 @@ __host__ __device__ inline void select_ps_order_scaling(const double nrm[4], int
     }
     const int sa = scaling_for_term(e1, eps, 17), sb = scaling_for_term(e2, eps, 18);
     s = sa > sb ? sa : sb;
-    if (s >= kSCap) { s = kSCap; flags |= 2; }
+    if (s > kSCap) { s = kSCap; flags |= 2; }  // Algorithm clips only when more than the cap is asked for
 }
 
 // Products after the powers: k-1 Horner steps, plus one per squaring.
@@ -416,6 +416,21 @@ __device__ __forceinline__ int xcd_remap(int pid, int total)
     return xcd < tall ? xcd * per + idx : tall * per + (xcd - tall) * (per - 1) + idx;
 }
 
+// A kernel's dynamic-LDS limit is an attribute of the (kernel, device) pair: run `set` once per device.
+struct PerDeviceOnce {
+    unsigned long long done = 0;  // bit d: set on device d
+    template <class F> hipError_t operator()(F &&set)
+    {
+        int dev = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e != hipSuccess) return e;
+        if (dev >= 0 && dev < 64 && ((done >> dev) & 1ull)) return hipSuccess;
+        e = set();
+        if (e == hipSuccess && dev >= 0 && dev < 64) done |= 1ull << dev;
+        return e;
+    }
+};
+
 // small fused path
 bool small_path_supported(int n, int dtype);
 hipError_t launch_small(const void *A, void *out, int n, int batch, int dtype, double eps, int select_only,
@@ -438,6 +453,6 @@ int rect_gemm_slices(int M, int N, int K, int batch, int dtype);
 bool first_round_is_self_contained(int n, int scheme);
 hipError_t launch_first_round(const GeneralBuffers &gb, int n, int batch, int dtype, hipStream_t stream);
 hipError_t launch_chain_round(const GeneralBuffers &gb, int n, int active, int round, int dtype, int wt, int scheme,
-                              hipStream_t stream, int first = 0, int step = 1);
+                              hipStream_t stream, int first = 0, int step = 1, bool device_plan = false);
 
 }  // namespace expmk

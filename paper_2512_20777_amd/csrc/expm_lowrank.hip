@@ -317,13 +317,12 @@ template <typename T, int WT, int MODE>
 hipError_t launch_rect_v(const RectParams &p, dim3 grid, hipStream_t stream)
 {
     const int lds = 2 * rect_stage_bytes<T, WT>(MODE == kRectDma);
-    static bool attr_done = false;  // the 128x128 tile needs more dynamic LDS than the default limit
-    if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(rect_gemm_kernel<T, WT, MODE>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-        if (e != hipSuccess) return e;
-        attr_done = true;
-    }
+    static PerDeviceOnce lds_limit;  // the 128x128 tile needs more dynamic LDS than the default limit
+    hipError_t e = lds_limit([] {
+        return hipFuncSetAttribute(reinterpret_cast<const void *>(rect_gemm_kernel<T, WT, MODE>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    });
+    if (e != hipSuccess) return e;
     hipLaunchKernelGGL((rect_gemm_kernel<T, WT, MODE>), grid, dim3(kRectThreads), lds, stream, p);
     return hipGetLastError();
 }

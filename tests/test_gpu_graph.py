@@ -1,9 +1,9 @@
-"""The single-launch paths recorded into a HIP graph and replayed.
+"""Calls recorded into a HIP graph and replayed; calls on several streams.
 
-The fused path of expm() (matrices that fit a compute unit) and expm_lowrank() enqueue kernels only: no host
-read-back, no memset, no allocation once the workspace is reserved.  A caller with a launch-bound loop (many small
-batches per step, as in a flow model) can therefore record them into a graph.  Every replay is checked bit for bit
-against an eager call on the same input, with eager work and synchronisations between the replays.
+Under stream capture expm() and expm_lowrank() enqueue kernels only: no host read-back, no memset, no other stream,
+no allocation once the workspace is reserved.  A caller with a launch-bound loop (many small batches per step, as in
+a flow model) can therefore record them into a graph.  Every replay is checked bit for bit against an eager call on
+the same input, with eager work and synchronisations between the replays.
 """
 import numpy as np
 import pytest
@@ -76,3 +76,79 @@ def test_lowrank_replayed_from_a_graph_equals_eager(ex):
         graph.replay()
         torch.cuda.synchronize()
         assert torch.equal(static_out, eager), rep
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("n,batch,dtype,scheme", [(200, 5, np.float64, 0), (512, 3, np.float64, 0), (136, 6, np.float32, 0),
+                                                  (200, 4, np.float64, 1)])
+def test_round_based_expm_replayed_from_a_graph_equals_eager(ex, n, batch, dtype, scheme):
+    """Above the on-chip sizes the number of product rounds depends on the data.  Under capture the rounds are planned
+    on the device (every possible round is recorded, workgroups of rounds a matrix does not need leave at once), so one
+    graph serves inputs with different (m, s): each replay gets norms from another range."""
+    import torch
+    dt = ex.DTYPE_F64 if dtype == np.float64 else ex.DTYPE_F32
+    static_in = torch.from_numpy(workloads.random_stack(9400 + n, batch, n, dtype, 0.5, 20.0)).cuda()
+    static_out = torch.empty_like(static_in)
+    ex.expm_reserve(n, batch, dt)
+    ex.expm(static_in, 0.0, out=static_out, scheme=scheme)   # first call outside the capture: attributes, workspace
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    print("capture n=%d batch=%d %s scheme %d" % (n, batch, np.dtype(dtype).name, scheme), flush=True)
+    with torch.cuda.graph(graph, stream=side):
+        ex.expm(static_in, 0.0, out=static_out, scheme=scheme)
+    ranges = [(1e-9, 1e-3), (0.05, 2.0), (5.0, 300.0), (1e-3, 80.0)]
+    for rep, (lo, hi) in enumerate(ranges):
+        fresh = workloads.random_stack(9500 + 7 * rep + n, batch, n, dtype, lo, hi, "dense" if rep % 2 else "triu")
+        static_in.copy_(torch.from_numpy(fresh).cuda())
+        static_out.zero_()
+        eager, st = ex.expm(static_in.clone(), 0.0, scheme=scheme)     # the program's own eager work between replays
+        torch.cuda.synchronize()
+        m_e, s_e, _ = ex.expm_select(static_in, 0.0, scheme=scheme)
+        print("   replay %d: s up to %d" % (rep, int(s_e.max())), flush=True)
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(static_out, eager), (n, batch, rep)
+
+
+@pytest.mark.gpu
+def test_capture_refuses_to_grow_the_workspace(ex):
+    import torch
+    ex.expm_shutdown()                    # drop the cached workspace: the capture below would have to allocate
+    a = torch.from_numpy(workloads.random_stack(9600, 2, 160, np.float64, 0.5, 5.0)).cuda()
+    out = torch.empty_like(a)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    lib = ex.load_library()
+    with torch.cuda.graph(graph, stream=side):
+        out.zero_()                       # so that the graph is not empty
+        status = lib.expm(a.data_ptr(), 160, 2, ex.DTYPE_F64, 0.0, out.data_ptr(), torch.cuda.current_stream().cuda_stream)
+    assert status == -6, status           # refused, nothing enqueued, the capture itself stays valid
+    torch.cuda.synchronize()
+    res, st = ex.expm(a, 0.0, out=out)    # and the library is usable afterwards
+    torch.cuda.synchronize()
+    assert st == 0 and bool(torch.isfinite(res).all())
+
+
+@pytest.mark.gpu
+def test_calls_on_two_streams_are_ordered_not_corrupted(ex):
+    """All calls share one workspace per device: a call on another stream is ordered behind the previous call."""
+    import torch
+    a = torch.from_numpy(workloads.random_stack(9700, 6, 256, np.float64, 0.5, 40.0)).cuda()
+    b = torch.from_numpy(workloads.random_stack(9701, 6, 256, np.float64, 0.5, 40.0)).cuda()
+    ra, _ = ex.expm(a)
+    ra = ra.clone()
+    rb, _ = ex.expm(b)
+    rb = rb.clone()
+    torch.cuda.synchronize()
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    oa, ob = torch.empty_like(a), torch.empty_like(b)
+    for rep in range(3):
+        oa.zero_(); ob.zero_()
+        torch.cuda.synchronize()
+        ex.expm(a, out=oa, stream=s1)
+        ex.expm(b, out=ob, stream=s2)     # no synchronisation in between
+        ex.expm(a, out=oa, stream=s1)
+        torch.cuda.synchronize()
+        assert torch.equal(oa, ra) and torch.equal(ob, rb), rep
