@@ -18,8 +18,8 @@
  * Threading and streams: the library keeps one cached device workspace per device.  Entry points are
  * serialised by a lock, and a call on another stream than the previous call's is ordered on the device
  * behind everything queued on that stream so far, so calls from several host threads or on several
- * streams are safe; they run one after another, not side by side.  Exception: calls recorded into a HIP
- * graph are not ordered against other calls (see expm).
+ * streams are safe; they run one after another, not side by side.  Exceptions: calls recorded into a HIP
+ * graph and expm_noalloc() are not ordered against other calls (see there).
  */
 #ifndef EXPM_MI355X_H
 #define EXPM_MI355X_H
@@ -44,7 +44,8 @@ extern "C" {
 #define EXPM_ERR_ALLOC         -3  /* device or pinned-host allocation failed */
 #define EXPM_ERR_HIP           -4  /* a HIP call failed; expm_last_hip_error() returns its hipError_t */
 #define EXPM_ERR_UNSUPPORTED   -5  /* the scheme asked for is not available for this matrix size */
-#define EXPM_ERR_WORKSPACE     -6  /* the cached workspace would have to grow inside a stream capture (expm_reserve first) */
+#define EXPM_ERR_WORKSPACE     -6  /* the workspace of this shape exceeds what the call may use: the static scratch of
+                                      expm_noalloc(), or a cached workspace that would have to grow inside a stream capture */
 
 #define EXPM_S_CAP 20  /* largest scaling Algorithm 4 returns */
 
@@ -101,6 +102,28 @@ int expm_select(const void *A, int n, int batch, int dtype, double tol,
  * finished the call; the library owns its workspace (see expm_workspace_bytes).
  */
 int expm(const void *A, int n, int batch, int dtype, double tol, void *out, void *stream);
+
+/*
+ * expm_noalloc -- expm() for callers that cannot allocate: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid allocation.  Same arguments, result and status codes as expm(); the differences:
+ *
+ *   - It calls no allocator of any kind (no hipMalloc / hipFree / hipHostMalloc, no stream or event creation, no
+ *     host allocation).  Its workspace (per-matrix records, norm partials and, above the fused-path sizes, the seven
+ *     matrix stacks) lives in a static device array of EXPM_NOALLOC_SCRATCH_BYTES that every GPU the library runs on
+ *     holds from the moment the library is loaded until the process ends.  A shape whose
+ *     expm_workspace_bytes(n, batch, dtype) exceeds that size is rejected with EXPM_ERR_WORKSPACE, nothing enqueued.
+ *     (64 MiB: batches of on-chip sizes up to about a million matrices, 52 bytes each; e.g. 29 matrices of 200 x 200 or 4 of
+ *     512 x 512 in fp64 on the round-based path.)
+ *   - It only enqueues kernels on `stream` (rounds planned on the device, see expm()), never waits, and may be
+ *     recorded into a HIP graph as it is.  It therefore returns 0 or an error; warnings surface through
+ *     expm_get_stats().
+ *   - All calls on one GPU share that GPU's array, which keeps the previous call's contents (every call rewrites what
+ *     it reads; nothing needs clearing).  Calls that overlap in time on one GPU -- two streams, or a graph replay
+ *     beside another call -- race on it: the caller orders them.  expm_noalloc does not touch the cached workspace
+ *     of the other entry points, so it may run beside those.
+ */
+#define EXPM_NOALLOC_SCRATCH_BYTES (64u << 20)
+int expm_noalloc(const void *A, int n, int batch, int dtype, double tol, void *out, void *stream);
 
 /*
  * Variants of the two calls above that pick the evaluation scheme (Sec. 3.3, Algorithm 2 with either

@@ -16,6 +16,7 @@ from .binding import (  # noqa: F401
     expm_get_stats,
     expm_lowrank,
     expm_lowrank_select,
+    expm_noalloc,
     expm_profile_enable,
     expm_profile_read,
     expm_profile_reset,

@@ -69,6 +69,8 @@ def load_library():
     lib.expm_select.argtypes = [vp, ci, ci, ci, cd, i32p, i32p]
     lib.expm.restype = ci
     lib.expm.argtypes = [vp, ci, ci, ci, cd, vp, vp]
+    lib.expm_noalloc.restype = ci
+    lib.expm_noalloc.argtypes = [vp, ci, ci, ci, cd, vp, vp]
     lib.expm_select_scheme.restype = ci
     lib.expm_select_scheme.argtypes = [vp, ci, ci, ci, cd, ci, i32p, i32p]
     lib.expm_scheme.restype = ci
@@ -171,6 +173,25 @@ def expm(A, tol: float = 0.0, out=None, stream=None, scheme: int = SCHEME_SASTRE
     else:
         with torch.cuda.device(dev):
             st = lib.expm_ex(A.data_ptr(), n, batch, dt, tol, scheme, norm, out.data_ptr(), sp)
+    if st < 0:
+        _check(st)
+    return out, st
+
+
+def expm_noalloc(A, tol: float = 0.0, out=None, stream=None):
+    """expm() through the entry point that allocates nothing (static device scratch); `out` must be given by callers
+    that may not allocate.  Returns (out, status)."""
+    import torch
+    lib = _lib if _lib is not None else load_library()
+    n, batch, dt = _describe(A)
+    if out is None:
+        out = torch.empty_like(A)
+    elif out.shape != A.shape or out.dtype is not A.dtype or out.device != A.device or not out.is_contiguous():
+        raise ExpmError(-1, "out must match the input's shape, dtype and device and be contiguous")
+    dev = A.device.index
+    sp = stream.cuda_stream if stream is not None else torch.cuda.current_stream(dev).cuda_stream
+    with torch.cuda.device(dev):
+        st = lib.expm_noalloc(A.data_ptr(), n, batch, dt, tol, out.data_ptr(), sp)
     if st < 0:
         _check(st)
     return out, st

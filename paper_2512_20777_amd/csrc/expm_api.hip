@@ -15,7 +15,8 @@ namespace {
 using namespace expmk;
 
 // Everything the library keeps between calls is kept per device: the cached workspace block, the pinned mirror of
-// the plan summary, and the side streams and events of the round-based path.
+// the plan summary, the side streams and events of the round-based path, and the address of that device's copy of
+// the static scratch array.
 constexpr int kMaxDevices = 16;
 constexpr int kChains = 2;                        // chains of rounds that run side by side below n = 1024
 
@@ -29,6 +30,7 @@ struct DeviceState {
     hipStream_t chain_stream[kChains] = {};     // [0] unused (the caller's stream), [1] = side_stream, rest their own
     hipEvent_t chain_join[kChains] = {};
     hipEvent_t order_event = nullptr;           // orders a call behind the previous one when the stream changes
+    unsigned char *scratch_ptr = nullptr;       // device address of this device's copy of `scratch`
 };
 
 struct LastCall {
@@ -49,6 +51,12 @@ struct ProfEvent {
     int kclass;
     double flops, bytes;
 };
+
+// Scratch for the entry point that must not allocate (expm_noalloc): its control block and matrix stacks live here
+// instead of in the cached workspace.  Every GPU the library runs on holds its own copy at its own address
+// (hipGetSymbolAddress with that device current); in host code the name below is only a handle for that lookup.
+constexpr size_t kStaticScratchBytes = (size_t)EXPM_NOALLOC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
 DeviceState g_dev[kMaxDevices];
 std::vector<MatInfo> g_host_info;   // pageable mirror of the per-matrix records for stats / select
@@ -458,7 +466,11 @@ int run_rounds(DeviceState *ds, const Bound &B, int n, int batch, int dtype, dou
     return EXPM_OK;
 }
 
-int expm_impl(const void *A, int n, int batch, int dtype, double tol, int scheme, int norm_kind, void *out, void *stream_v)
+constexpr int kModeCached = 0;   // workspace from the cached block (allocated and grown on demand)
+constexpr int kModeStatic = 1;   // workspace in the static scratch array: no allocation of any kind
+
+int expm_impl(const void *A, int n, int batch, int dtype, double tol, int scheme, int norm_kind, void *out, void *stream_v,
+              int mode)
 {
     if (scheme != EXPM_SCHEME_SASTRE && scheme != EXPM_SCHEME_PS && scheme != EXPM_SCHEME_BASELINE)
         return EXPM_ERR_INVALID_ARG;
@@ -476,6 +488,7 @@ int expm_impl(const void *A, int n, int batch, int dtype, double tol, int scheme
     }
     hipStream_t stream = static_cast<hipStream_t>(stream_v);
     const Layout L = make_layout(n, batch, dtype);
+    if (mode == kModeStatic && L.total > kStaticScratchBytes) return EXPM_ERR_WORKSPACE;   // before any device work
     std::lock_guard<std::mutex> lock(g_mutex);
     DeviceState *ds = nullptr;
     int dev = 0;
@@ -483,7 +496,15 @@ int expm_impl(const void *A, int n, int batch, int dtype, double tol, int scheme
     if (rc != EXPM_OK) return rc;
     const bool capturing = stream_is_capturing(stream);
     unsigned char *base = nullptr;
-    {
+    if (mode == kModeStatic) {
+        if (!ds->scratch_ptr) {
+            // once per device, with that device current: where this device keeps its copy of the array
+            void *p = nullptr;
+            EXPM_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+            ds->scratch_ptr = static_cast<unsigned char *>(p);
+        }
+        base = ds->scratch_ptr;
+    } else {
         if (capturing && L.total > ds->bytes) return EXPM_ERR_WORKSPACE;   // a capture cannot allocate: expm_reserve first
         rc = ensure_workspace(ds, L.total);
         if (rc != EXPM_OK) return rc;
@@ -493,7 +514,7 @@ int expm_impl(const void *A, int n, int batch, int dtype, double tol, int scheme
             if (rc != EXPM_OK) return rc;
         }
     }
-    g_brackets = g_profile && !capturing;
+    g_brackets = g_profile && mode == kModeCached && !capturing;
     const Bound B = bind(base, A, out, n, batch, dtype, norm_kind);
     const double w = dtype == EXPM_DTYPE_F64 ? 8.0 : 4.0;
     const double nn = (double)n * n;
@@ -507,7 +528,7 @@ int expm_impl(const void *A, int n, int batch, int dtype, double tol, int scheme
         remember(n, batch, dtype, 0, 1, scheme, dev, stream, !capturing, B.gb.info, B.gb.summary);
         return EXPM_OK;
     }
-    bool on_device = capturing;
+    bool on_device = mode == kModeStatic || capturing;
     if (!on_device) on_device = env_plan() == 1 || (env_plan() == 0 && plan_on_device_by_default(n, batch));
     int rounds = 0, warning = EXPM_OK;
     rc = run_rounds(ds, B, n, batch, dtype, tol, scheme, stream, on_device, &rounds, &warning);
@@ -602,17 +623,22 @@ int expm_select_ex(const void *A, int n, int batch, int dtype, double tol, int s
 
 int expm(const void *A, int n, int batch, int dtype, double tol, void *out, void *stream_v)
 {
-    return expm_impl(A, n, batch, dtype, tol, EXPM_SCHEME_SASTRE, EXPM_NORM_ONE, out, stream_v);
+    return expm_impl(A, n, batch, dtype, tol, EXPM_SCHEME_SASTRE, EXPM_NORM_ONE, out, stream_v, kModeCached);
 }
 
 int expm_scheme(const void *A, int n, int batch, int dtype, double tol, int scheme, void *out, void *stream_v)
 {
-    return expm_impl(A, n, batch, dtype, tol, scheme, EXPM_NORM_ONE, out, stream_v);
+    return expm_impl(A, n, batch, dtype, tol, scheme, EXPM_NORM_ONE, out, stream_v, kModeCached);
 }
 
 int expm_ex(const void *A, int n, int batch, int dtype, double tol, int scheme, int norm_kind, void *out, void *stream_v)
 {
-    return expm_impl(A, n, batch, dtype, tol, scheme, norm_kind, out, stream_v);
+    return expm_impl(A, n, batch, dtype, tol, scheme, norm_kind, out, stream_v, kModeCached);
+}
+
+int expm_noalloc(const void *A, int n, int batch, int dtype, double tol, void *out, void *stream_v)
+{
+    return expm_impl(A, n, batch, dtype, tol, EXPM_SCHEME_SASTRE, EXPM_NORM_ONE, out, stream_v, kModeStatic);
 }
 
 // ---- low-rank variant (Sec. 2.2): e^(A1 A2) = I + A1 phi(A2 A1) A2 ------------------------------------------
@@ -880,7 +906,7 @@ int expm_shutdown(void)
             if (c > 1 && ds.chain_stream[c]) (void)hipStreamDestroy(ds.chain_stream[c]);
         }
         if (ds.side_stream) (void)hipStreamDestroy(ds.side_stream);
-        ds = DeviceState{};
+        ds = DeviceState{};   // the static scratch array stays with the device; its address is looked up again on demand
     }
     if (have_prev) (void)hipSetDevice(prev);
     (void)hipGetLastError();
@@ -903,7 +929,8 @@ const char *expm_status_string(int status)
     case EXPM_ERR_ALLOC: return "error: allocation failed";
     case EXPM_ERR_HIP: return "error: a HIP call failed (see expm_last_hip_error)";
     case EXPM_ERR_UNSUPPORTED: return "error: this scheme is not available for this matrix size";
-    case EXPM_ERR_WORKSPACE: return "error: the workspace would have to grow inside a stream capture (reserve it first)";
+    case EXPM_ERR_WORKSPACE: return "error: the workspace this shape needs exceeds what the call may use (static scratch "
+                                    "of expm_noalloc, or a workspace that would have to grow inside a stream capture)";
     default: return "unknown status";
     }
 }

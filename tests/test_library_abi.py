@@ -71,6 +71,15 @@ def test_argument_validation_happens_before_any_device_work(lib):
     assert lib.expm_select(null, 0, 4, 1, 0.0, mp, sp) == 0 and list(m) == [0, 0, 0, 0]
 
 
+def test_noalloc_entry_point_refuses_oversized_shapes_without_a_device(lib):
+    fake = ctypes.c_void_p(0x1000)
+    far = ctypes.c_void_p(0x1000 + (1 << 40))
+    assert lib.expm_workspace_bytes(512, 32, 1) > (64 << 20)
+    assert lib.expm_noalloc(fake, 512, 32, 1, 0.0, far, None) == -6
+    assert lib.expm_noalloc(fake, -1, 32, 1, 0.0, far, None) == -1
+    assert "workspace" in lib.expm_status_string(-6).decode()
+
+
 def test_workspace_size_formula(lib):
     assert lib.expm_workspace_bytes(0, 4, 1) == 0
     assert lib.expm_workspace_bytes(16, -1, 0) == 0
