@@ -137,10 +137,13 @@ int expm_noalloc(const void *A, int n, int batch, int dtype, double tol, void *o
  *   EXPM_SCHEME_BASELINE  the comparison baseline of the paper (its Algorithm 1, Sec. 2.2, after Xiao & Liu):
  *                       smallest s with ||W||/2^s < 1/2, Taylor terms Y <- W Y/k added while ||Y|| > tol,
  *                       s squarings.  m_out holds the degree reached (it may exceed 16; the paper prices it at
- *                       (m-1)+s products), no cap on s.  Available on the fused path only (n <= 128 in fp32,
- *                       n <= 96 in fp64; the paper's flow models use it below 24x24): larger n returns
- *                       EXPM_ERR_UNSUPPORTED.  expm_select_scheme runs the term loop as well, since the degree
- *                       is only known at its end.
+ *                       (m-1)+s products), no cap on s.  Up to n = 128 (fp32) / 96 (fp64) the whole loop runs on
+ *                       chip in the fused kernel; above, every term is a product round over the matrices still in
+ *                       the loop (as many rounds as the tolerance can ask for are enqueued, a matrix leaves them when
+ *                       its term has dropped to tol), and the largest s is read back once to size the squaring
+ *                       rounds -- so for larger n this scheme waits on the stream like expm() does by default, and
+ *                       returns EXPM_ERR_UNSUPPORTED under stream capture.  expm_select_scheme runs the term loop
+ *                       as well, since the degree is only known at its end.
  * All other arguments, blocking behaviour, ownership and status codes are as for expm_select / expm.
  */
 #define EXPM_SCHEME_SASTRE   0

@@ -466,6 +466,55 @@ int run_rounds(DeviceState *ds, const Bound &B, int n, int batch, int dtype, dou
     return EXPM_OK;
 }
 
+// Baseline of the paper's comparison (its Algorithm 1) on the round-based path.  The term rounds are planned on the
+// device: as many as the tolerance can ask for are launched over the whole batch (a matrix whose last term has
+// dropped to the tolerance leaves them), each followed by the norm reduction of the new term and the decision who
+// goes on.  The scalings follow from ||W|| alone: the largest travels to the host while the term rounds run, and
+// exactly that many squaring rounds follow (Algorithm 1 has no cap on s, so these cannot be launched blind).
+int run_baseline_rounds(DeviceState *ds, const Bound &B, int n, int batch, int dtype, double tol, hipStream_t stream,
+                        bool select_only, int *rounds_out, int *warning_out)
+{
+    const double w = dtype == EXPM_DTYPE_F64 ? 8.0 : 4.0;
+    const double nn = (double)n * n;
+    *warning_out = EXPM_OK;
+    int rc = ensure_host_summary(ds);
+    if (rc != EXPM_OK) return rc;
+    {
+        Bracket br(stream, EXPM_KCLASS_NORM, 0.0, batch * nn * w);
+        EXPM_TRY(launch_colabs(B.gb, n, batch, dtype, stream));
+        EXPM_TRY(launch_colmax(B.gb, n, batch, 1, B.gb.norm_inf ? 1 : general_colchunks(n), stream));
+    }
+    {
+        Bracket br(stream, EXPM_KCLASS_SELECT, 0.0, 0.0);
+        EXPM_TRY(launch_baseline_decide(B.gb, n, batch, tol, 0, stream));
+    }
+    EXPM_TRY(hipMemcpyAsync(ds->host_summary, B.gb.summary, 64 * sizeof(int), hipMemcpyDeviceToHost, stream));
+    if (!ds->summary_ready) EXPM_TRY(hipEventCreateWithFlags(&ds->summary_ready, hipEventDisableTiming));
+    EXPM_TRY(hipEventRecord(ds->summary_ready, stream));
+    const int wt = choose_tile_shape(n, batch);
+    const int terms = baseline_max_terms(tol);
+    for (int t = 1; t <= terms; ++t) {
+        {
+            Bracket br(stream, EXPM_KCLASS_GEMM, 0.0, 0.0);   // how many matrices are still in the loop is known on the device only
+            EXPM_TRY(launch_baseline_round(B.gb, n, batch, t, dtype, wt, select_only, stream));
+        }
+        Bracket br(stream, EXPM_KCLASS_SELECT, 0.0, 0.0);
+        EXPM_TRY(launch_colmax(B.gb, n, batch, 2, (n + 32 * wt - 1) / (32 * wt), stream));
+        EXPM_TRY(launch_baseline_decide(B.gb, n, batch, tol, t, stream));
+    }
+    EXPM_TRY(hipEventSynchronize(ds->summary_ready));
+    const int smax = ds->host_summary[0];
+    *warning_out = warning_from_flags(ds->host_summary[1]);
+    if (!select_only) {
+        for (int q = 1; q <= smax; ++q) {
+            Bracket br(stream, EXPM_KCLASS_GEMM, 0.0, 0.0);
+            EXPM_TRY(launch_baseline_round(B.gb, n, batch, kBaselineSquareRound + q, dtype, wt, false, stream));
+        }
+    }
+    *rounds_out = terms + (select_only ? 0 : smax);
+    return EXPM_OK;
+}
+
 constexpr int kModeCached = 0;   // workspace from the cached block (allocated and grown on demand)
 constexpr int kModeStatic = 1;   // workspace in the static scratch array: no allocation of any kind
 
@@ -479,7 +528,6 @@ int expm_impl(const void *A, int n, int batch, int dtype, double tol, int scheme
     if (rc != EXPM_OK) return rc;
     if (n == 0 || batch == 0) return EXPM_OK;
     if (out == nullptr) return EXPM_ERR_INVALID_ARG;
-    if (scheme == EXPM_SCHEME_BASELINE && !small_path_supported(n, dtype)) return EXPM_ERR_UNSUPPORTED;
     {
         const size_t bytes = (size_t)batch * n * n * (dtype == EXPM_DTYPE_F64 ? 8 : 4);
         const uintptr_t a0 = (uintptr_t)A, o0 = (uintptr_t)out;
@@ -529,8 +577,16 @@ int expm_impl(const void *A, int n, int batch, int dtype, double tol, int scheme
         return EXPM_OK;
     }
     bool on_device = mode == kModeStatic || capturing;
-    if (!on_device) on_device = env_plan() == 1 || (env_plan() == 0 && plan_on_device_by_default(n, batch));
     int rounds = 0, warning = EXPM_OK;
+    if (scheme == EXPM_SCHEME_BASELINE) {
+        // its squarings have no cap, so their number has to be read back: not under capture
+        if (on_device) return EXPM_ERR_UNSUPPORTED;
+        rc = run_baseline_rounds(ds, B, n, batch, dtype, tol, stream, false, &rounds, &warning);
+        if (rc != EXPM_OK) return rc;
+        remember(n, batch, dtype, rounds, 0, scheme, dev, stream, true, B.gb.info, B.gb.summary);
+        return warning;
+    }
+    if (!on_device) on_device = env_plan() == 1 || (env_plan() == 0 && plan_on_device_by_default(n, batch));
     rc = run_rounds(ds, B, n, batch, dtype, tol, scheme, stream, on_device, &rounds, &warning);
     if (rc != EXPM_OK) return rc;
     remember(n, batch, dtype, rounds, 0, scheme, dev, stream, !capturing, B.gb.info, B.gb.summary);
@@ -583,7 +639,6 @@ int expm_select_ex(const void *A, int n, int batch, int dtype, double tol, int s
     int rc = check_args(A, n, batch, dtype, tol);
     if (rc != EXPM_OK) return rc;
     if (batch > 0 && (m_out == nullptr || s_out == nullptr)) return EXPM_ERR_INVALID_ARG;
-    if (scheme == EXPM_SCHEME_BASELINE && !small_path_supported(n, dtype)) return EXPM_ERR_UNSUPPORTED;
     if (batch == 0) return EXPM_OK;
     if (n == 0) {
         for (int b = 0; b < batch; ++b) { m_out[b] = 0; s_out[b] = 0; }
@@ -605,6 +660,12 @@ int expm_select_ex(const void *A, int n, int batch, int dtype, double tol, int s
     if (small_path_supported(n, dtype)) {
         EXPM_TRY(launch_small(A, nullptr, n, batch, dtype, tol, 1, scheme, B.gb.norm_inf, B.gb.info, stream));
         remember(n, batch, dtype, 0, 1, scheme, dev, stream, true, B.gb.info, B.gb.summary);
+    } else if (scheme == EXPM_SCHEME_BASELINE) {
+        // the degree is only known once the term loop has run: all of it, without the squarings
+        int rounds = 0, warning = EXPM_OK;
+        rc = run_baseline_rounds(ds, B, n, batch, dtype, tol, stream, true, &rounds, &warning);
+        if (rc != EXPM_OK) return rc;
+        remember(n, batch, dtype, rounds, 0, scheme, dev, stream, true, B.gb.info, B.gb.summary);
     } else {
         rc = run_selection_general(ds, B, n, batch, dtype, tol, scheme, stream, false);
         if (rc != EXPM_OK) return rc;

@@ -72,6 +72,7 @@ struct GemmParams {
     int scheme;  // kSchemeSastre or kSchemePS
     int norm_inf;  // power rounds: emit row abs-sums (infinity-norm) instead of column abs-sums
     const int *active;  // rounds planned on the device: &summary[2], active[r] = matrices still active in round r; else null
+    int keep;    // baseline scheme: accumulate X in the workspace even when s = 0 (only (m, s) are wanted)
 };
 
 __device__ __forceinline__ double pow2neg(int e)
@@ -177,6 +178,30 @@ __global__ __launch_bounds__(kThreads, WT == 4 ? 2 : 4) void gemm_round_kernel(G
         st.R = BUF_W;
         st.acc_scale = (T)1; st.nsrc = 0; st.nout = 1;
         st.dst[0] = p.round == 0 ? BUF_W2 : (p.round == -1 ? BUF_W3 : BUF_W4);
+    } else if (p.scheme == kSchemeBaseline) {
+        // Algorithm 1: matrices in input order; a matrix leaves the term rounds when the norm of its last term
+        // has dropped to the tolerance, and takes part in squaring q only while q <= s
+        b = slot;
+        const MatInfo mi = p.info[b];
+        if (p.round <= kBaselineSquareRound) {
+            if (!mi.len) {
+                if (p.round == 1) {
+                    // never entered the loop (zero matrix, or ||A|| <= eps): X = I; not finite: NaN
+                    int tm0, tn0;
+                    tile_position(tile, p.tiles, tm0, tn0);
+                    T *O = reinterpret_cast<T *>(p.base[(mi.s <= 0 && !p.keep) ? BUF_OUT : BUF_T2]) + (size_t)b * n * n;
+                    for (int e = tid; e < BM * BN; e += kThreads) {
+                        const int r = tm0 * BM + e / BN, c = tn0 * BN + e % BN;
+                        if (r < n && c < n)
+                            O[(size_t)r * n + c] = mi.m < 0 ? (T)__longlong_as_double(0x7ff8000000000000LL) : (r == c ? (T)1 : (T)0);
+                    }
+                }
+                return;
+            }
+        } else if (p.round - kBaselineSquareRound > mi.s) {
+            return;
+        }
+        st = build_step_baseline<T>(mi.s, p.round, p.keep != 0);
     } else {
         b = p.order[p.slot0 + slot * p.slot_step];
         const MatInfo mi = p.info[b];
@@ -518,7 +543,12 @@ __global__ __launch_bounds__(kThreads, WT == 4 ? 2 : 4) void gemm_round_kernel(G
             }
     }
 
-    if (p.round <= 0 && !p.norm_inf) {
+    // norm partials of the product just formed: the power rounds (W^2, W^3, W^4) and the term rounds of the baseline
+    // (whose term Y = acc_scale * product decides whether the matrix goes on)
+    const bool term_round = p.scheme == kSchemeBaseline && p.round >= 1 && p.round <= kBaselineSquareRound;
+    const bool emit_norm = p.round <= 0 || term_round;
+    const T nscale = term_round ? st.acc_scale : (T)1;
+    if (emit_norm && !p.norm_inf) {
         // column abs-sums of this tile of the new power, in double: 16*WT rows per wave, then the two wave rows
         double *red = reinterpret_cast<double *>(smem);  // [2][BN]; the k-loop's last barrier has passed
 #pragma unroll
@@ -527,7 +557,7 @@ __global__ __launch_bounds__(kThreads, WT == 4 ? 2 : 4) void gemm_round_kernel(G
 #pragma unroll
             for (int ti = 0; ti < WT; ++ti)
 #pragma unroll
-                for (int v = 0; v < 4; ++v) cs += fabs((double)acc[ti][tj][v]);
+                for (int v = 0; v < 4; ++v) cs += fabs((double)(nscale * acc[ti][tj][v]));
             cs += __shfl_xor(cs, 16);
             cs += __shfl_xor(cs, 32);
             if (lg == 0) red[wm * BN + wn * 16 * WT + (tj / G) * 16 * G + G * lj + tj % G] = cs;
@@ -537,7 +567,7 @@ __global__ __launch_bounds__(kThreads, WT == 4 ? 2 : 4) void gemm_round_kernel(G
             const int col = col0 + tid;
             if (col < n) p.colpart[((size_t)b * p.tiles + tm) * n + col] = red[tid] + red[BN + tid];
         }
-    } else if (p.round <= 0) {
+    } else if (emit_norm) {
         // row abs-sums of this tile (infinity-norm): 16*WT columns per wave, then the two wave columns;
         // partials are indexed by tile column: colpart[b][tn][row]
         double *red = reinterpret_cast<double *>(smem);  // [2][BM]
@@ -547,7 +577,7 @@ __global__ __launch_bounds__(kThreads, WT == 4 ? 2 : 4) void gemm_round_kernel(G
             for (int v = 0; v < 4; ++v) {
                 double rs = 0.0;
 #pragma unroll
-                for (int tj = 0; tj < WT; ++tj) rs += fabs((double)acc[ti][tj][v]);
+                for (int tj = 0; tj < WT; ++tj) rs += fabs((double)(nscale * acc[ti][tj][v]));
                 rs += __shfl_xor(rs, 1);
                 rs += __shfl_xor(rs, 2);
                 rs += __shfl_xor(rs, 4);
@@ -690,6 +720,56 @@ __global__ __launch_bounds__(1024) void select_plan_kernel(const double *__restr
     }
 }
 
+// ---- baseline (Algorithm 1): who is still in the term loop ------------------------------------------------------
+// One workgroup.  term = 0: from ||W|| (per-block maxima in p1) the scaling s = smallest s >= 0 with ||W|| / 2^s < 1/2
+// and whether the first term A = W / 2^s exceeds the tolerance; summary[0] = largest s, summary[1] = OR of flags.
+// term = t >= 1: from the norm of the term Y_(t+1) that round t formed (maxima in p2) whether the matrix goes on.
+__global__ __launch_bounds__(1024) void baseline_decide_kernel(const double *__restrict__ p1, const double *__restrict__ p2,
+                                                               int nblk, MatInfo *__restrict__ info, int *__restrict__ summary,
+                                                               int batch, double eps, int term)
+{
+    __shared__ int smax, flags_or;
+    const int tid = threadIdx.x;
+    if (tid == 0) { smax = 0; flags_or = 0; }
+    __syncthreads();
+    for (int b = tid; b < batch; b += blockDim.x) {
+        const double *pq = (term == 0 ? p1 : p2) + (size_t)b * nblk;
+        double nrm = 0.0;
+        bool bad = false;
+        for (int k = 0; k < nblk; ++k) {
+            const double x = pq[k];
+            if (!(x <= 1.7976931348623157e308)) bad = true;
+            nrm = x > nrm ? x : nrm;
+        }
+        if (term == 0) {
+            MatInfo mi;
+            mi.m = 0; mi.s = 0; mi.len = 0; mi.flags = 0;
+            if (bad) {
+                mi.m = -1; mi.s = -1; mi.flags = 1;
+            } else {
+                double t = nrm;
+                while (!(t < 0.5)) { t *= 0.5; ++mi.s; }   // exact halvings: t = ||W|| / 2^s
+                if (t > eps) { mi.m = 1; mi.len = 1; }
+            }
+            info[b] = mi;
+            atomicMax(&smax, mi.s);
+            if (mi.flags) atomicOr(&flags_or, mi.flags);
+        } else {
+            MatInfo mi = info[b];
+            if (mi.len) {
+                if (!bad && nrm > eps) mi.m = term + 1;
+                else mi.len = 0;
+                info[b] = mi;
+            }
+        }
+    }
+    __syncthreads();
+    if (term == 0 && tid == 0) {
+        summary[0] = smax;
+        summary[1] = flags_or;
+    }
+}
+
 // ---- operand preparation --------------------------------------------------------------------------
 // Orders 0, 1, 2 are finished here (no further product); orders 4, 8, 15+ get the operands of their
 // first chain round.  One workgroup handles 1024 consecutive elements of one matrix.
@@ -782,6 +862,7 @@ GemmParams make_params(const GeneralBuffers &gb, int n, int round, int matrices,
     p.slot0 = 0;
     p.slot_step = 1;
     p.active = nullptr;
+    p.keep = 0;
     return p;
 }
 
@@ -933,6 +1014,23 @@ hipError_t launch_chain_round(const GeneralBuffers &gb, int n, int active, int r
     p.slot_step = step;
     if (device_plan) p.active = gb.summary + 2;   // `active` is then the whole batch
     return launch_gemm(p, dtype, wt, gb.ptr_align16, stream);
+}
+
+// Round of the baseline (Algorithm 1) over the whole batch: term round `round` >= 1, or squaring
+// round - kBaselineSquareRound; workgroups of matrices that do not take part leave at once.
+hipError_t launch_baseline_round(const GeneralBuffers &gb, int n, int batch, int round, int dtype, int wt,
+                                 bool keep_in_workspace, hipStream_t stream)
+{
+    GemmParams p = make_params(gb, n, round, batch, wt, kSchemeBaseline);
+    p.keep = keep_in_workspace ? 1 : 0;
+    return launch_gemm(p, dtype, wt, gb.ptr_align16, stream);
+}
+
+hipError_t launch_baseline_decide(const GeneralBuffers &gb, int n, int batch, double eps, int term, hipStream_t stream)
+{
+    hipLaunchKernelGGL(baseline_decide_kernel, dim3(1), dim3(1024), 0, stream, gb.n1, gb.n2, general_colblocks(n), gb.info,
+                       gb.summary, batch, eps, term);
+    return hipGetLastError();
 }
 
 }  // namespace expmk

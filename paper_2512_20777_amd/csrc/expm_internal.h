@@ -255,7 +255,7 @@ template <> struct Mfma<float> {
 // ---------------------------------------------------------------------------------------------
 constexpr int kSchemeSastre = 0;  // evaluation formulas of Sec. 3.1 with Algorithm 4
 constexpr int kSchemePS = 1;      // Paterson-Stockmeyer with Algorithm 3
-constexpr int kSchemeBaseline = 2;  // the paper's comparison baseline (its Algorithm 1); fused path only
+constexpr int kSchemeBaseline = 2;  // the paper's comparison baseline (its Algorithm 1)
 constexpr int kSchemePhi = 3;       // core series of the low-rank variant, sum_i V^i/(i+1)!, no scaling; fused path only
 
 enum Buf : int { BUF_W = 0, BUF_W2 = 1, BUF_T0 = 2, BUF_T1 = 3, BUF_T2 = 4, BUF_T3 = 5, BUF_T4 = 6, BUF_T5 = 7,
@@ -390,6 +390,70 @@ __device__ __forceinline__ Step<T> build_step_ps(int m, int s, int r)
 }
 
 // ---------------------------------------------------------------------------------------------
+// Baseline of the paper's comparison (its Algorithm 1, Sec. 2.2) on the round-based path.  Per matrix:
+// s = smallest s >= 0 with ||W|| / 2^s < 1/2, A = W / 2^s; X = I, Y_1 = A; while ||Y_t|| > eps: X += Y_t,
+// Y_(t+1) = A Y_t / (t + 1); then s squarings of X.  Term round t (t = 1, 2, ...) of a matrix that is still in the
+// loop does both halves of one pass through the loop body: X += Y_t in its epilogue and the product for Y_(t+1),
+// whose norm (taken in the same epilogue) decides whether the matrix takes part in round t + 1.
+// MatInfo of this scheme: m = terms added once the coming round has run, s, len = 1 while the matrix is in the loop.
+// Buffers: Y_1 is W itself (scaled through the coefficients), Y_t for t >= 2 alternates between T0 and T1, X
+// accumulates in OUT when s = 0 and in T2 otherwise (or always in T2 when only (m, s) are wanted); squaring q reads
+// T2 (q odd) or T3 (q even) and writes the other one, the last squaring writes OUT.
+// ---------------------------------------------------------------------------------------------
+constexpr int kBaselineSquareRound = 64;  // round numbers above this are squarings: q = round - kBaselineSquareRound
+
+// Term rounds that can be needed at tolerance eps: ||Y_t|| <= (1/2)^t / t! (the norm of A is below 1/2), so the loop
+// has ended once that bound is at most eps; two spare rounds for norms that rounding carries past the bound.
+__host__ __device__ inline int baseline_max_terms(double eps)
+{
+    double bound = 0.5;
+    int t = 1;
+    while (bound > eps && t < 60) {
+        ++t;
+        bound *= 0.5 / (double)t;
+    }
+    return t + 1;
+}
+
+template <typename T>
+__device__ __forceinline__ Step<T> build_step_baseline(int s, int round, bool keep_in_workspace)
+{
+    Step<T> st;
+    st.acc_scale = (T)1; st.nsrc = 0; st.nout = 1;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        st.src[i] = BUF_W; st.g[i] = (T)0; st.dst[i] = BUF_OUT; st.a[i] = (T)1; st.d[i] = (T)0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) st.b[i][j] = (T)0;
+    }
+    const int xbuf = (s == 0 && !keep_in_workspace) ? BUF_OUT : BUF_T2;
+    if (round <= kBaselineSquareRound) {
+        const int t = round;
+        const double sg = __longlong_as_double((long long)(1023 - s) << 52);   // 2^-s
+        st.L = BUF_W;
+        st.R = t == 1 ? BUF_W : ((t & 1) ? BUF_T0 : BUF_T1);                // Y_t
+        // Y_(t+1) = A Y_t / (t+1) = 2^-s (W Y_t) / (t+1);  Y_1 = 2^-s W adds one more factor 2^-s in round 1
+        st.acc_scale = (T)((t == 1 ? sg * sg : sg) / (double)(t + 1));
+        st.nout = 2;
+        st.dst[0] = ((t + 1) & 1) ? BUF_T0 : BUF_T1;                          // Y_(t+1)
+        st.dst[1] = xbuf; st.a[1] = (T)0;
+        if (t == 1) {
+            st.nsrc = 1; st.src[0] = BUF_W;
+            st.b[1][0] = (T)sg; st.d[1] = (T)1;                               // X = I + A
+        } else {
+            st.nsrc = 2; st.src[0] = xbuf; st.src[1] = st.R;
+            st.b[1][0] = (T)1; st.b[1][1] = (T)1;                             // X += Y_t
+        }
+    } else {
+        const int q = round - kBaselineSquareRound;                           // squaring q of s
+        const int in = q == 1 ? BUF_T2 : ((q & 1) ? BUF_T2 : BUF_T3);
+        st.L = st.R = in;
+        st.dst[0] = q == s ? BUF_OUT : ((q & 1) ? BUF_T3 : BUF_T2);
+    }
+    return st;
+}
+
+// ---------------------------------------------------------------------------------------------
 // Host-side launchers implemented by the kernel translation units.
 // ---------------------------------------------------------------------------------------------
 struct GeneralBuffers {
@@ -454,5 +518,9 @@ bool first_round_is_self_contained(int n, int scheme);
 hipError_t launch_first_round(const GeneralBuffers &gb, int n, int batch, int dtype, hipStream_t stream);
 hipError_t launch_chain_round(const GeneralBuffers &gb, int n, int active, int round, int dtype, int wt, int scheme,
                               hipStream_t stream, int first = 0, int step = 1, bool device_plan = false);
+// baseline (Algorithm 1) on the round-based path
+hipError_t launch_baseline_round(const GeneralBuffers &gb, int n, int batch, int round, int dtype, int wt,
+                                 bool keep_in_workspace, hipStream_t stream);
+hipError_t launch_baseline_decide(const GeneralBuffers &gb, int n, int batch, double eps, int term, hipStream_t stream);
 
 }  // namespace expmk

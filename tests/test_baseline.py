@@ -109,6 +109,47 @@ def test_gpu_baseline_parity(ex, n, dtype):
 
 
 @pytest.mark.gpu
+@pytest.mark.parametrize("n,batch,dtype,tol", [(129, 6, np.float32, 1e-6), (200, 7, np.float64, 1e-8), (257, 4, np.float64, 2.0 ** -53),
+                                                (384, 4, np.float32, 2.0 ** -24), (515, 3, np.float64, 1e-8),
+                                                (1024, 8, np.float64, 1e-8)])
+def test_gpu_baseline_parity_round_based(ex, n, batch, dtype, tol):
+    """Above the on-chip sizes every term of Algorithm 1 is a product round over the matrices still in the loop."""
+    from paper_2512_20777_amd import workloads
+    a = workloads.random_stack(1300 + n, batch, n, dtype, 0.05, 60.0)
+    a[0] = 0.0                                     # never enters the loop: X = I
+    a[1] *= 1e-20                                  # first term already below the tolerance: X = I as well
+    a[2] *= dtype(40.0) / np.abs(a[2]).sum(axis=0).max()   # norm 40: seven squarings
+    m, s, stats = _run(ex, a, tol, "baseline rounds n=%d" % n, 1e-11 if dtype == np.float64 else 5e-5)
+    assert stats["fused_path"] == 0 and stats["scheme"] == 2
+    assert (m[0], s[0]) == (0, 0) and (m[1], s[1]) == (0, 0) and s[2] == 7
+    assert stats["products"] == int(np.maximum(m - 1, 0).sum() + s.sum())
+
+
+@pytest.mark.gpu
+def test_gpu_baseline_round_based_infinity_norm_and_nonfinite(ex):
+    import torch
+    from oracle import oracle_expm_baseline_batch
+    from paper_2512_20777_amd import workloads
+    a = workloads.random_stack(1400, 5, 160, np.float64, 0.5, 20.0, kind="triu")
+    at = np.ascontiguousarray(np.swapaxes(a, -1, -2))
+    X, info = oracle_expm_baseline_batch(at, 1e-8)            # infinity-norm of W = 1-norm of its transpose
+    d = torch.from_numpy(a).cuda()
+    out, _ = ex.expm(d, 1e-8, scheme=ex.SCHEME_BASELINE, norm=ex.NORM_INF)
+    m, s, _ = ex.expm_select(d, 1e-8, scheme=ex.SCHEME_BASELINE, norm=ex.NORM_INF)
+    got = out.cpu().numpy()
+    for b in range(5):
+        assert (m[b], s[b]) == (info["m"][b], info["s"][b]) or info["near"][b]
+        if (m[b], s[b]) == (info["m"][b], info["s"][b]):
+            assert np.linalg.norm(got[b] - X[b].T) / np.linalg.norm(X[b]) <= 1e-11
+    a[2, 5, 7] = np.inf
+    d = torch.from_numpy(a).cuda()
+    out, st = ex.expm(d, 1e-8, scheme=ex.SCHEME_BASELINE)
+    m, s, st2 = ex.expm_select(d, 1e-8, scheme=ex.SCHEME_BASELINE)
+    assert st == 1 and st2 == 1 and (m[2], s[2]) == (-1, -1) and bool(torch.isnan(out[2]).all())
+    assert bool(torch.isfinite(out[[0, 1, 3, 4]]).all())
+
+
+@pytest.mark.gpu
 def test_gpu_baseline_examples_and_limits(ex):
     import torch
     a = np.stack([12.8 * np.eye(8), np.zeros((8, 8))])
@@ -117,10 +158,19 @@ def test_gpu_baseline_examples_and_limits(ex):
     assert (m[0], s[0]) == (8, 5) and (m[1], s[1]) == (0, 0)       # the paper's worked example (Sec. 4.2)
     out, _ = ex.expm(d, 1e-8, scheme=ex.SCHEME_BASELINE)
     assert torch.equal(out[1], torch.eye(8, dtype=torch.float64, device="cuda"))
+    # above the on-chip sizes the number of squarings is read back: not available under stream capture
     big = torch.zeros(1, 200, 200, dtype=torch.float64, device="cuda")
-    with pytest.raises(ex.ExpmError) as e:
-        ex.expm(big, 1e-8, scheme=ex.SCHEME_BASELINE)
-    assert e.value.status == -5
+    res = torch.empty_like(big)
+    ex.expm(big, 1e-8, out=res, scheme=ex.SCHEME_BASELINE)
+    torch.cuda.synchronize()
+    assert torch.equal(res[0], torch.eye(200, dtype=torch.float64, device="cuda"))
+    lib = ex.load_library()
+    side, graph = torch.cuda.Stream(), torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        res.zero_()
+        status = lib.expm_scheme(big.data_ptr(), 200, 1, ex.DTYPE_F64, 1e-8, ex.SCHEME_BASELINE, res.data_ptr(),
+                                 torch.cuda.current_stream().cuda_stream)
+    assert status == -5
 
 
 @pytest.mark.gpu
