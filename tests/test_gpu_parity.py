@@ -191,8 +191,8 @@ def test_workload_c4_full(ex):
 
 @pytest.mark.parametrize("name", ["C5f64", "C5f32"])
 def test_workload_c5_against_stored_oracle_samples(ex, name, golden_dir):
-    """Full-size 4096x4096 batch: sampled entries of the oracle's result, written beforehand by
-    tests/golden/make_c5_samples.py (the oracle needs about ten minutes per dtype)."""
+    """Full-size 4096x4096 batch against what tests/golden/make_c5_samples.py stored of the oracle's result (the
+    oracle needs about a quarter of an hour per dtype): sampled entries, and a digest of every 128x128 tile."""
     import torch
     from paper_2512_20777_amd import workloads
     w = workloads.WORKLOADS[name]
@@ -224,6 +224,27 @@ def test_workload_c5_against_stored_oracle_samples(ex, name, golden_dir):
               % (name, b, m[b], s[b], err, abs(fro - g["fro"][b]) / g["fro"][b]), flush=True)
         assert err <= gate, (name, b, err)
         assert abs(fro - g["fro"][b]) <= gate * g["fro"][b]
+        # Every 128 x 128 tile, not only the sampled entries: its Frobenius norm, a bilinear probe u_I^T X_IJ v_J with
+        # stored vectors of +-1 (an error E in the tile moves it by about ||E||_F), and all row and column sums in
+        # blocks of 128 (same reasoning), each against the oracle's stored value, scaled by the tile's (block's) norm.
+        x = out[b].double()
+        t = w.n // 128
+        ref_fro = torch.from_numpy(g["tile_fro"][b]).cuda()
+        u = torch.from_numpy(g["probe_u"].astype(np.float64)).cuda()
+        v = torch.from_numpy(g["probe_v"].astype(np.float64)).cuda()
+        fro_t = (x * x).reshape(t, 128, t, 128).sum(dim=(1, 3)).sqrt()
+        probe = ((u[:, None] * x) * v[None, :]).reshape(t, 128, t, 128).sum(dim=(1, 3))
+        d_fro = ((fro_t - ref_fro).abs() / ref_fro).max()
+        d_probe = ((probe - torch.from_numpy(g["tile_probe"][b]).cuda()).abs() / ref_fro).max()
+        row_fro = (ref_fro ** 2).sum(dim=1).sqrt()      # norm of each block of 128 rows
+        col_fro = (ref_fro ** 2).sum(dim=0).sqrt()
+        d_row = ((x.sum(dim=1) - torch.from_numpy(g["rowsum"][b]).cuda()).reshape(t, 128).norm(dim=1) / row_fro).max()
+        d_col = ((x.sum(dim=0) - torch.from_numpy(g["colsum"][b]).cuda()).reshape(t, 128).norm(dim=1) / col_fro).max()
+        print("      per tile: norm rel diff %.3e, probe diff / tile norm %.3e; row-block sums %.3e, column-block sums %.3e"
+              % (float(d_fro), float(d_probe), float(d_row), float(d_col)), flush=True)
+        assert float(d_fro) <= gate, (name, b, float(d_fro))
+        assert float(d_probe) <= 8 * gate and float(d_row) <= 8 * gate and float(d_col) <= 8 * gate, (name, b)
+        del x
 
 
 # ------------------------------------------------------------------------------------------------
