@@ -180,7 +180,9 @@ int expm_ex(const void *A, int n, int batch, int dtype, double tol, int scheme, 
  * guaranteed.  A non-finite V gives m = -1 and an all-NaN result (EXPM_WARN_NONFINITE).
  *
  *   A1     DEVICE, const, [batch][n][t] row-major.      A2   DEVICE, const, [batch][t][n] row-major.
- *   n, t   >= 0; t <= 128 (fp32) / 96 (fp64), otherwise EXPM_ERR_UNSUPPORTED; batch <= 65535.
+ *   n, t   >= 0; batch <= 65535.  Up to t = 128 (fp32) / 96 (fp64) the core series is evaluated on chip in one
+ *          kernel; a larger core goes through the product rounds of expm() (powers V^2..V^4 for the whole batch,
+ *          one round per Horner step; the call then waits once on the stream like expm(), unless captured).
  *   tol    as for expm_select.                           out  DEVICE, [batch][n][n], must not overlap A1, A2.
  *   m_out  HOST, int32[batch].
  * expm_lowrank_select is synchronous (null stream) and returns the warning; expm_lowrank is asynchronous on

@@ -308,8 +308,9 @@ int run_selection_general(DeviceState *ds, const Bound &B, int n, int batch, int
         Bracket br(stream, EXPM_KCLASS_NORM, 0.0, 0.0);
         EXPM_TRY(launch_colmax(B.gb, n, batch, 2, (n + 32 * wt0 - 1) / (32 * wt0), stream));
     }
-    if (scheme == kSchemePS) {
+    if (scheme == kSchemePS || scheme == kSchemePhi) {
         // Algorithm 3 looks at ||W^3|| and ||W^4|| as well: W^3 = W^2 W, W^4 = W^3 W for the whole batch
+        // (the core series of the low-rank variant only needs the powers, formed here for all orders alike)
         for (int which = 3; which <= 4; ++which) {
             {
                 Bracket br(stream, EXPM_KCLASS_GEMM, 2.0 * nn * n * batch, 2.0 * batch * nn * w);
@@ -715,7 +716,7 @@ LowrankLayout make_lowrank_layout(int n, int t, int batch, int dtype)
 {
     LowrankLayout L{};
     const size_t w = dtype == EXPM_DTYPE_F64 ? 8 : 4;
-    L.ctl = make_layout(t, batch, dtype);  // t is within the fused path: control records only
+    L.ctl = make_layout(t, batch, dtype);  // control records; for a core beyond the on-chip sizes also the matrix stacks
     size_t off = align_up(L.ctl.total, 256);
     L.V = off;   off = align_up(off + (size_t)batch * t * t * w, 256);
     L.vslices = rect_gemm_slices(t, t, n, batch, dtype == EXPM_DTYPE_F64 ? 1 : 0);
@@ -738,13 +739,19 @@ int check_lowrank_args(const void *A1, const void *A2, int n, int t, int batch, 
     if (!(tol == tol) || tol < 0.0) return EXPM_ERR_TOLERANCE;
     if (tol == 0.0) tol = u;
     if (tol < u) return EXPM_ERR_TOLERANCE;
-    if (t > 0 && !small_path_supported(t, dtype)) return EXPM_ERR_UNSUPPORTED;  // the core series runs on chip
+    if (t > 0 && !small_path_supported(t, dtype)) {
+        // the core series runs on the round-based path: the limits of that path, for t x t matrices
+        const double tiles = (double)((t + 31) / 32);
+        if ((double)batch * tiles * tiles > 2.0e9) return EXPM_ERR_INVALID_ARG;
+    }
     return EXPM_OK;
 }
 
-// V = A2 A1 and, unless select_only, Phi = series of V; leaves the per-matrix records (m, flags) in the workspace
-int run_lowrank_core(unsigned char *base, const void *A1, const void *A2, int n, int t, int batch, int dtype, double tol,
-                     int select_only, const LowrankLayout &L, hipStream_t stream)
+// V = A2 A1 and, unless select_only, Phi = series of V; leaves the per-matrix records (m, flags) in the workspace.
+// A core that fits a compute unit's LDS is evaluated on chip by the fused kernel; a larger one goes through the
+// round-based path (powers V^2..V^4 for the whole batch, top Horner block, one product round per Horner step).
+int run_lowrank_core(DeviceState *ds, unsigned char *base, const void *A1, const void *A2, int n, int t, int batch, int dtype,
+                     double tol, int select_only, bool plan_on_device, const LowrankLayout &L, hipStream_t stream)
 {
     const double w = dtype == EXPM_DTYPE_F64 ? 8.0 : 4.0;
     {
@@ -752,17 +759,24 @@ int run_lowrank_core(unsigned char *base, const void *A1, const void *A2, int n,
         EXPM_TRY(launch_rect_gemm(A2, A1, base + L.V, t, t, n, n, t, t, (size_t)t * n, (size_t)n * t, (size_t)t * t, batch,
                                   dtype, 0, L.vslices, L.vslices > 1 ? base + L.Vpart : nullptr, stream));
     }
-    Bracket br(stream, EXPM_KCLASS_FUSED, 0.0, 2.0 * batch * (double)t * t * w);
-    EXPM_TRY(launch_small(base + L.V, base + L.Phi, t, batch, dtype, tol, select_only, kSchemePhi, 0,
-                          reinterpret_cast<MatInfo *>(base + L.ctl.info), stream));
-    return EXPM_OK;
+    if (small_path_supported(t, dtype)) {
+        Bracket br(stream, EXPM_KCLASS_FUSED, 0.0, 2.0 * batch * (double)t * t * w);
+        EXPM_TRY(launch_small(base + L.V, base + L.Phi, t, batch, dtype, tol, select_only, kSchemePhi, 0,
+                              reinterpret_cast<MatInfo *>(base + L.ctl.info), stream));
+        return EXPM_OK;
+    }
+    const Bound B = bind(base, base + L.V, base + L.Phi, t, batch, dtype, EXPM_NORM_ONE);
+    if (select_only) return run_selection_general(ds, B, t, batch, dtype, tol, kSchemePhi, stream, false);
+    int rounds = 0, warning = EXPM_OK;
+    return run_rounds(ds, B, t, batch, dtype, tol, kSchemePhi, stream, plan_on_device, &rounds, &warning);
 }
 
 void remember_lowrank(unsigned char *base, int t, int batch, int dtype, int dev, hipStream_t stream, bool usable,
                       const LowrankLayout &L)
 {
-    remember(t, batch, dtype, 0, 1, kSchemePhi, dev, stream, usable, reinterpret_cast<MatInfo *>(base + L.ctl.info),
-             reinterpret_cast<int *>(base + L.ctl.summary));
+    const int fused = small_path_supported(t, dtype) ? 1 : 0;
+    remember(t, batch, dtype, fused ? 0 : -1, fused, kSchemePhi, dev, stream, usable,
+             reinterpret_cast<MatInfo *>(base + L.ctl.info), reinterpret_cast<int *>(base + L.ctl.summary));
 }
 
 }  // namespace
@@ -790,7 +804,7 @@ int expm_lowrank_select(const void *A1, const void *A2, int n, int t, int batch,
     if (rc != EXPM_OK) return rc;
     g_brackets = false;
     unsigned char *base = static_cast<unsigned char *>(ds->dev);
-    rc = run_lowrank_core(base, A1, A2, n, t, batch, dtype, tol, 1, L, stream);
+    rc = run_lowrank_core(ds, base, A1, A2, n, t, batch, dtype, tol, 1, false, L, stream);
     if (rc != EXPM_OK) return rc;
     remember_lowrank(base, t, batch, dtype, dev, stream, true, L);
     g_host_info.resize((size_t)batch);
@@ -835,7 +849,8 @@ int expm_lowrank(const void *A1, const void *A2, int n, int t, int batch, int dt
     g_brackets = g_profile && !capturing;
     unsigned char *base = static_cast<unsigned char *>(ds->dev);
     if (t > 0) {
-        rc = run_lowrank_core(base, A1, A2, n, t, batch, dtype, tol, 0, L, stream);
+        const bool on_device = capturing || env_plan() == 1;
+        rc = run_lowrank_core(ds, base, A1, A2, n, t, batch, dtype, tol, 0, on_device, L, stream);
         if (rc != EXPM_OK) return rc;
         // U = A1 Phi
         Bracket br(stream, EXPM_KCLASS_GEMM, 2.0 * n * (double)t * t * batch, (2.0 * n * t + (double)t * t) * batch * (double)w);

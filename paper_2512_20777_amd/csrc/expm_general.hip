@@ -69,7 +69,7 @@ struct GemmParams {
     int round;   // <= 0 power round (0: W2 = W*W, -1: W3 = W2*W, -2: W4 = W3*W), >= 1 chain round
     int total;   // workgroups in the grid
     int slot0, slot_step;  // chain rounds: this launch covers the sorted matrices slot0, slot0 + slot_step, ...
-    int scheme;  // kSchemeSastre or kSchemePS
+    int scheme;  // kSchemeSastre, kSchemePS, kSchemeBaseline or kSchemePhi
     int norm_inf;  // power rounds: emit row abs-sums (infinity-norm) instead of column abs-sums
     const int *active;  // rounds planned on the device: &summary[2], active[r] = matrices still active in round r; else null
     int keep;    // baseline scheme: accumulate X in the workspace even when s = 0 (only (m, s) are wanted)
@@ -244,7 +244,8 @@ __global__ __launch_bounds__(kThreads, WT == 4 ? 2 : 4) void gemm_round_kernel(G
             }
         } else {
             if (p.round > mi.len) return;
-            st = p.scheme == kSchemePS ? build_step_ps<T>(mi.m, mi.s, p.round) : build_step<T>(mi.m, mi.s, p.round);
+            st = p.scheme == kSchemePS ? build_step_ps<T>(mi.m, mi.s, p.round)
+                 : (p.scheme == kSchemePhi ? build_step_ps<T>(mi.m, 0, p.round, 1) : build_step<T>(mi.m, mi.s, p.round));
         }
     }
     int tm, tn;
@@ -677,7 +678,7 @@ __global__ __launch_bounds__(1024) void select_plan_kernel(const double *__restr
     for (int b = tid; b < batch; b += blockDim.x) {
         double nrm[4] = {0.0, 0.0, 0.0, 0.0};
         bool bad = false;
-        const int used = scheme == kSchemePS ? 4 : 2;
+        const int used = scheme == kSchemePS ? 4 : (scheme == kSchemePhi ? 1 : 2);
         for (int q = 0; q < used; ++q) {
             const double *pq = q == 0 ? p1 : (q == 1 ? p2 : (q == 2 ? p3 : p4));
             for (int k = 0; k < nblk; ++k) {
@@ -692,6 +693,11 @@ __global__ __launch_bounds__(1024) void select_plan_kernel(const double *__restr
             bool need_more;
             select_ps_order_scaling(nrm, 4, eps, mi.m, mi.s, mi.flags, need_more);
             mi.len = chain_length_ps(mi.m, mi.s);
+        } else if (scheme == kSchemePhi) {
+            // core series of the low-rank variant: the order follows from the norm alone, no scaling
+            select_lowrank_order(nrm[0], eps, mi.m, mi.flags);
+            mi.s = mi.m < 0 ? -1 : 0;
+            mi.len = mi.m < 0 ? 0 : chain_length_ps(mi.m, 0);
         } else {
             select_order_scaling(nrm[0], nrm[1], eps, mi.m, mi.s, mi.flags);
             mi.len = chain_length(mi.m, mi.s);
@@ -786,11 +792,25 @@ __global__ __launch_bounds__(256) void prepare_kernel(GemmParams p)
     T *T0 = reinterpret_cast<T *>(p.base[BUF_T0]) + moff;
     T *T1 = reinterpret_cast<T *>(p.base[BUF_T1]) + moff;
     const double sg = mi.s > 0 ? pow2neg(mi.s) : 1.0, sg2 = mi.s > 0 ? pow2neg(2 * mi.s) : 1.0;
-    if (p.scheme == kSchemePS && mi.m >= 4) {
+    const int shift = p.scheme == kSchemePhi ? 1 : 0;   // coefficients 1/(i+1)! instead of 1/i!
+    if (shift && mi.m >= 0 && mi.m <= 2) {
+        // core series of the low-rank variant, orders without a further product: I, I + V/2, I + V/2 + V^2/6
+        for (int e = 0; e < 4; ++e) {
+            const size_t idx = ((size_t)blockIdx.x * 4 + e) * 256 + threadIdx.x;
+            if (idx >= nn) break;
+            const int row = (int)(idx / n), col = (int)(idx - (size_t)row * n);
+            T o = row == col ? (T)1 : (T)0;
+            if (mi.m >= 1) o += W[idx] / (T)2;
+            if (mi.m == 2) o += W2[idx] / (T)6;
+            O[idx] = o;
+        }
+        return;
+    }
+    if ((p.scheme == kSchemePS || shift) && mi.m >= 4) {
         // top block of the Paterson-Stockmeyer form: H0 = sum_{r=0..j} c_{(k-1)j+r} A^r  ->  T0
         const T *W3 = reinterpret_cast<const T *>(p.base[BUF_W3]) + moff;
         const T *W4 = reinterpret_cast<const T *>(p.base[BUF_W4]) + moff;
-        const int j = ps_j(mi.m), base = (ps_k(mi.m) - 1) * j;
+        const int j = ps_j(mi.m), base = (ps_k(mi.m) - 1) * j + shift;
         const T h0 = (T)inv_factorial(base), h1 = (T)(inv_factorial(base + 1) * sg),
                 h2 = (T)(inv_factorial(base + 2) * sg2), h3 = j >= 3 ? (T)(inv_factorial(base + 3) * sg2 * sg) : (T)0,
                 h4 = j >= 4 ? (T)(inv_factorial(base + 4) * sg2 * sg2) : (T)0;

@@ -256,7 +256,7 @@ template <> struct Mfma<float> {
 constexpr int kSchemeSastre = 0;  // evaluation formulas of Sec. 3.1 with Algorithm 4
 constexpr int kSchemePS = 1;      // Paterson-Stockmeyer with Algorithm 3
 constexpr int kSchemeBaseline = 2;  // the paper's comparison baseline (its Algorithm 1)
-constexpr int kSchemePhi = 3;       // core series of the low-rank variant, sum_i V^i/(i+1)!, no scaling; fused path only
+constexpr int kSchemePhi = 3;       // core series of the low-rank variant, sum_i V^i/(i+1)!, no scaling
 
 enum Buf : int { BUF_W = 0, BUF_W2 = 1, BUF_T0 = 2, BUF_T1 = 3, BUF_T2 = 4, BUF_T3 = 5, BUF_T4 = 6, BUF_T5 = 7,
                  BUF_OUT = 8, BUF_COUNT = 9,
@@ -349,8 +349,10 @@ __device__ __forceinline__ Step<T> build_step(int m, int s, int r)
 // Round r (1-based, after the power products) of the Paterson-Stockmeyer chain for order m = j*k and
 // scaling s.  Horner in A^j:  H <- H * A^j + sum_{r'<j} c_{qj+r'} A^r',  q = k-2 .. 0, with the top block
 // prepared beforehand in T0; intermediate H ping-pongs between T0 and T2; then the squarings.
+// `shift` = 0: coefficients 1/i! (the Taylor polynomial); 1: coefficients 1/(i+1)! (core series of the low-rank
+// variant, Sec. 2.2, which is never scaled: s = 0).
 template <typename T>
-__device__ __forceinline__ Step<T> build_step_ps(int m, int s, int r)
+__device__ __forceinline__ Step<T> build_step_ps(int m, int s, int r, int shift = 0)
 {
     Step<T> st;
     st.L = BUF_T0; st.R = BUF_W2; st.acc_scale = (T)1; st.nsrc = 0; st.nout = 1;
@@ -373,13 +375,13 @@ __device__ __forceinline__ Step<T> build_step_ps(int m, int s, int r)
         st.acc_scale = (T)sgj;                       // H * A^j = sigma^j (H * W^j)
         st.nsrc = j - 1;                             // A, A^2, A^3 as far as the block reaches
         st.src[0] = BUF_W; st.src[1] = BUF_W2; st.src[2] = BUF_W3;
-        st.g[0] = (T)(inv_factorial(q * j + 1) * sg);
-        if (j >= 3) st.g[1] = (T)(inv_factorial(q * j + 2) * sg * sg);
-        if (j >= 4) st.g[2] = (T)(inv_factorial(q * j + 3) * sg * sg * sg);
+        st.g[0] = (T)(inv_factorial(q * j + 1 + shift) * sg);
+        if (j >= 3) st.g[1] = (T)(inv_factorial(q * j + 2 + shift) * sg * sg);
+        if (j >= 4) st.g[2] = (T)(inv_factorial(q * j + 3 + shift) * sg * sg * sg);
         st.nout = 1;
         st.dst[0] = r == horner ? poly_dst : ((r & 1) ? BUF_T2 : BUF_T0);
         st.a[0] = (T)1;
-        st.d[0] = (T)inv_factorial(q * j);
+        st.d[0] = (T)inv_factorial(q * j + shift);
     } else {
         const int q = r - horner;  // squaring q of s
         const bool cur_is_out = (((s - (q - 1)) & 1) == 0);

@@ -194,6 +194,23 @@ def test_gpu_lowrank_parity_many_tiles(ex, n, t, batch, dtype):
 
 
 @pytest.mark.gpu
+@pytest.mark.parametrize("n,t,batch,dtype", [(300, 129, 5, np.float32), (256, 160, 4, np.float64), (400, 200, 9, np.float32),
+                                             (97, 97, 6, np.float64), (1100, 256, 3, np.float64)])
+def test_gpu_lowrank_core_beyond_the_on_chip_sizes(ex, n, t, batch, dtype):
+    """t above 128 (fp32) / 96 (fp64): the core series runs as product rounds (powers, top Horner block, one round per
+    Horner step) instead of in the fused kernel; every order of the series occurs, also the ones without a product."""
+    u = U32 if dtype == np.float32 else U64
+    hi = 2.0 if dtype == np.float32 else 0.9
+    a1, a2 = _stack(6000 + n + t, batch + 3, n, t, dtype, 1e-3, hi)
+    a1[0] = 0.0                                              # V = 0: order 0, e^W = I exactly
+    a1[1] *= 1e-6; a2[1] *= 1e-6                             # ||V|| ~ 1e-12 or less: order 1
+    a1[2] *= 3e-3; a2[2] *= 3e-3                             # ||V|| ~ 1e-5: order 2
+    m, st, stats, info = _check_lowrank(ex, a1, a2, u, "lowrank large core n=%d t=%d" % (n, t))
+    assert st == 0 and stats["fused_path"] == 0 and stats["n"] == t and m[0] == 0
+    assert len(set(int(x) for x in m)) >= 4
+
+
+@pytest.mark.gpu
 def test_gpu_lowrank_user_tolerance_orders_and_flags(ex):
     """eps = 1e-8 as in the paper's experiments: all seven orders occur; a norm beyond the reach of order 16 is
     flagged, not silently wrong; a pair with A2 A1 = 0 is exact with order 0; non-finite input gives NaN."""
@@ -225,9 +242,6 @@ def test_gpu_lowrank_argument_checks_and_empty_shapes(ex):
     import torch
     a1 = torch.zeros(2, 10, 200, dtype=torch.float32, device="cuda")
     a2 = torch.zeros(2, 200, 10, dtype=torch.float32, device="cuda")
-    with pytest.raises(ex.ExpmError) as e:
-        ex.expm_lowrank(a1, a2)                              # t = 200 is beyond the on-chip core
-    assert e.value.status == -5
     with pytest.raises(ex.ExpmError):
         ex.expm_lowrank(a1, a2.transpose(1, 2).contiguous())
     b1 = torch.zeros(3, 5, 0, dtype=torch.float64, device="cuda")
