@@ -219,10 +219,10 @@ def run_lowrank_workload(name, steps, warmup, with_cpu):
 
 def cpu_baseline(name, a, tol, workloads, ms=None):
     """The oracle, as it stands, on the host cores, timed in this run: the whole batch when that takes seconds; for the
-    4096 x 4096 workloads (whose whole run takes more than ten minutes) one of its products, timed here, times the
-    number of products the oracle spends on the batch.  `ms` = (m, s) per matrix as the device selected them."""
+    4096 x 4096 workloads (whose whole run takes minutes) the first matrix of the batch, scaled by the number of
+    products the oracle spends on the whole batch.  `ms` = (m, s) per matrix as the device selected them."""
     import numpy as np
-    from oracle import oracle_expm_batch, oracle_matmul_threads
+    from oracle import oracle_expm_batch
     w = workloads.WORKLOADS[name]
     if name.startswith("C5"):
         # The oracle forms W^2 for the selection, then sums the series term by term from A (m - 1 products, one more
@@ -230,15 +230,17 @@ def cpu_baseline(name, a, tol, workloads, ms=None):
         # 2 n^3 flops, everything else is O(n^2).
         m, sc = ms
         counts = [1 + max(int(mm) - 1, 0) + (1 if mm == 15 else 0) + int(ss) for mm, ss in zip(m, sc)]
-        x = np.ascontiguousarray(a[-1], dtype=np.float64)
+        # sample: the whole oracle on the first matrix of the batch (the one with the smallest norm, no squarings)
         t0 = time.perf_counter()
-        _, used = oracle_matmul_threads(x, x)
+        _, info = oracle_expm_batch(a[:1], tol)
         sec = time.perf_counter() - t0
-        total = sec * sum(counts)
-        res = {"value": w.batch / total, "unit": "matrices/s", "cores": int(used), "kind": "oracle",
-               "sample": "one 4096^3 product of the oracle (W*W of the last matrix, rows over %d threads) timed in this "
-                         "run: %.2f s; times the %d products the oracle spends on this batch (1 + (m-1) + [m=15] + s "
-                         "per matrix) = %.0f s for the batch, extrapolated" % (used, sec, sum(counts), total)}
+        used = int(info["threads"])
+        own = 1 + max(int(info["m"][0]) - 1, 0) + (1 if info["m"][0] == 15 else 0) + int(info["s"][0])
+        total = sec * sum(counts) / own
+        res = {"value": w.batch / total, "unit": "matrices/s", "cores": used, "kind": "oracle",
+               "sample": "the oracle on the first matrix of the batch, timed in this run: %.1f s for its %d products of "
+                         "4096^3 on %d threads; the batch costs the oracle %d products (1 + (m-1) + [m=15] + s per "
+                         "matrix), i.e. %.0f s, extrapolated by product count" % (sec, own, used, sum(counts), total)}
         path = os.path.join(ROOT, "tests", "golden", "c5_samples_%s.npz" % w.dtype)
         if os.path.exists(path):
             g = np.load(path)
