@@ -720,9 +720,33 @@ __global__ __launch_bounds__(1024) void select_plan_kernel(const double *__restr
         summary[2] = batch;
     }
     __syncthreads();
-    for (int b = tid; b < batch; b += blockDim.x) {
-        const int len = info[b].len;
-        order[atomicAdd(&cursor[len], 1)] = b;
+    // Stable placement (matrices of one chain length keep their input order, so that the plan and with it every
+    // launch's work list is the same from run to run): chunks of blockDim matrices in ascending order; inside a
+    // chunk a matrix's rank among those of its length comes from wave ballots and per-wave counts.
+    __shared__ int wave_count[16][kMaxRounds + 1];
+    const int lane = tid & 63, wave = tid >> 6, waves = blockDim.x >> 6;
+    for (int base = 0; base < batch; base += blockDim.x) {
+        const int b = base + tid;
+        const int len = b < batch ? info[b].len : -1;
+        int my_rank = 0;
+        for (int L = 0; L <= kMaxRounds; ++L) {
+            const unsigned long long mask = __ballot(len == L);
+            if (len == L) my_rank = __popcll(mask & ((1ull << lane) - 1ull));
+            if (lane == 0) wave_count[wave][L] = __popcll(mask);
+        }
+        __syncthreads();
+        if (len >= 0) {
+            int pos = cursor[len] + my_rank;
+            for (int w = 0; w < wave; ++w) pos += wave_count[w][len];
+            order[pos] = b;
+        }
+        __syncthreads();
+        if (tid <= kMaxRounds) {
+            int add = 0;
+            for (int w = 0; w < waves; ++w) add += wave_count[w][tid];
+            cursor[tid] += add;
+        }
+        __syncthreads();
     }
 }
 
