@@ -148,7 +148,14 @@ __global__ __launch_bounds__(kThreads, WT == 4 ? 2 : 4) void gemm_round_kernel(G
     constexpr int STAGE = stage_bytes<T, WT>(DMA);
     constexpr int kRot = 16 * (int)sizeof(T);     // rotation of a B row per k-group, in bytes
     static_assert(BK / BSTEP == WT && BM / 32 == WT, "WT staged vectors per thread and operand");
-    extern __shared__ __align__(16) unsigned char smem[];
+    // Two LDS stages.  With the direct-to-LDS loads they are two separate LDS objects and the k-loop below is written
+    // out for both parities: the compiler orders every LDS read behind all outstanding loads into an LDS object the
+    // read may alias, so with one array holding both stages a wave waited for the next k-block's loads before it
+    // read the current k-block's fragments, and nothing was fetched while it multiplied.
+    extern __shared__ __align__(16) unsigned char smem_dyn[];
+    __shared__ __align__(16) unsigned char stage_even[DMA ? STAGE : 16];
+    __shared__ __align__(16) unsigned char stage_odd[DMA ? STAGE : 16];
+    unsigned char *const smem = DMA ? stage_even : smem_dyn;   // stage 0: prologue, and scratch of the epilogue
 
     const int n = p.n;
     const int tid = threadIdx.x;
@@ -366,9 +373,7 @@ __global__ __launch_bounds__(kThreads, WT == 4 ? 2 : 4) void gemm_round_kernel(G
     const int b_rd = BM * APitch + (lg * KQ) * BPitch;
     const int b_rc0 = (wn * 16 * WT + G * lj + 16 * lg) * (int)sizeof(T);  // rotated column of this lane's first group, before wrap
 
-    for (int kb = 0; kb < kblocks; ++kb) {
-        const unsigned char *cur = smem + (kb & 1) * STAGE;
-        unsigned char *nxt = smem + ((kb + 1) & 1) * STAGE;
+    auto kstep = [&](const unsigned char *cur, unsigned char *nxt, int kb) __attribute__((always_inline)) {
         const bool more = kb + 1 < kblocks;
         if (more) {
             const int k0 = (kb + 1) * BK;
@@ -455,6 +460,16 @@ __global__ __launch_bounds__(kThreads, WT == 4 ? 2 : 4) void gemm_round_kernel(G
             }
         }
         __syncthreads();
+    };
+    if constexpr (DMA) {
+        int kb = 0;
+        for (; kb + 1 < kblocks; kb += 2) {
+            kstep(stage_even, stage_odd, kb);
+            kstep(stage_odd, stage_even, kb + 1);
+        }
+        if (kb < kblocks) kstep(stage_even, stage_odd, kb);
+    } else {
+        for (int kb = 0; kb < kblocks; ++kb) kstep(smem + (kb & 1) * STAGE, smem + ((kb + 1) & 1) * STAGE, kb);
     }
 
     // ---- epilogue -----------------------------------------------------------------------------
@@ -879,6 +894,12 @@ __global__ __launch_bounds__(256) void prepare_kernel(GemmParams p)
 template <typename T, int WT, int ALIGNED, bool FIRST = false>
 hipError_t launch_gemm_t(const GemmParams &p, hipStream_t stream)
 {
+    // the direct-to-LDS variants hold their two stages in static LDS (at most 64 KB); the others in dynamic LDS
+    if constexpr (ALIGNED == kAccessDma) {
+        static_assert(2 * stage_bytes<T, WT>(true) <= 65536, "static LDS of the direct-to-LDS variants");
+        hipLaunchKernelGGL((gemm_round_kernel<T, WT, ALIGNED, FIRST>), dim3(p.total), dim3(kThreads), 0, stream, p);
+        return hipGetLastError();
+    }
     static PerDeviceOnce lds_limit;
     const int lds = 2 * stage_bytes<T, WT>(ALIGNED == kAccessDma);
     hipError_t e = lds_limit([] {

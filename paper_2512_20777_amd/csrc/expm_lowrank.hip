@@ -96,7 +96,13 @@ __global__ __launch_bounds__(kRectThreads, WT == 4 ? 2 : 4) void rect_gemm_kerne
     constexpr int STAGE = rect_stage_bytes<T, WT>(DMA);
     constexpr int kRot = 16 * (int)sizeof(T);
     static_assert(BK / BSTEP == WT, "WT staged vectors per thread and operand");
-    extern __shared__ __align__(16) unsigned char smem[];
+    // Two LDS stages; with the direct-to-LDS loads two separate LDS objects and a loop written out for both parities
+    // (an LDS read is ordered behind every outstanding load into an LDS object it may alias: with one array for both
+    // stages nothing would be fetched while a wave multiplies).
+    extern __shared__ __align__(16) unsigned char smem_dyn[];
+    __shared__ __align__(16) unsigned char stage_even[DMA ? STAGE : 16];
+    __shared__ __align__(16) unsigned char stage_odd[DMA ? STAGE : 16];
+    unsigned char *const smem = DMA ? stage_even : smem_dyn;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1, lj = lane & 15, lg = lane >> 4;
@@ -141,7 +147,7 @@ __global__ __launch_bounds__(kRectThreads, WT == 4 ? 2 : 4) void rect_gemm_kerne
     const int steps = nct * kblocks;
     V ra[WT], rb[WT];
     int f_kb = 0, f_ct = ct0;  // step the next fetch belongs to
-    auto fetch = [&]() {
+    auto fetch = [&]() __attribute__((always_inline)) {
         const int k0 = kbeg + f_kb * BK, col0 = f_ct * BN;
 #pragma unroll
         for (int i = 0; i < WT; ++i) {
@@ -153,7 +159,7 @@ __global__ __launch_bounds__(kRectThreads, WT == 4 ? 2 : 4) void rect_gemm_kerne
             ++f_ct;
         }
     };
-    auto stash = [&](unsigned char *stage) {
+    auto stash = [&](unsigned char *stage) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < WT; ++i) {
             *reinterpret_cast<V *>(stage + a_lds + 32 * i * APitch) = ra[i];
@@ -164,7 +170,7 @@ __global__ __launch_bounds__(kRectThreads, WT == 4 ? 2 : 4) void rect_gemm_kerne
     // k-vector v' ^ ((row / 2) & 7) of the row; right tile: slot (row, v') holds column vector v' - rot(row).
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);
     const int a_kv = ((tid & 7) ^ ((tid >> 4) & 7)) * VN;
-    auto dma = [&](unsigned char *stage) {
+    auto dma = [&](unsigned char *stage) __attribute__((always_inline)) {
         if constexpr (DMA) {
             const int k0 = kbeg + f_kb * BK, col0 = f_ct * BN;
 #pragma unroll
@@ -192,7 +198,7 @@ __global__ __launch_bounds__(kRectThreads, WT == 4 ? 2 : 4) void rect_gemm_kerne
         if constexpr (DMA) __builtin_amdgcn_s_waitcnt(0x0F70);
     };
     // lane holds C[row0 + wm*16*WT + 16*ti + Mfma<T>::row(lg, v)][ct*BN + wn*16*WT + 16*tj + lj]
-    auto store_tile = [&](int ct) {
+    auto store_tile = [&](int ct) __attribute__((always_inline)) {
         int er = row0 + wm * 16 * WT;
         asm volatile("" : "+v"(er));  // offsets are formed here, next to the stores, not kept in registers across the loop
         int ec = wn * 16 * WT + lj;
@@ -251,7 +257,7 @@ __global__ __launch_bounds__(kRectThreads, WT == 4 ? 2 : 4) void rect_gemm_kerne
     const int b_rd = BM * APitch + (lg * KQ) * BPitch + lj * (int)sizeof(T);
     const int b_rc0 = (wn * 16 * WT + 16 * lg) * (int)sizeof(T);
 
-    auto multiply = [&](const unsigned char *cur) {
+    auto multiply = [&](const unsigned char *cur) __attribute__((always_inline)) {
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
             V af[WT];
@@ -275,9 +281,7 @@ __global__ __launch_bounds__(kRectThreads, WT == 4 ? 2 : 4) void rect_gemm_kerne
     };
 
     int c_kb = 0, c_ct = ct0;  // step being multiplied
-    for (int s = 0; s < steps; ++s) {
-        const unsigned char *cur = smem + (s & 1) * STAGE;
-        unsigned char *nxt = smem + ((s + 1) & 1) * STAGE;
+    auto step = [&](const unsigned char *cur, unsigned char *nxt, int s) __attribute__((always_inline)) {
         const bool more = s + 1 < steps;
         if (c_kb == 0 && s > 0) {
             store_tile(c_ct - 1);
@@ -297,6 +301,16 @@ __global__ __launch_bounds__(kRectThreads, WT == 4 ? 2 : 4) void rect_gemm_kerne
             c_kb = 0;
             ++c_ct;
         }
+    };
+    if constexpr (DMA) {
+        int s = 0;
+        for (; s + 1 < steps; s += 2) {
+            step(stage_even, stage_odd, s);
+            step(stage_odd, stage_even, s + 1);
+        }
+        if (s < steps) step(stage_even, stage_odd, s);
+    } else {
+        for (int s = 0; s < steps; ++s) step(smem + (s & 1) * STAGE, smem + ((s + 1) & 1) * STAGE, s);
     }
     store_tile(ct0 + nct - 1);
 }
@@ -317,6 +331,12 @@ template <typename T, int WT, int MODE>
 hipError_t launch_rect_v(const RectParams &p, dim3 grid, hipStream_t stream)
 {
     const int lds = 2 * rect_stage_bytes<T, WT>(MODE == kRectDma);
+    if constexpr (MODE == kRectDma) {
+        // the direct-to-LDS variant holds its two stages in static LDS
+        static_assert(2 * rect_stage_bytes<T, WT>(true) <= 65536, "static LDS of the direct-to-LDS variant");
+        hipLaunchKernelGGL((rect_gemm_kernel<T, WT, MODE>), grid, dim3(kRectThreads), 0, stream, p);
+        return hipGetLastError();
+    }
     static PerDeviceOnce lds_limit;  // the 128x128 tile needs more dynamic LDS than the default limit
     hipError_t e = lds_limit([] {
         return hipFuncSetAttribute(reinterpret_cast<const void *>(rect_gemm_kernel<T, WT, MODE>),
