@@ -80,7 +80,8 @@ def test_lowrank_replayed_from_a_graph_equals_eager(ex):
 
 @pytest.mark.gpu
 @pytest.mark.parametrize("n,batch,dtype,scheme", [(200, 5, np.float64, 0), (512, 3, np.float64, 0), (136, 6, np.float32, 0),
-                                                  (200, 4, np.float64, 1)])
+                                                  (200, 4, np.float64, 1), (512, 32, np.float64, 0), (1024, 8, np.float64, 0),
+                                                  (1152, 8, np.float32, 1)])
 def test_round_based_expm_replayed_from_a_graph_equals_eager(ex, n, batch, dtype, scheme):
     """Above the on-chip sizes the number of product rounds depends on the data.  Under capture the rounds are planned
     on the device (every possible round is recorded, workgroups of rounds a matrix does not need leave at once), so one
