@@ -129,7 +129,7 @@ __device__ __forceinline__ typename Tile<T>::vec_t load_vec(const T *__restrict_
 // while its tile is staged (one more vector per staged vector, combined just before the LDS store), and the
 // workgroups of matrices of order <= 2, which need no product, write their tile of the result and leave.
 template <typename T, int WT, int ALIGNED, bool FIRST = false>
-__global__ __launch_bounds__(kThreads, WT == 4 ? 2 : 4) void gemm_round_kernel(GemmParams p)
+__global__ __launch_bounds__(kThreads, WT == 4 ? 2 : (FIRST && ALIGNED == kAccessDma ? 3 : 4)) void gemm_round_kernel(GemmParams p)
 {
     using V = typename Tile<T>::vec_t;
     using acc_t = typename Mfma<T>::acc_t;
@@ -142,10 +142,15 @@ __global__ __launch_bounds__(kThreads, WT == 4 ? 2 : 4) void gemm_round_kernel(G
     constexpr int G = col_group<T, WT>();         // neighbouring columns per lane (see col_group)
     using GV = typename VecOfN<T, G>::type;
     constexpr bool DMA = ALIGNED == kAccessDma;
-    constexpr bool kPipe = DMA && sizeof(T) == 4;  // fragment reads one k-step ahead (fp32: registers to spare; fp64 loses)
-    static_assert(!(DMA && FIRST), "the combined operand of the first round is formed in registers");
+    constexpr bool kPipe = DMA && !FIRST && sizeof(T) == 4;  // fragment reads one k-step ahead (fp32: registers to spare; fp64 loses)
     constexpr int APitch = DMA ? 128 : kAPitch;   // DMA: unpadded rows, 16-byte slots swizzled instead
-    constexpr int STAGE = stage_bytes<T, WT>(DMA);
+    // FIRST with the direct-to-LDS loads: a third tile per stage holds the part of W that goes into the combined
+    // operand, in the layout of the side it belongs to (both tiles are 32*WT*128 bytes); the combination is formed
+    // from the two fragments, on their way from LDS into the MFMAs.
+    constexpr bool kFragComb = DMA && FIRST;
+    constexpr int kXOff = BM * APitch + BK * BPitch;   // offset of that tile in a stage
+    static_assert(!kFragComb || BM * APitch == BK * BPitch, "left and right tiles of equal size");
+    constexpr int STAGE = stage_bytes<T, WT>(DMA) + (kFragComb ? BM * APitch : 0);
     constexpr int kRot = 16 * (int)sizeof(T);     // rotation of a B row per k-group, in bytes
     static_assert(BK / BSTEP == WT && BM / 32 == WT, "WT staged vectors per thread and operand");
     // Two LDS stages.  With the direct-to-LDS loads they are two separate LDS objects and the k-loop below is written
@@ -335,6 +340,15 @@ __global__ __launch_bounds__(kThreads, WT == 4 ? 2 : 4) void gemm_round_kernel(G
                                                  (__attribute__((address_space(3))) void *)(stage + BM * APitch +
                                                                                            (i * 256 + wave_u * 64) * 16),
                                                  16, 0, 0);
+                if constexpr (kFragComb) {
+                    // W at the positions of the side that is combined (uniform over the workgroup)
+                    const T *gx = comb_a ? Xp + (size_t)(row0 + a_row0 + 32 * i) * n + k0 + a_kv
+                                         : Xp + (size_t)(k0 + brow) * n + col0 + bv * VN;
+                    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)gx,
+                                                     (__attribute__((address_space(3))) void *)(stage + kXOff +
+                                                                                               (i * 256 + wave_u * 64) * 16),
+                                                     16, 0, 0);
+                }
             }
         }
     };
@@ -429,14 +443,38 @@ __global__ __launch_bounds__(kThreads, WT == 4 ? 2 : 4) void gemm_round_kernel(G
 #pragma unroll
                 for (int ti = 0; ti < WT; ++ti)
                     af[ti] = *reinterpret_cast<const V *>(cur + (h ? a_rd1 : a_rd0) + ti * 16 * APitch);
+                if constexpr (kFragComb) {
+                    if (comb_a) {
+                        // left factor of T_4: xa * (A^2 fragment) + xb * (A fragment) + I; the lane holds row
+                        // (wave's first row + 16 ti + lj) at the k values lg * KQ + h * VN + q of this k-block
+#pragma unroll
+                        for (int ti = 0; ti < WT; ++ti) {
+                            const V ax = *reinterpret_cast<const V *>(cur + kXOff + (h ? a_rd1 : a_rd0) + ti * 16 * APitch);
+                            const int row = row0 + wm * 16 * WT + 16 * ti + lj;
+#pragma unroll
+                            for (int q = 0; q < VN; ++q) {
+                                T v = xa * reinterpret_cast<const T *>(&af[ti])[q] + xb * reinterpret_cast<const T *>(&ax)[q];
+                                if (row == kb * BK + lg * KQ + h * VN + q) v += (T)1;
+                                reinterpret_cast<T *>(&af[ti])[q] = v;
+                            }
+                        }
+                    }
+                }
 #pragma unroll
                 for (int q = 0; q < VN; ++q) {
                     const int kk = h * VN + q;
                     T bf[WT];
 #pragma unroll
                     for (int g = 0; g < WT / G; ++g) {
-                        const GV x = *reinterpret_cast<const GV *>(cur + b_rd + kk * BPitch +
-                                                                    ((b_rc0 + g * 16 * G * (int)sizeof(T)) & (BPitch - 1)));
+                        const int off = b_rd + kk * BPitch + ((b_rc0 + g * 16 * G * (int)sizeof(T)) & (BPitch - 1));
+                        GV x = *reinterpret_cast<const GV *>(cur + off);
+                        if constexpr (kFragComb) {
+                            if (!comb_a) {
+                                // right factor of y02: xa * (W^2 fragment) + xb * (W fragment)
+                                const GV xw = *reinterpret_cast<const GV *>(cur + kXOff - BM * APitch + off);
+                                x = xa * x + xb * xw;
+                            }
+                        }
 #pragma unroll
                         for (int e = 0; e < G; ++e) bf[g * G + e] = x[e];
                     }
@@ -896,7 +934,8 @@ hipError_t launch_gemm_t(const GemmParams &p, hipStream_t stream)
 {
     // the direct-to-LDS variants hold their two stages in static LDS (at most 64 KB); the others in dynamic LDS
     if constexpr (ALIGNED == kAccessDma) {
-        static_assert(2 * stage_bytes<T, WT>(true) <= 65536, "static LDS of the direct-to-LDS variants");
+        static_assert(2 * (stage_bytes<T, WT>(true) + (FIRST ? 32 * WT * 128 : 0)) <= 65536,
+                      "static LDS of the direct-to-LDS variants");
         hipLaunchKernelGGL((gemm_round_kernel<T, WT, ALIGNED, FIRST>), dim3(p.total), dim3(kThreads), 0, stream, p);
         return hipGetLastError();
     }
@@ -958,7 +997,7 @@ hipError_t launch_gemm(const GemmParams &p, int dtype, int wt, bool ptr_align16,
 template <typename T>
 hipError_t launch_gemm_first(const GemmParams &p, bool aligned, hipStream_t stream)
 {
-    if (aligned && p.n % 64 == 0 && p.n % Tile<T>::BK == 0) return launch_gemm_t<T, 2, kAccessFull, true>(p, stream);
+    if (aligned && p.n % 64 == 0 && p.n % Tile<T>::BK == 0) return launch_gemm_t<T, 2, kAccessDma, true>(p, stream);
     return aligned ? launch_gemm_t<T, 2, kAccessVector, true>(p, stream) : launch_gemm_t<T, 2, kAccessScalar, true>(p, stream);
 }
 

@@ -155,15 +155,17 @@ def test_rounds_128_tiles_straight_to_lds_whole_matrices(ex, n, dtype):
     assert stats["fused_path"] == 0 and int(s.max()) >= 1
 
 
+@pytest.mark.parametrize("n", [144, 192])
 @pytest.mark.parametrize("dtype", [np.float64, np.float32])
-def test_rounds_all_orders_in_one_batch(ex, dtype):
-    """Norms from 1e-10 to 300 in one batch: every order 0,1,2,4,8,15+ and several scalings at once."""
+def test_rounds_all_orders_in_one_batch(ex, dtype, n):
+    """Norms from 1e-10 to 300 in one batch: every order 0,1,2,4,8,15+ and several scalings at once.  n = 192: full
+    64x64 tiles, where the first chain round fetches straight into LDS and forms its combined operand (the right
+    factor of y02, the left factor of T_4) from the fragments; n = 144: the same round with register staging."""
     from paper_2512_20777_amd import workloads
-    n = 144
     norms = np.array([0.0, 1e-10, 1e-9, 1e-6, 1e-5, 1e-3, 5e-3, 0.03, 0.1, 0.4, 1.0, 3.0, 10.0, 40.0, 120.0, 300.0])
     a = workloads.random_stack(77, len(norms), n, np.float64, 1.0, 1.0)
     a = (a * norms[:, None, None]).astype(dtype)
-    _, m, s, info, stats = _run_and_check(ex, a, label="all-orders %s" % np.dtype(dtype).name)
+    _, m, s, info, stats = _run_and_check(ex, a, label="all-orders n=%d %s" % (n, np.dtype(dtype).name))
     assert set(np.unique(m)) >= {0, 1, 2, 4, 8, 15}
     assert stats["hist_m"][0] == 1
     assert stats["rounds"] == 3 + int(s.max())
