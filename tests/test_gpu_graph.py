@@ -153,3 +153,34 @@ def test_calls_on_two_streams_are_ordered_not_corrupted(ex):
         ex.expm(a, out=oa, stream=s1)
         torch.cuda.synchronize()
         assert torch.equal(oa, ra) and torch.equal(ob, rb), rep
+
+
+@pytest.mark.gpu
+def test_calls_from_two_host_threads_are_serialised(ex):
+    """Entry points take a lock and order calls on different streams: two threads hammering the library with
+    different inputs each get their own results."""
+    import threading
+    import torch
+    a = torch.from_numpy(workloads.random_stack(9800, 5, 192, np.float64, 0.5, 40.0)).cuda()
+    b = torch.from_numpy(workloads.random_stack(9801, 64, 48, np.float32, 0.5, 40.0)).cuda()
+    ra = ex.expm(a)[0].clone()
+    rb = ex.expm(b)[0].clone()
+    torch.cuda.synchronize()
+    errors = []
+
+    def worker(x, ref, stream):
+        try:
+            out = torch.empty_like(x)
+            for _ in range(6):
+                out.zero_()
+                ex.expm(x, out=out, stream=stream)
+                stream.synchronize()
+                if not torch.equal(out, ref):
+                    errors.append("mismatch for shape %s" % (tuple(x.shape),))
+        except Exception as e:  # noqa: BLE001 - reported below
+            errors.append(repr(e))
+
+    t1 = threading.Thread(target=worker, args=(a, ra, torch.cuda.Stream()))
+    t2 = threading.Thread(target=worker, args=(b, rb, torch.cuda.Stream()))
+    t1.start(); t2.start(); t1.join(); t2.join()
+    assert not errors, errors
