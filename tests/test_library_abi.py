@@ -158,6 +158,78 @@ def test_selection_rule_of_the_library_matches_the_oracle_on_a_grid_of_norms(tmp
     assert seen_s >= set(range(0, 21))   # every scaling up to the cap was exercised
 
 
+def test_cap_warning_only_when_more_than_twenty_squarings_are_asked_for(tmp_path):
+    """Algorithm 4 clips s to 20 only when more is asked for: a scaling of exactly 20 meets the tolerance and is not
+    flagged; 21 and beyond (or an error term that is not finite) are clipped to 20 and flagged.  Expected values from
+    an exact rational evaluation of the two error terms."""
+    import math
+    import subprocess
+    from fractions import Fraction
+    src = tmp_path / "cap.cpp"
+    src.write_text(
+        '#include <cstdio>\n#include <cstdlib>\n#include <cmath>\n'
+        '#define __host__\n#define __device__\n#define __forceinline__ inline\n'
+        + _selection_source() +
+        'int main() { double n1, n2, eps; while (scanf("%lf %lf %lf", &n1, &n2, &eps) == 3) {'
+        ' int m, s, f; expmk::select_order_scaling(n1, n2, eps, m, s, f); printf("%d %d %d\\n", m, s, f); } return 0; }\n')
+    exe = tmp_path / "cap"
+    subprocess.run(["g++", "-O1", "-o", str(exe), str(src)], check=True)
+    c1 = Fraction(4.018761610201036e-4)
+    d16 = abs(Fraction(1, math.factorial(16)) - c1 ** 4)
+
+    def exact(n1, n2, eps):
+        e1 = d16 * Fraction(n2) ** 8
+        e2 = Fraction(n2) ** 8 * Fraction(n1) / math.factorial(17)
+        s = 0
+        while e1 > Fraction(eps) * 2 ** (16 * s) or e2 > Fraction(eps) * 2 ** (17 * s):
+            s += 1
+        return s
+
+    cases = []
+    for eps in (2.0 ** -53, 1e-8):
+        x20 = (eps * 2.0 ** (16 * 20) / float(d16)) ** (1.0 / 16.0)      # E1 = eps 2^(16 20) for W = x I
+        for f in (0.5, 0.97, 1 - 1e-4, 1 + 1e-4, 1.05, 2.0, 1e3):
+            cases.append((x20 * f, (x20 * f) ** 2, eps))
+    cases.append((1e200, 1e300, 2.0 ** -53))                               # n2^8 overflows: not finite
+    out = subprocess.run([str(exe)], input="".join("%r %r %r\n" % c for c in cases), capture_output=True, text=True,
+                         check=True)
+    got = [tuple(int(x) for x in ln.split()) for ln in out.stdout.splitlines()]
+    seen = set()
+    for (n1, n2, eps), (m, s, flag) in zip(cases[:-1], got[:-1]):
+        want = exact(n1, n2, eps)
+        assert m == 15 and s == min(want, 20), (n1, eps, s, want)
+        assert flag == (2 if want > 20 else 0), (n1, eps, s, want, flag)
+        seen.add(min(want, 21))
+    assert {20, 21} <= seen and min(seen) < 20
+    assert got[-1] == (15, 20, 2)
+
+
+def test_term_rounds_enqueued_for_the_baseline_cover_the_tolerance(tmp_path):
+    """Rounds the baseline (Algorithm 1) enqueues above the on-chip sizes: ||Y_t|| <= (1/2)^t / t!, so once that
+    bound is at most eps no further term can be added; checked in exact rationals."""
+    import math
+    import subprocess
+    from fractions import Fraction
+    text = open(os.path.join(ROOT, "paper_2512_20777_amd", "csrc", "expm_internal.h")).read()
+    a = text.index("__host__ __device__ inline int baseline_max_terms(double eps)")
+    b = text.index("template <typename T>", a)
+    src = tmp_path / "terms.cpp"
+    src.write_text('#include <cstdio>\n#define __host__\n#define __device__\n' + text[a:b] +
+                   'int main() { double e; while (scanf("%lf", &e) == 1) printf("%d\\n", baseline_max_terms(e)); return 0; }\n')
+    exe = tmp_path / "terms"
+    subprocess.run(["g++", "-O1", "-o", str(exe), str(src)], check=True)
+    eps_list = [2.0 ** -53, 2.0 ** -24, 1e-8, 1e-3, 0.2]   # tolerances below the fp64 unit roundoff are rejected earlier
+    out = subprocess.run([str(exe)], input="".join("%r\n" % e for e in eps_list), capture_output=True, text=True, check=True)
+    got = [int(x) for x in out.stdout.split()]
+    for eps, rounds in zip(eps_list, got):
+        t = 1
+        while Fraction(1, 2) ** t / math.factorial(t) > Fraction(eps):
+            t += 1
+        # term t is never added, so t - 1 rounds do the work; the library keeps two spare
+        assert t - 1 <= rounds <= t + 2, (eps, t, rounds)
+    assert got[0] > got[2] > got[4]
+
+
 def test_paterson_stockmeyer_selection_of_the_library_matches_the_oracle(tmp_path):
     """Same check for the selection of the Paterson-Stockmeyer variant (four power norms)."""
     import subprocess
