@@ -157,9 +157,14 @@ __global__ __launch_bounds__(kThreads, WT == 4 ? 2 : (FIRST && ALIGNED == kAcces
     // out for both parities: the compiler orders every LDS read behind all outstanding loads into an LDS object the
     // read may alias, so with one array holding both stages a wave waited for the next k-block's loads before it
     // read the current k-block's fragments, and nothing was fetched while it multiplied.
+    // The 32 x 32 tiles (a few workgroups per compute unit, launches of small batches and the tails of chains) wait
+    // for memory most of the time with one k-block in flight; they keep three in flight in a ring of four stages.
+    constexpr bool kRing = DMA && WT == 1;
     extern __shared__ __align__(16) unsigned char smem_dyn[];
     __shared__ __align__(16) unsigned char stage_even[DMA ? STAGE : 16];
     __shared__ __align__(16) unsigned char stage_odd[DMA ? STAGE : 16];
+    __shared__ __align__(16) unsigned char stage_2[kRing ? STAGE : 16];
+    __shared__ __align__(16) unsigned char stage_3[kRing ? STAGE : 16];
     unsigned char *const smem = DMA ? stage_even : smem_dyn;   // stage 0: prologue, and scratch of the epilogue
 
     const int n = p.n;
@@ -358,10 +363,13 @@ __global__ __launch_bounds__(kThreads, WT == 4 ? 2 : (FIRST && ALIGNED == kAcces
         if constexpr (DMA) __builtin_amdgcn_s_waitcnt(0x0F70);
     };
 
-    // prologue: first k-block into stage 0
+    // prologue: first k-block into stage 0 (the ring of four stages has its own, below)
+    const bool ring = kRing && kblocks >= 3;   // uniform over the launch
     if constexpr (DMA) {
-        dma(0, smem);
-        dma_done();
+        if (!ring) {
+            dma(0, smem);
+            dma_done();
+        }
     } else {
 #pragma unroll
         for (int i = 0; i < WT; ++i) {
@@ -376,7 +384,7 @@ __global__ __launch_bounds__(kThreads, WT == 4 ? 2 : (FIRST && ALIGNED == kAcces
             *reinterpret_cast<V *>(smem + b_wr(i)) = rb[i];
         }
     }
-    __syncthreads();
+    if (!ring) __syncthreads();
 
     // per-lane LDS read offsets (bytes) inside a stage
     //   A: row (wm*16*WT + 16*ti + lj), k values lg*KQ .. lg*KQ+KQ-1  -> two 16-byte reads (h = 0, 1)
@@ -387,21 +395,8 @@ __global__ __launch_bounds__(kThreads, WT == 4 ? 2 : (FIRST && ALIGNED == kAcces
     const int b_rd = BM * APitch + (lg * KQ) * BPitch;
     const int b_rc0 = (wn * 16 * WT + G * lj + 16 * lg) * (int)sizeof(T);  // rotated column of this lane's first group, before wrap
 
-    auto kstep = [&](const unsigned char *cur, unsigned char *nxt, int kb) __attribute__((always_inline)) {
-        const bool more = kb + 1 < kblocks;
-        if (more) {
-            const int k0 = (kb + 1) * BK;
-            if constexpr (DMA) {
-                dma(k0, nxt);
-            } else {
-#pragma unroll
-                for (int i = 0; i < WT; ++i) {
-                    ra[i] = load_vec<T, ALIGNED>(Lp, row0 + a_row0 + 32 * i, k0 + a_col, n);
-                    rb[i] = load_vec<T, ALIGNED>(Rp, k0 + b_row0 + BSTEP * i, col0 + b_col, n);
-                }
-                fetch_x(k0);
-            }
-        }
+    // the products of one staged k-block
+    auto multiply = [&](const unsigned char *cur, int kb) __attribute__((always_inline)) {
         // A fragments: each lane's KQ k-values of a row are two 16-byte halves (h = 0, 1), VN k-steps each.
         if constexpr (kPipe) {
             // Fragment registers in two sets: the reads for k-step kk + 1 (and, at the end of a half, for the next
@@ -487,6 +482,23 @@ __global__ __launch_bounds__(kThreads, WT == 4 ? 2 : (FIRST && ALIGNED == kAcces
                 }
             }
         }
+    };
+    auto kstep = [&](const unsigned char *cur, unsigned char *nxt, int kb) __attribute__((always_inline)) {
+        const bool more = kb + 1 < kblocks;
+        if (more) {
+            const int k0 = (kb + 1) * BK;
+            if constexpr (DMA) {
+                dma(k0, nxt);
+            } else {
+#pragma unroll
+                for (int i = 0; i < WT; ++i) {
+                    ra[i] = load_vec<T, ALIGNED>(Lp, row0 + a_row0 + 32 * i, k0 + a_col, n);
+                    rb[i] = load_vec<T, ALIGNED>(Rp, k0 + b_row0 + BSTEP * i, col0 + b_col, n);
+                }
+                fetch_x(k0);
+            }
+        }
+        multiply(cur, kb);
         if constexpr (DMA) {
             dma_done();
         } else if (more) {
@@ -499,7 +511,57 @@ __global__ __launch_bounds__(kThreads, WT == 4 ? 2 : (FIRST && ALIGNED == kAcces
         }
         __syncthreads();
     };
-    if constexpr (DMA) {
+    // Ring of four stages: k-blocks kb + 1 .. kb + 3 are in flight while k-block kb is multiplied.  A wave's loads
+    // complete in the order it issued them, and the loop holds no other vector memory operation, so "at most two
+    // k-blocks' loads of this wave outstanding" means that its part of k-block kb + 1 has landed; the barrier after
+    // that wait publishes it to the other waves and also says that every wave has finished reading the stage the
+    // next step's loads overwrite.  The waits are counted by hand and the barrier is the bare instruction, because
+    // the fences of __syncthreads() wait for every outstanding load into LDS; the scheduling barriers around it keep
+    // the LDS reads on their side.  The stages are separate LDS objects for the reason given above.
+    constexpr int kGroup = (kFragComb ? 3 : 2) * WT;   // loads per thread and k-block
+    auto ring_barrier = [&]() __attribute__((always_inline)) {
+        __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    auto ring_step = [&](const unsigned char *cur, unsigned char *pre, int kb) __attribute__((always_inline)) {
+        dma((kb + 3) * BK, pre);
+        multiply(cur, kb);
+        __builtin_amdgcn_s_waitcnt(0x0F70 | (2 * kGroup));   // vmcnt: two k-blocks may stay outstanding
+        ring_barrier();
+    };
+    // the last (at most six) k-blocks: loads only while there is a k-block left to fetch, and full waits
+    auto ring_tail = [&](const unsigned char *cur, unsigned char *pre, int kb) __attribute__((always_inline)) {
+        if (kb >= kblocks) return;
+        if (kb + 3 < kblocks) dma((kb + 3) * BK, pre);
+        multiply(cur, kb);
+        __builtin_amdgcn_s_waitcnt(0x0F70);
+        ring_barrier();
+    };
+    if (ring) {
+        if constexpr (kRing) {
+            static_assert(2 * kGroup <= 15, "wait count fits the low bits of the immediate");
+            dma(0, stage_even);
+            dma(BK, stage_odd);
+            dma(2 * BK, stage_2);
+            __builtin_amdgcn_s_waitcnt(0x0F70 | (2 * kGroup));
+            ring_barrier();
+            int kb = 0;
+            for (; kb + 6 < kblocks; kb += 4) {   // every step of these fetches a k-block
+                ring_step(stage_even, stage_3, kb);
+                ring_step(stage_odd, stage_even, kb + 1);
+                ring_step(stage_2, stage_odd, kb + 2);
+                ring_step(stage_3, stage_2, kb + 3);
+            }
+            ring_tail(stage_even, stage_3, kb);
+            ring_tail(stage_odd, stage_even, kb + 1);
+            ring_tail(stage_2, stage_odd, kb + 2);
+            ring_tail(stage_3, stage_2, kb + 3);
+            ring_tail(stage_even, stage_3, kb + 4);
+            ring_tail(stage_odd, stage_even, kb + 5);
+        }
+    } else if constexpr (DMA) {
         int kb = 0;
         for (; kb + 1 < kblocks; kb += 2) {
             kstep(stage_even, stage_odd, kb);
@@ -932,9 +994,10 @@ __global__ __launch_bounds__(256) void prepare_kernel(GemmParams p)
 template <typename T, int WT, int ALIGNED, bool FIRST = false>
 hipError_t launch_gemm_t(const GemmParams &p, hipStream_t stream)
 {
-    // the direct-to-LDS variants hold their two stages in static LDS (at most 64 KB); the others in dynamic LDS
+    // the direct-to-LDS variants hold their stages (two, or the four of the 32x32 tiles' ring) in static LDS (at most
+    // 64 KB); the others in dynamic LDS
     if constexpr (ALIGNED == kAccessDma) {
-        static_assert(2 * (stage_bytes<T, WT>(true) + (FIRST ? 32 * WT * 128 : 0)) <= 65536,
+        static_assert((WT == 1 ? 4 : 2) * (stage_bytes<T, WT>(true) + (FIRST ? 32 * WT * 128 : 0)) <= 65536,
                       "static LDS of the direct-to-LDS variants");
         hipLaunchKernelGGL((gemm_round_kernel<T, WT, ALIGNED, FIRST>), dim3(p.total), dim3(kThreads), 0, stream, p);
         return hipGetLastError();
@@ -993,12 +1056,12 @@ hipError_t launch_gemm(const GemmParams &p, int dtype, int wt, bool ptr_align16,
     return wt == 4 ? launch_gemm_a<float, 4>(p, al, stream) : launch_gemm_a<float, 2>(p, al, stream);
 }
 
-// chain round 1 with the operands formed on the fly (64x64 tiles only)
-template <typename T>
+// chain round 1 with the operands formed on the fly (64x64 tiles, or 32x32 for thin launches)
+template <typename T, int WT>
 hipError_t launch_gemm_first(const GemmParams &p, bool aligned, hipStream_t stream)
 {
-    if (aligned && p.n % 64 == 0 && p.n % Tile<T>::BK == 0) return launch_gemm_t<T, 2, kAccessDma, true>(p, stream);
-    return aligned ? launch_gemm_t<T, 2, kAccessVector, true>(p, stream) : launch_gemm_t<T, 2, kAccessScalar, true>(p, stream);
+    if (aligned && p.n % (32 * WT) == 0 && p.n % Tile<T>::BK == 0) return launch_gemm_t<T, WT, kAccessDma, true>(p, stream);
+    return aligned ? launch_gemm_t<T, WT, kAccessVector, true>(p, stream) : launch_gemm_t<T, WT, kAccessScalar, true>(p, stream);
 }
 
 }  // namespace
@@ -1013,10 +1076,15 @@ bool first_round_is_self_contained(int n, int scheme)
 
 hipError_t launch_first_round(const GeneralBuffers &gb, int n, int batch, int dtype, hipStream_t stream)
 {
-    const GemmParams p = make_params(gb, n, 1, batch, 2, kSchemeSastre);
+    const int wt = choose_tile_shape(n, batch) == 1 ? 1 : 2;
+    const GemmParams p = make_params(gb, n, 1, batch, wt, kSchemeSastre);
     if (p.total <= 0) return hipSuccess;
-    if (dtype == 1) return launch_gemm_first<double>(p, gb.ptr_align16 && n % 2 == 0, stream);
-    return launch_gemm_first<float>(p, gb.ptr_align16 && n % 4 == 0, stream);
+    if (dtype == 1) {
+        const bool al = gb.ptr_align16 && n % 2 == 0;
+        return wt == 1 ? launch_gemm_first<double, 1>(p, al, stream) : launch_gemm_first<double, 2>(p, al, stream);
+    }
+    const bool al = gb.ptr_align16 && n % 4 == 0;
+    return wt == 1 ? launch_gemm_first<float, 1>(p, al, stream) : launch_gemm_first<float, 2>(p, al, stream);
 }
 
 // Tile shape for a round with `matrices` active matrices of order n: 128x128 tiles (WT = 4) for large
@@ -1027,11 +1095,11 @@ hipError_t launch_first_round(const GeneralBuffers &gb, int n, int batch, int dt
 // quarter of the work at roughly 0.9 of the efficiency.
 int choose_tile_shape(int n, int matrices)
 {
-    // debugging aid: EXPM_FORCE_WT=2|4 pins the shape (read once)
+    // debugging aid: EXPM_FORCE_WT=1|2|4 pins the shape (read once)
     static const int forced = [] {
         const char *e = getenv("EXPM_FORCE_WT");
         const int v = e ? atoi(e) : 0;
-        return (v == 2 || v == 4) ? v : 0;
+        return (v == 1 || v == 2 || v == 4) ? v : 0;
     }();
     if (forced) return forced;
     // Thin launches (late rounds with few matrices left, small batches): a compute unit that holds a single workgroup
