@@ -348,6 +348,8 @@ void remember(int n, int batch, int dtype, int rounds, int fused, int scheme, in
     g_last.summary_dev = summary;
 }
 
+constexpr long long kTwoChainTiles = 1024;  // 64 x 64 tiles in round 2 from which the rounds run as two chains
+
 // Profiling aids read once from the environment: EXPM_CHAINS=1 keeps one chain of rounds (a kernel trace then
 // shows launches that do not overlap); EXPM_PLAN=device|host forces where the rounds are planned.
 int env_chain_limit()
@@ -430,8 +432,13 @@ int run_rounds(DeviceState *ds, const Bound &B, int n, int batch, int dtype, dou
     // workgroups towards its end, the other's fills the compute units (a single chain leaves them idle there,
     // 8 % of the call for 32 matrices of 512 x 512).  With the per-class timers on, one chain on the caller's
     // stream, so that launches do not overlap and each is timed by itself.
+    // A round that does not even give every compute unit four 64 x 64 tiles gains nothing from a second chain and
+    // pays for the fork and the join (8 matrices of 256 x 256 fp64: 0.113 ms on one chain, 0.143 ms on two; 12 of
+    // 512 x 512: 0.523 / 0.550; from 16 of 512 x 512 on two chains win).
     int chains = 1;
-    if (!g_brackets && n < 1024 && longest >= 2 && ds->side_stream != nullptr) chains = std::min(env_chain_limit(), ds->host_summary[4]);
+    const long long tiles64 = (long long)ds->host_summary[4] * ((n + 63) / 64) * ((n + 63) / 64);  // round 2
+    if (!g_brackets && n < 1024 && longest >= 2 && tiles64 >= kTwoChainTiles && ds->side_stream != nullptr)
+        chains = std::min(env_chain_limit(), ds->host_summary[4]);
     if (chains > 1) {
         EXPM_TRY(hipEventRecord(ds->fork, stream));
         for (int c = 1; c < chains; ++c) {

@@ -610,31 +610,52 @@ __global__ __launch_bounds__(kThreads, WT == 4 ? 2 : (FIRST && ALIGNED == kAcces
             S[i] = reinterpret_cast<const T *>(p.base[st.src[i]]) + moff;
             D[i] = reinterpret_cast<T *>(p.base[st.dst[i]]) + moff;
         }
+        // A lane holds 4 * WT rows of the tile ((ti, v) pairs).  The source vectors of a batch of rows are all fetched
+        // before the first result of the batch is stored: the memory counter of a wave counts loads and stores
+        // together and in order, so a load issued behind a store is waited for together with that store, and row by
+        // row the epilogue was 4 * WT memory round trips one after another.  The batch is as many rows as fit 32
+        // registers (more and the 64 x 64 fp64 kernel spills; the 128 x 128 kernels have none to spare and go row by row).
+        constexpr int kRows = 4 * WT;
+        constexpr int kRegsPerRow = (WT / G) * 4 * (int)sizeof(GV) / 4;
+        constexpr int NB = WT == 4 ? 1 : (32 / kRegsPerRow < kRows ? 32 / kRegsPerRow : kRows);
+        static_assert(kRows % NB == 0, "whole batches");
 #pragma unroll
-        for (int ti = 0; ti < WT; ++ti)
+        for (int it0 = 0; it0 < kRows; it0 += NB) {
+            GV sv[NB][WT / G][4];
 #pragma unroll
-            for (int v = 0; v < 4; ++v) {
+            for (int q = 0; q < NB; ++q) {
+                const int row = er + 16 * ((it0 + q) / 4) + Mfma<T>::row(lg, (it0 + q) % 4);
+#pragma unroll
+                for (int g = 0; g < WT / G; ++g) {
+                    const int col = ec + g * 16 * G;
+                    const size_t idx = (size_t)row * n + col;
+                    if (kVecIO ? (ALIGNED >= kAccessFull || (row < n && col < n)) : row < n) {
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            if constexpr (kVecIO) {
+                                sv[q][g][i] = i < st.nsrc ? *reinterpret_cast<const GV *>(S[i] + idx) : (GV)(0);
+                            } else {
+#pragma unroll
+                                for (int e = 0; e < G; ++e) sv[q][g][i][e] = (i < st.nsrc && col + e < n) ? S[i][idx + e] : (T)0;
+                            }
+                        }
+                    }
+                }
+            }
+#pragma unroll
+            for (int q = 0; q < NB; ++q) {
+                const int ti = (it0 + q) / 4, v = (it0 + q) % 4;
                 const int row = er + 16 * ti + Mfma<T>::row(lg, v);
 #pragma unroll
                 for (int g = 0; g < WT / G; ++g) {
                     const int col = ec + g * 16 * G;
                     const size_t idx = (size_t)row * n + col;
                     if (kVecIO ? (ALIGNED >= kAccessFull || (row < n && col < n)) : row < n) {
-                        GV sv[4];
-#pragma unroll
-                        for (int i = 0; i < 4; ++i) {
-                            if constexpr (kVecIO) {
-                                sv[i] = i < st.nsrc ? *reinterpret_cast<const GV *>(S[i] + idx) : (GV)(0);
-                            } else {
-#pragma unroll
-                                for (int e = 0; e < G; ++e) sv[i][e] = (i < st.nsrc && col + e < n) ? S[i][idx + e] : (T)0;
-                            }
-                        }
                         GV t;
 #pragma unroll
                         for (int e = 0; e < G; ++e) t[e] = st.acc_scale * acc[ti][g * G + e][v];
 #pragma unroll
-                        for (int i = 0; i < 4; ++i) t += st.g[i] * sv[i];
+                        for (int i = 0; i < 4; ++i) t += st.g[i] * sv[q][g][i];
                         GV dg;
 #pragma unroll
                         for (int e = 0; e < G; ++e) dg[e] = row == col + e ? (T)1 : (T)0;
@@ -643,7 +664,7 @@ __global__ __launch_bounds__(kThreads, WT == 4 ? 2 : (FIRST && ALIGNED == kAcces
                             if (j < st.nout) {
                                 GV o = st.a[j] * t;
 #pragma unroll
-                                for (int i = 0; i < 4; ++i) o += st.b[j][i] * sv[i];
+                                for (int i = 0; i < 4; ++i) o += st.b[j][i] * sv[q][g][i];
                                 o += st.d[j] * dg;
                                 if constexpr (kVecIO) {
                                     *reinterpret_cast<GV *>(D[j] + idx) = o;
@@ -657,6 +678,7 @@ __global__ __launch_bounds__(kThreads, WT == 4 ? 2 : (FIRST && ALIGNED == kAcces
                     }
                 }
             }
+        }
     }
 
     // norm partials of the product just formed: the power rounds (W^2, W^3, W^4) and the term rounds of the baseline
