@@ -132,6 +132,24 @@ def test_rounds_fp32_sizes(ex, n, batch):
     assert stats["fused_path"] == 0
 
 
+# 32x32 tiles straight into LDS (small batches of full-tile sizes) keep three k-blocks in flight in a ring of four
+# stages: a loop of four steps and a tail of three to six.  k-blocks are 32 (fp32) or 16 (fp64) wide, so these sizes
+# give every tail length after zero, one or several turns of the loop, and a single matrix gives the first chain
+# round its 32x32 variant with the third tile per stage.
+@pytest.mark.parametrize("n,dtype", [(160, np.float32), (224, np.float32), (288, np.float32), (320, np.float32),
+                                     (352, np.float32), (416, np.float32), (160, np.float64), (224, np.float64),
+                                     (288, np.float64), (352, np.float64)])
+def test_rounds_thin_tiles_ring_every_tail_length(ex, n, dtype):
+    from paper_2512_20777_amd import workloads
+    a = workloads.random_stack(900 + n, 2, n, dtype, 0.5, 120.0)
+    a[0] *= 60.0 / np.abs(a[0]).sum(axis=0).max()   # order 15+ with several squarings
+    a[1] *= 0.02 / np.abs(a[1]).sum(axis=0).max()   # a low order as well (its first round is the last one)
+    _, m, s, info, stats = _run_and_check(ex, a, label="ring n=%d %s" % (n, np.dtype(dtype).name))
+    assert stats["fused_path"] == 0 and m[0] == 15 and s[0] >= 3
+    one = a[:1].copy()
+    _run_and_check(ex, one, label="ring single n=%d %s" % (n, np.dtype(dtype).name))
+
+
 @pytest.mark.parametrize("n,dtype", [(1030, np.float64), (1027, np.float64), (1028, np.float32), (1030, np.float32),
                                      (1152, np.float32)])
 def test_rounds_128_tiles_ragged_and_full(ex, n, dtype):
