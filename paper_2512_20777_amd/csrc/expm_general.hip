@@ -15,6 +15,7 @@
 // Operands are staged through double-buffered LDS in k-blocks of 128 bytes per row: straight from global
 // memory into LDS when tiles are full and rows 16-byte aligned, through registers otherwise.
 #include "expm_internal.h"
+#include "expm_tile.h"
 
 #include <utility>
 
@@ -24,27 +25,9 @@ namespace expmk {
 
 namespace {
 
-constexpr int kThreads = 256;
-constexpr int kAPitch = 144;    // bytes per A row in LDS: 128 data + 16 pad (conflict-free 16-byte reads)
+constexpr int kThreads = kTileThreads;
 constexpr int kThinGroups = 384;    // launches of at most this many 64x64 tiles switch to 32x32 tiles
 constexpr int kColChunk = 32;   // rows per column-abs-sum partial of the input matrix
-
-template <typename T> struct Tile;
-template <> struct Tile<double> {
-    static constexpr int BK = 16;        // k-block: 128 bytes of a row
-    static constexpr int VN = 2;         // elements per 16-byte vector
-    using vec_t = double2;
-};
-template <> struct Tile<float> {
-    static constexpr int BK = 32;
-    static constexpr int VN = 4;
-    using vec_t = float4;
-};
-
-template <typename T, int WT> constexpr int stage_bytes(bool dma = false)
-{
-    return 32 * WT * (dma ? 128 : kAPitch) + Tile<T>::BK * 32 * WT * (int)sizeof(T);
-}
 
 // G neighbouring columns per lane: the 16 columns of MFMA tile tj of a wave do not stand for columns 16 tj .. 16 tj + 15
 // of the wave's span but, in groups of G tiles, for columns (tj / G) * 16 G + G * lj + tj % G (lj = lane % 16).  A lane's
@@ -133,17 +116,13 @@ __global__ __launch_bounds__(kThreads, WT == 4 ? 2 : (FIRST && ALIGNED == kAcces
 {
     using V = typename Tile<T>::vec_t;
     using acc_t = typename Mfma<T>::acc_t;
-    constexpr int BM = 32 * WT, BN = 32 * WT;
-    constexpr int BK = Tile<T>::BK, VN = Tile<T>::VN;
-    constexpr int BPitch = BN * (int)sizeof(T);   // B rows are rotated, not padded
-    constexpr int KQ = BK / 4;                    // k values each 16-lane group owns per k-block
-    constexpr int VPR = BN / VN;                  // 16-byte vectors per B row
-    constexpr int BSTEP = kThreads / VPR;         // B rows covered by one pass of the workgroup
+    constexpr bool DMA = ALIGNED == kAccessDma;
+    using S = TileStaging<T, WT, DMA>;            // tile layouts in LDS and who stages what (expm_tile.h)
+    constexpr int BM = S::BM, BN = S::BN, BK = S::BK, VN = S::VN;
+    constexpr int APitch = S::APitch, BPitch = S::BPitch, BSTEP = S::BSTEP;
     constexpr int G = col_group<T, WT>();         // neighbouring columns per lane (see col_group)
     using GV = typename VecOfN<T, G>::type;
-    constexpr bool DMA = ALIGNED == kAccessDma;
     constexpr bool kPipe = DMA && !FIRST && sizeof(T) == 4;  // fragment reads one k-step ahead (fp32: registers to spare; fp64 loses)
-    constexpr int APitch = DMA ? 128 : kAPitch;   // DMA: unpadded rows, 16-byte slots swizzled instead
     // FIRST with the direct-to-LDS loads: a third tile per stage holds the part of W that goes into the combined
     // operand, in the layout of the side it belongs to (both tiles are 32*WT*128 bytes); the combination is formed
     // from the two fragments, on their way from LDS into the MFMAs.
@@ -151,8 +130,6 @@ __global__ __launch_bounds__(kThreads, WT == 4 ? 2 : (FIRST && ALIGNED == kAcces
     constexpr int kXOff = BM * APitch + BK * BPitch;   // offset of that tile in a stage
     static_assert(!kFragComb || BM * APitch == BK * BPitch, "left and right tiles of equal size");
     constexpr int STAGE = stage_bytes<T, WT>(DMA) + (kFragComb ? BM * APitch : 0);
-    constexpr int kRot = 16 * (int)sizeof(T);     // rotation of a B row per k-group, in bytes
-    static_assert(BK / BSTEP == WT && BM / 32 == WT, "WT staged vectors per thread and operand");
     // Two LDS stages.  With the direct-to-LDS loads they are two separate LDS objects and the k-loop below is written
     // out for both parities: the compiler orders every LDS read behind all outstanding loads into an LDS object the
     // read may alias, so with one array holding both stages a wave waited for the next k-block's loads before it
@@ -271,20 +248,9 @@ __global__ __launch_bounds__(kThreads, WT == 4 ? 2 : (FIRST && ALIGNED == kAcces
     const T *Lp = reinterpret_cast<const T *>(p.base[st.L]) + moff;
     const T *Rp = reinterpret_cast<const T *>(p.base[st.R]) + moff;
 
-    // ---- staging maps -----------------------------------------------------------------------
-    // A tile: BM rows x 8 vectors ; B tile: BK rows x VPR vectors ; WT vectors per thread each.
-    // vector v = tid + 256*i: A row = tid/8 + 32*i, B row = tid/VPR + BSTEP*i.
-    // B rows are rotated by 16 elements per 16-lane k-group (row / KQ) so that the four groups of a
-    // fragment read hit different banks.
-    const int a_row0 = tid >> 3, a_col = (tid & 7) * VN;
-    const int b_row0 = tid / VPR, b_col = (tid % VPR) * VN;
-    const int a_lds = a_row0 * APitch + (tid & 7) * 16;
-    const int b_lds = BM * APitch + b_row0 * BPitch;
-    const int b_vcol = (tid % VPR) * 16;  // byte offset of this thread's vector inside an unrotated row
-    // LDS byte offset of staged B vector i (recomputed where used: two instructions, no register held)
-    auto b_wr = [&](int i) -> int {
-        return b_lds + BSTEP * i * BPitch + ((b_vcol + kRot * ((b_row0 + BSTEP * i) / KQ)) & (BPitch - 1));
-    };
+    // ---- staging maps (expm_tile.h) -----------------------------------------------------------
+    const S sg(tid);
+    const int a_row0 = sg.a_row0, a_col = sg.a_col, b_row0 = sg.b_row0, b_col = sg.b_col;
     const int row0 = tm * BM, col0 = tn * BN;
 
     acc_t acc[WT][WT];
@@ -323,36 +289,17 @@ __global__ __launch_bounds__(kThreads, WT == 4 ? 2 : (FIRST && ALIGNED == kAcces
             }
         }
     };
-    // DMA staging: pass i of the workgroup covers the 256 slots i*256 .. i*256+255 of a tile, one per thread.
-    //   left tile:  slot (row, v') with row = tid/8 + 32 i holds k-vector v' ^ ((row / 2) & 7) of the row (rows two
-    //               apart differ in the swizzle, odd and even rows in the bank half: 16 rows of a fragment read
-    //               hit 16 different 16-byte bank groups)
-    //   right tile: slot (row, v') holds column vector v' - rot(row) of the row, rot = the rotation per k-group
-    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
-    const int a_kv = ((tid & 7) ^ ((tid >> 4) & 7)) * VN;  // ((row / 2) & 7) does not depend on the pass
+    // one k-block straight into a stage (slot layout: expm_tile.h)
     auto dma = [&](int k0, unsigned char *stage) {
         if constexpr (DMA) {
+            sg.fetch_to_lds(Lp, (size_t)n, row0, Rp, (size_t)n, col0, k0, stage);
+            if constexpr (kFragComb) {
+                // W at the positions of the side that is combined (uniform over the workgroup)
 #pragma unroll
-            for (int i = 0; i < WT; ++i) {
-                const T *ga = Lp + (size_t)(row0 + a_row0 + 32 * i) * n + k0 + a_kv;
-                const int brow = b_row0 + BSTEP * i;
-                const int bv = ((tid % VPR) - (kRot / 16) * (brow / KQ)) & (VPR - 1);
-                const T *gb = Rp + (size_t)(k0 + brow) * n + col0 + bv * VN;
-                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)ga,
-                                                 (__attribute__((address_space(3))) void *)(stage + (i * 256 + wave_u * 64) * 16),
-                                                 16, 0, 0);
-                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)gb,
-                                                 (__attribute__((address_space(3))) void *)(stage + BM * APitch +
-                                                                                           (i * 256 + wave_u * 64) * 16),
-                                                 16, 0, 0);
-                if constexpr (kFragComb) {
-                    // W at the positions of the side that is combined (uniform over the workgroup)
-                    const T *gx = comb_a ? Xp + (size_t)(row0 + a_row0 + 32 * i) * n + k0 + a_kv
-                                         : Xp + (size_t)(k0 + brow) * n + col0 + bv * VN;
-                    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)gx,
-                                                     (__attribute__((address_space(3))) void *)(stage + kXOff +
-                                                                                               (i * 256 + wave_u * 64) * 16),
-                                                     16, 0, 0);
+                for (int i = 0; i < WT; ++i) {
+                    const T *gx = comb_a ? Xp + (size_t)(row0 + sg.left_row(i)) * n + k0 + sg.a_kv
+                                         : Xp + (size_t)(k0 + sg.right_row(i)) * n + col0 + sg.right_col(i);
+                    S::to_lds(gx, stage + kXOff + sg.slot(i));
                 }
             }
         }
@@ -380,19 +327,16 @@ __global__ __launch_bounds__(kThreads, WT == 4 ? 2 : (FIRST && ALIGNED == kAcces
         combine(0);
 #pragma unroll
         for (int i = 0; i < WT; ++i) {
-            *reinterpret_cast<V *>(smem + a_lds + 32 * i * APitch) = ra[i];
-            *reinterpret_cast<V *>(smem + b_wr(i)) = rb[i];
+            *reinterpret_cast<V *>(smem + sg.left_write(i)) = ra[i];
+            *reinterpret_cast<V *>(smem + sg.right_write(i)) = rb[i];
         }
     }
     if (!ring) __syncthreads();
 
-    // per-lane LDS read offsets (bytes) inside a stage
-    //   A: row (wm*16*WT + 16*ti + lj), k values lg*KQ .. lg*KQ+KQ-1  -> two 16-byte reads (h = 0, 1)
-    //   B: row (lg*KQ + kk), column (wn*16*WT + 16*tj + lj) rotated by 16*lg elements
-    const int a_row_rd = (wm * 16 * WT + lj) * APitch;
-    const int a_rd0 = a_row_rd + (DMA ? ((2 * lg) ^ ((lj >> 1) & 7)) * 16 : lg * 32);
-    const int a_rd1 = a_row_rd + (DMA ? ((2 * lg + 1) ^ ((lj >> 1) & 7)) * 16 : lg * 32 + 16);
-    const int b_rd = BM * APitch + (lg * KQ) * BPitch;
+    // per-lane LDS read offsets (bytes) inside a stage: two 16-byte reads per left fragment (h = 0, 1), and the right
+    // rows of this lane group; the rotated column of the lane's first group of G tiles follows below
+    const int a_rd0 = S::left_read(wm, lj, lg, 0), a_rd1 = S::left_read(wm, lj, lg, 1);
+    const int b_rd = S::right_read_base(lg);
     const int b_rc0 = (wn * 16 * WT + G * lj + 16 * lg) * (int)sizeof(T);  // rotated column of this lane's first group, before wrap
 
     // the products of one staged k-block
@@ -449,7 +393,7 @@ __global__ __launch_bounds__(kThreads, WT == 4 ? 2 : (FIRST && ALIGNED == kAcces
 #pragma unroll
                             for (int q = 0; q < VN; ++q) {
                                 T v = xa * reinterpret_cast<const T *>(&af[ti])[q] + xb * reinterpret_cast<const T *>(&ax)[q];
-                                if (row == kb * BK + lg * KQ + h * VN + q) v += (T)1;
+                                if (row == kb * BK + lg * S::KQ + h * VN + q) v += (T)1;
                                 reinterpret_cast<T *>(&af[ti])[q] = v;
                             }
                         }
@@ -505,8 +449,8 @@ __global__ __launch_bounds__(kThreads, WT == 4 ? 2 : (FIRST && ALIGNED == kAcces
             combine((kb + 1) * BK);
 #pragma unroll
             for (int i = 0; i < WT; ++i) {
-                *reinterpret_cast<V *>(nxt + a_lds + 32 * i * APitch) = ra[i];
-                *reinterpret_cast<V *>(nxt + b_wr(i)) = rb[i];
+                *reinterpret_cast<V *>(nxt + sg.left_write(i)) = ra[i];
+                *reinterpret_cast<V *>(nxt + sg.right_write(i)) = rb[i];
             }
         }
         __syncthreads();

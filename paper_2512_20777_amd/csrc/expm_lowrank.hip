@@ -11,29 +11,14 @@
 // for 16-byte fragment reads, right rows rotated per k-group.  Operands are read as 16-byte vectors when the
 // leading dimensions, sizes and addresses allow it and element by element otherwise; every access is bounds-checked.
 #include "expm_internal.h"
+#include "expm_tile.h"
 
 namespace expmk {
 
 namespace {
 
-constexpr int kRectThreads = 256;
+constexpr int kRectThreads = kTileThreads;
 constexpr int kRectMinGroups = 1024;
-constexpr int kLeftPitch = 144;  // bytes per left-operand row in LDS: 128 data + 16 pad
-
-template <typename T> struct RectTile;
-template <> struct RectTile<double> {
-    static constexpr int BK = 16, VN = 2;
-    using vec_t = double2;
-};
-template <> struct RectTile<float> {
-    static constexpr int BK = 32, VN = 4;
-    using vec_t = float4;
-};
-
-template <typename T, int WT> constexpr int rect_stage_bytes(bool dma)
-{
-    return 32 * WT * (dma ? 128 : kLeftPitch) + RectTile<T>::BK * 32 * WT * (int)sizeof(T);
-}
 
 // How the operands are fetched: element by element, as 16-byte vectors through registers (both bounds-checked),
 // or -- every tile full, every slice a whole number of k-blocks -- as 16-byte vectors straight into LDS
@@ -59,11 +44,11 @@ struct RectParams {
 
 // VN elements of row `row` from column `col` of a rows x cols matrix; zero beyond it
 template <typename T, bool VEC>
-__device__ __forceinline__ typename RectTile<T>::vec_t rect_load(const T *__restrict__ p, int row, int col, int rows, int cols,
+__device__ __forceinline__ typename Tile<T>::vec_t rect_load(const T *__restrict__ p, int row, int col, int rows, int cols,
                                                                  int ld)
 {
-    using V = typename RectTile<T>::vec_t;
-    constexpr int VN = RectTile<T>::VN;
+    using V = typename Tile<T>::vec_t;
+    constexpr int VN = Tile<T>::VN;
     V v;
     T *e = reinterpret_cast<T *>(&v);
     if constexpr (VEC) {
@@ -84,18 +69,12 @@ template <typename T, int WT, int MODE>
 __global__ __launch_bounds__(kRectThreads, WT == 4 ? 2 : 4) void rect_gemm_kernel(RectParams p)
 {
     constexpr bool VEC = MODE >= kRectVector, DMA = MODE == kRectDma;
-    constexpr int APitch = DMA ? 128 : kLeftPitch;  // DMA: unpadded rows, 16-byte slots swizzled instead
-    using V = typename RectTile<T>::vec_t;
+    using S = TileStaging<T, WT, DMA>;              // tile layouts in LDS and who stages what (expm_tile.h)
+    using V = typename Tile<T>::vec_t;
     using acc_t = typename Mfma<T>::acc_t;
-    constexpr int BM = 32 * WT, BN = 32 * WT;
-    constexpr int BK = RectTile<T>::BK, VN = RectTile<T>::VN;
-    constexpr int BPitch = BN * (int)sizeof(T);
-    constexpr int KQ = BK / 4;
-    constexpr int VPR = BN / VN;
-    constexpr int BSTEP = kRectThreads / VPR;
-    constexpr int STAGE = rect_stage_bytes<T, WT>(DMA);
-    constexpr int kRot = 16 * (int)sizeof(T);
-    static_assert(BK / BSTEP == WT, "WT staged vectors per thread and operand");
+    constexpr int BM = S::BM, BN = S::BN, BK = S::BK, VN = S::VN;
+    constexpr int APitch = S::APitch, BPitch = S::BPitch, BSTEP = S::BSTEP, kRot = S::kRot;
+    constexpr int STAGE = stage_bytes<T, WT>(DMA);
     // Two LDS stages; with the direct-to-LDS loads two separate LDS objects and a loop written out for both parities
     // (an LDS read is ordered behind every outstanding load into an LDS object it may alias: with one array for both
     // stages nothing would be fetched while a wave multiplies).
@@ -121,15 +100,9 @@ __global__ __launch_bounds__(kRectThreads, WT == 4 ? 2 : 4) void rect_gemm_kerne
     const T *Rp = reinterpret_cast<const T *>(p.B) + (size_t)b * p.sb;
     T *Cp = reinterpret_cast<T *>(p.C) + (size_t)b * p.sc + (size_t)slice * p.sslice;
 
-    // staging maps: left tile BM rows x 8 vectors, right tile BK rows x VPR vectors, WT vectors per thread each
-    const int a_row0 = tid >> 3, a_col = (tid & 7) * VN;
-    const int b_row0 = tid / VPR, b_col = (tid % VPR) * VN;
-    const int a_lds = a_row0 * APitch + (tid & 7) * 16;
-    const int b_lds = BM * APitch + b_row0 * BPitch;
-    const int b_vcol = (tid % VPR) * 16;
-    auto b_wr = [&](int i) -> int {
-        return b_lds + BSTEP * i * BPitch + ((b_vcol + kRot * ((b_row0 + BSTEP * i) / KQ)) & (BPitch - 1));
-    };
+    // staging maps (expm_tile.h)
+    const S sg(tid);
+    const int a_row0 = sg.a_row0, a_col = sg.a_col, b_row0 = sg.b_row0, b_col = sg.b_col;
 
     acc_t acc[WT][WT];
     auto clear = [&]() {
@@ -162,31 +135,14 @@ __global__ __launch_bounds__(kRectThreads, WT == 4 ? 2 : 4) void rect_gemm_kerne
     auto stash = [&](unsigned char *stage) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < WT; ++i) {
-            *reinterpret_cast<V *>(stage + a_lds + 32 * i * APitch) = ra[i];
-            *reinterpret_cast<V *>(stage + b_wr(i)) = rb[i];
+            *reinterpret_cast<V *>(stage + sg.left_write(i)) = ra[i];
+            *reinterpret_cast<V *>(stage + sg.right_write(i)) = rb[i];
         }
     };
-    // DMA: pass i covers the slots i*256 .. i*256+255 of a tile, one per thread.  Left tile: slot (row, v') holds
-    // k-vector v' ^ ((row / 2) & 7) of the row; right tile: slot (row, v') holds column vector v' - rot(row).
-    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
-    const int a_kv = ((tid & 7) ^ ((tid >> 4) & 7)) * VN;
+    // one k-block of the step the next fetch belongs to, straight into a stage (slot layout: expm_tile.h)
     auto dma = [&](unsigned char *stage) __attribute__((always_inline)) {
         if constexpr (DMA) {
-            const int k0 = kbeg + f_kb * BK, col0 = f_ct * BN;
-#pragma unroll
-            for (int i = 0; i < WT; ++i) {
-                const T *ga = Lp + (size_t)(row0 + a_row0 + 32 * i) * p.lda + k0 + a_kv;
-                const int brow = b_row0 + BSTEP * i;
-                const int bv = ((tid % VPR) - (kRot / 16) * (brow / KQ)) & (VPR - 1);
-                const T *gb = Rp + (size_t)(k0 + brow) * p.ldb + col0 + bv * VN;
-                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)ga,
-                                                 (__attribute__((address_space(3))) void *)(stage + (i * 256 + wave_u * 64) * 16),
-                                                 16, 0, 0);
-                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)gb,
-                                                 (__attribute__((address_space(3))) void *)(stage + BM * APitch +
-                                                                                           (i * 256 + wave_u * 64) * 16),
-                                                 16, 0, 0);
-            }
+            sg.fetch_to_lds(Lp, (size_t)p.lda, row0, Rp, (size_t)p.ldb, f_ct * BN, kbeg + f_kb * BK, stage);
             if (++f_kb == kblocks) {
                 f_kb = 0;
                 ++f_ct;
@@ -251,10 +207,8 @@ __global__ __launch_bounds__(kRectThreads, WT == 4 ? 2 : 4) void rect_gemm_kerne
     }
     __syncthreads();
 
-    const int a_row_rd = (wm * 16 * WT + lj) * APitch;
-    const int a_rd0 = a_row_rd + (DMA ? ((2 * lg) ^ ((lj >> 1) & 7)) * 16 : lg * 32);
-    const int a_rd1 = a_row_rd + (DMA ? ((2 * lg + 1) ^ ((lj >> 1) & 7)) * 16 : lg * 32 + 16);
-    const int b_rd = BM * APitch + (lg * KQ) * BPitch + lj * (int)sizeof(T);
+    const int a_rd0 = S::left_read(wm, lj, lg, 0), a_rd1 = S::left_read(wm, lj, lg, 1);
+    const int b_rd = S::right_read_base(lg) + lj * (int)sizeof(T);
     const int b_rc0 = (wn * 16 * WT + 16 * lg) * (int)sizeof(T);
 
     auto multiply = [&](const unsigned char *cur) __attribute__((always_inline)) {
@@ -330,10 +284,10 @@ __global__ __launch_bounds__(256) void slice_sum_kernel(const T *__restrict__ P,
 template <typename T, int WT, int MODE>
 hipError_t launch_rect_v(const RectParams &p, dim3 grid, hipStream_t stream)
 {
-    const int lds = 2 * rect_stage_bytes<T, WT>(MODE == kRectDma);
+    const int lds = 2 * stage_bytes<T, WT>(MODE == kRectDma);
     if constexpr (MODE == kRectDma) {
         // the direct-to-LDS variant holds its two stages in static LDS
-        static_assert(2 * rect_stage_bytes<T, WT>(true) <= 65536, "static LDS of the direct-to-LDS variant");
+        static_assert(2 * stage_bytes<T, WT>(true) <= 65536, "static LDS of the direct-to-LDS variant");
         hipLaunchKernelGGL((rect_gemm_kernel<T, WT, MODE>), grid, dim3(kRectThreads), 0, stream, p);
         return hipGetLastError();
     }
@@ -365,7 +319,7 @@ hipError_t launch_rect_t(const RectParams &p, int batch, bool vec, hipStream_t s
     if (total > 0x7fffffffL) return hipErrorInvalidValue;
     q.total = (int)total;
     const dim3 grid((unsigned)total);
-    constexpr int bk = RectTile<T>::BK;
+    constexpr int bk = Tile<T>::BK;
     if (vec && p.M % BT == 0 && p.N % BT == 0 && p.K % bk == 0) return launch_rect_v<T, WT, kRectDma>(q, grid, stream);
     if (vec) return launch_rect_v<T, WT, kRectVector>(q, grid, stream);
     return launch_rect_v<T, WT, kRectScalar>(q, grid, stream);
