@@ -386,6 +386,29 @@ def test_inverse_and_determinant_identities_at_size(ex):
     assert bool((sign > 0).all()) and float((logdet - tr).abs().max()) < 1e-9
 
 
+@pytest.mark.parametrize("n,dtype,tol", [(6144, np.float32, 2e-4), (5000, np.float64, 1e-11)])
+def test_identities_beyond_the_benchmark_sizes(ex, n, dtype, tol):
+    """Sizes above the largest benchmark matrix (48 x 48 tiles of 128 x 128 that do not split evenly over the XCDs;
+    a ragged 5000 that leaves 8 rows and columns for the last tile), checked by what holds at any size:
+    e^W e^(-W) = I and (e^(W/2))^2 = e^W (Sec. 2.2 of the paper), products taken with torch on the device."""
+    import torch
+    from paper_2512_20777_amd import workloads
+    a = workloads.random_stack(n, 1, n, dtype, 30.0, 30.0)
+    d = torch.from_numpy(a).cuda()
+    print("case identities n=%d %s" % (n, np.dtype(dtype).name), flush=True)
+    x = ex.expm(d)[0].clone()
+    y = ex.expm(-d)[0].clone()
+    h = ex.expm(0.5 * d)[0].clone()
+    m, s, _ = ex.expm_select(d)
+    assert m[0] == 15
+    x64, y64, h64 = x[0].double(), y[0].double(), h[0].double()
+    eye = torch.eye(n, dtype=torch.float64, device="cuda")
+    err_inv = float((x64 @ y64 - eye).abs().max())
+    err_sq = float((h64 @ h64 - x64).abs().max() / x64.abs().max())
+    print("   |e^W e^-W - I|_max %.3e   |(e^(W/2))^2 - e^W|_max / |e^W|_max %.3e" % (err_inv, err_sq), flush=True)
+    assert err_inv < tol and err_sq < tol
+
+
 # ------------------------------------------------------------------------------------------------
 # infinity-norm selection and the tolerance of the paper's own runs (Sec. 4.2: eps = 1e-8, inf-norm)
 # ------------------------------------------------------------------------------------------------
