@@ -495,6 +495,11 @@ __global__ __launch_bounds__(256) void fused_expm_kernel(const T *__restrict__ A
         }
         select_order_scaling(n1, n2, eps, m, s, flags);
     }
+    // (m, s) are the same in every lane (the norms are, bit for bit): say so, and everything that depends on them
+    // -- which formulas, which coefficients, how many squarings -- becomes scalar control flow and scalar selects
+    m = __builtin_amdgcn_readfirstlane(m);
+    s = __builtin_amdgcn_readfirstlane(s);
+    flags = __builtin_amdgcn_readfirstlane(flags);
     if (tid == 0) {
         MatInfo mi;
         mi.m = m; mi.s = s; mi.len = 0; mi.flags = flags;
@@ -810,6 +815,10 @@ __global__ __launch_bounds__(256, 4) void fused_tile_kernel(const T *__restrict_
         }
         select_order_scaling(n1, n2, eps, m, s, flags);
     }
+    // (m, s) are the same in every lane: scalar control flow and scalar coefficient selects from here on
+    m = __builtin_amdgcn_readfirstlane(m);
+    s = __builtin_amdgcn_readfirstlane(s);
+    flags = __builtin_amdgcn_readfirstlane(flags);
     if (lane == 0) {
         MatInfo mi;
         mi.m = m; mi.s = s; mi.len = 0; mi.flags = flags;
