@@ -53,8 +53,10 @@ template <> struct VecOf<double> { using type = double2; };
 // x of the lane that the DPP control CTRL pairs with this one (within rows of 16 lanes)
 template <int CTRL> __device__ __forceinline__ double dpp_move(double x)
 {
-    const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(x), CTRL, 0xf, 0xf, false);
-    const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(x), CTRL, 0xf, 0xf, false);
+    // every lane is written (row and bank masks all ones, every source lane of these controls exists), so no
+    // previous value has to be set up for the destination: the form without one saves two moves per call
+    const int lo = __builtin_amdgcn_mov_dpp(__double2loint(x), CTRL, 0xf, 0xf, true);
+    const int hi = __builtin_amdgcn_mov_dpp(__double2hiint(x), CTRL, 0xf, 0xf, true);
     return __hiloint2double(hi, lo);
 }
 // Reduction over the 16 lanes of a row, result in every lane: mirror the row, mirror its halves, then
