@@ -75,12 +75,15 @@ __device__ __forceinline__ double pow2neg_f(int e)
     return __longlong_as_double((long long)(1023 - e) << 52);
 }
 
-template <typename T, int NT, int SCHEME>
-__global__ __launch_bounds__(256) void fused_expm_kernel(const T *__restrict__ Ain, T *__restrict__ Out, int n, int batch,
+// FULL: n = 16 NT exactly and 16-byte aligned pointers (the launcher checks): the size is a compile-time constant, so
+// the zero padding, the bounds of the load and store loops and their predicates fold away.
+template <typename T, int NT, int SCHEME, bool FULL = false>
+__global__ __launch_bounds__(256) void fused_expm_kernel(const T *__restrict__ Ain, T *__restrict__ Out, int n_arg, int batch,
                                                          double eps, int select_only, int norm_inf,
                                                          MatInfo *__restrict__ info)
 {
     using C = FusedCfg<T, NT>;
+    const int n = FULL ? C::NP : n_arg;
     using acc_t = typename Mfma<T>::acc_t;
     constexpr int NP = C::NP, LPA = C::LPA, LPB = C::LPB, TH = C::TH, WG = C::WG, NR = C::kRows;
     constexpr bool kWide = C::kWide;
@@ -121,7 +124,7 @@ __global__ __launch_bounds__(256) void fused_expm_kernel(const T *__restrict__ A
 
     // ---- load W into both operand layouts, zero padded -------------------------------------------
     constexpr int VN = 16 / (int)sizeof(T);  // elements per 16-byte vector
-    const bool vec_ok = (n % VN == 0) && ((reinterpret_cast<uintptr_t>(Ain) | reinterpret_cast<uintptr_t>(Out)) % 16 == 0);
+    const bool vec_ok = FULL || ((n % VN == 0) && ((reinterpret_cast<uintptr_t>(Ain) | reinterpret_cast<uintptr_t>(Out)) % 16 == 0));
     if (n < NR) {
         for (int e = tid; e < NR * NR; e += C::kThreads) {
             const int r = e / NR, c = e - r * NR;
@@ -691,12 +694,14 @@ template <typename T> struct Pair {
 };
 
 // (register budget of 128 per lane: the four workgroups a compute unit gets at a batch of 4096 are resident together)
-template <typename T, int SCHEME>
-__global__ __launch_bounds__(256, 4) void fused_tile_kernel(const T *__restrict__ Ain, T *__restrict__ Out, int n, int batch,
+// (FULL: n = 16 exactly, a compile-time constant for the index arithmetic and the bounds predicates)
+template <typename T, int SCHEME, bool FULL = false>
+__global__ __launch_bounds__(256, 4) void fused_tile_kernel(const T *__restrict__ Ain, T *__restrict__ Out, int n_arg, int batch,
                                                          double eps, int select_only, int norm_inf,
                                                          MatInfo *__restrict__ info)
 {
     using acc_t = typename Mfma<T>::acc_t;
+    const int n = FULL ? 16 : n_arg;
     using M = Pair<T>;
     const int b = blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     if (b >= batch) return;
@@ -952,8 +957,12 @@ template <typename T, int SCHEME>
 hipError_t launch_tile_t(const void *A, void *out, int n, int batch, double eps, int select_only, int norm_inf,
                          MatInfo *info, hipStream_t stream)
 {
-    hipLaunchKernelGGL((fused_tile_kernel<T, SCHEME>), dim3((batch + 3) / 4), dim3(256), 0, stream,
-                       reinterpret_cast<const T *>(A), reinterpret_cast<T *>(out), n, batch, eps, select_only, norm_inf, info);
+    if (SCHEME == kSchemeSastre && n == 16)
+        hipLaunchKernelGGL((fused_tile_kernel<T, SCHEME, SCHEME == kSchemeSastre>), dim3((batch + 3) / 4), dim3(256), 0, stream,
+                           reinterpret_cast<const T *>(A), reinterpret_cast<T *>(out), n, batch, eps, select_only, norm_inf, info);
+    else
+        hipLaunchKernelGGL((fused_tile_kernel<T, SCHEME>), dim3((batch + 3) / 4), dim3(256), 0, stream,
+                           reinterpret_cast<const T *>(A), reinterpret_cast<T *>(out), n, batch, eps, select_only, norm_inf, info);
     return hipGetLastError();
 }
 
@@ -968,6 +977,14 @@ hipError_t launch_fused_t(const void *A, void *out, int n, int batch, double eps
                                    hipFuncAttributeMaxDynamicSharedMemorySize, C::kLds);
     });
     if (e != hipSuccess) return e;
+    // one-tile matrices of exactly 16 x 16 at aligned addresses (the main scheme): the variant with the size folded in
+    constexpr bool kHasFull = NT == 1 && SCHEME == kSchemeSastre;
+    if (kHasFull && n == 16 && (reinterpret_cast<uintptr_t>(A) | reinterpret_cast<uintptr_t>(out)) % 16 == 0) {
+        hipLaunchKernelGGL((fused_expm_kernel<T, NT, SCHEME, kHasFull>), dim3((batch + C::kMPW - 1) / C::kMPW), dim3(C::kBlock),
+                           C::kLds, stream, reinterpret_cast<const T *>(A), reinterpret_cast<T *>(out), n, batch, eps,
+                           select_only, norm_inf, info);
+        return hipGetLastError();
+    }
     hipLaunchKernelGGL((fused_expm_kernel<T, NT, SCHEME>), dim3((batch + C::kMPW - 1) / C::kMPW), dim3(C::kBlock), C::kLds,
                        stream, reinterpret_cast<const T *>(A), reinterpret_cast<T *>(out), n, batch, eps, select_only,
                        norm_inf, info);
