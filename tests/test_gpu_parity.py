@@ -1,6 +1,6 @@
 """GPU parity: the HIP library against the CPU oracle, element by element, through the C ABI.
 
-Gates (fixed by the benchmark spec): (m, s) identical except for matrices whose norms lie within
+Gates: (m, s) identical except for matrices whose norms lie within
 1e-6 relative of a selection switch point (then the result must equal one of the corner choices);
 relative Frobenius error per matrix <= 1e-11 (fp64) / 5e-5 (fp32).
 """
