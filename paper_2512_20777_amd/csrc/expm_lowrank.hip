@@ -327,15 +327,16 @@ hipError_t launch_rect_t(const RectParams &p, int batch, bool vec, hipStream_t s
 
 }  // namespace
 
-// Slices of the inner dimension for a product with few output tiles: enough workgroups to cover the chip a few
-// times over, every slice at least two k-blocks long.  1 means no slicing (and no partial buffer).
+// Slices of the inner dimension for a product with few output tiles: enough workgroups to cover the chip twice,
+// every slice at least two k-blocks long (64 pairs of 64 x 1024 factors: 8 slices; 16 were 2 % slower for the call,
+// 4 the same).  1 means no slicing (and no partial buffer).
 int rect_gemm_slices(int M, int N, int K, int batch, int dtype)
 {
     if (M <= 0 || N <= 0 || K <= 0 || batch <= 0) return 1;
     const int bt = (M <= 64 || N <= 64) ? 64 : 128;
     const int bk = dtype == 1 ? 16 : 32;
     const long tiles = (long)((M + bt - 1) / bt) * ((N + bt - 1) / bt) * batch;
-    const long want = (1024 + tiles - 1) / tiles;
+    const long want = (512 + tiles - 1) / tiles;
     const long most = K / (2 * bk);
     long s = want < most ? want : most;
     if (s > 64) s = 64;
