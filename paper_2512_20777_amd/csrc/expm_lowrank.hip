@@ -65,22 +65,28 @@ __device__ __forceinline__ typename Tile<T>::vec_t rect_load(const T *__restrict
     return v;
 }
 
-template <typename T, int WT, int MODE>
+// RES (direct-to-LDS variant, inner dimension of at most kResBlocks k-blocks, several column tiles per workgroup):
+// the workgroup's left panel is fetched once and stays in LDS, the stages hold right tiles only.
+constexpr int kResBlocks = 2;
+template <typename T, int WT, int MODE, bool RES = false>
 __global__ __launch_bounds__(kRectThreads, WT == 4 ? 2 : 4) void rect_gemm_kernel(RectParams p)
 {
     constexpr bool VEC = MODE >= kRectVector, DMA = MODE == kRectDma;
+    static_assert(!RES || DMA, "the resident left panel belongs to the direct-to-LDS variant");
     using S = TileStaging<T, WT, DMA>;              // tile layouts in LDS and who stages what (expm_tile.h)
     using V = typename Tile<T>::vec_t;
     using acc_t = typename Mfma<T>::acc_t;
     constexpr int BM = S::BM, BN = S::BN, BK = S::BK, VN = S::VN;
     constexpr int APitch = S::APitch, BPitch = S::BPitch, BSTEP = S::BSTEP, kRot = S::kRot;
-    constexpr int STAGE = stage_bytes<T, WT>(DMA);
+    constexpr int STAGE = RES ? S::kRightBytes : stage_bytes<T, WT>(DMA);
+    constexpr int kRightAt = RES ? 0 : S::kLeftBytes;   // where the right tile starts in a stage
     // Two LDS stages; with the direct-to-LDS loads two separate LDS objects and a loop written out for both parities
     // (an LDS read is ordered behind every outstanding load into an LDS object it may alias: with one array for both
     // stages nothing would be fetched while a wave multiplies).
     extern __shared__ __align__(16) unsigned char smem_dyn[];
     __shared__ __align__(16) unsigned char stage_even[DMA ? STAGE : 16];
     __shared__ __align__(16) unsigned char stage_odd[DMA ? STAGE : 16];
+    __shared__ __align__(16) unsigned char left_panel[RES ? kResBlocks * S::kLeftBytes : 16];
     unsigned char *const smem = DMA ? stage_even : smem_dyn;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -142,7 +148,8 @@ __global__ __launch_bounds__(kRectThreads, WT == 4 ? 2 : 4) void rect_gemm_kerne
     // one k-block of the step the next fetch belongs to, straight into a stage (slot layout: expm_tile.h)
     auto dma = [&](unsigned char *stage) __attribute__((always_inline)) {
         if constexpr (DMA) {
-            sg.fetch_to_lds(Lp, (size_t)p.lda, row0, Rp, (size_t)p.ldb, f_ct * BN, kbeg + f_kb * BK, stage);
+            if constexpr (RES) sg.fetch_right_to_lds(Rp, (size_t)p.ldb, f_ct * BN, kbeg + f_kb * BK, stage);
+            else sg.fetch_to_lds(Lp, (size_t)p.lda, row0, Rp, (size_t)p.ldb, f_ct * BN, kbeg + f_kb * BK, stage);
             if (++f_kb == kblocks) {
                 f_kb = 0;
                 ++f_ct;
@@ -199,6 +206,10 @@ __global__ __launch_bounds__(kRectThreads, WT == 4 ? 2 : 4) void rect_gemm_kerne
         return;
     }
     if constexpr (DMA) {
+        if constexpr (RES) {
+            for (int kb = 0; kb < kblocks; ++kb)   // kblocks <= kResBlocks: the launcher's condition for this variant
+                sg.fetch_left_to_lds(Lp, (size_t)p.lda, row0, kbeg + kb * BK, left_panel + kb * S::kLeftBytes);
+        }
         dma(smem);
         dma_done();
     } else {
@@ -208,22 +219,22 @@ __global__ __launch_bounds__(kRectThreads, WT == 4 ? 2 : 4) void rect_gemm_kerne
     __syncthreads();
 
     const int a_rd0 = S::left_read(wm, lj, lg, 0), a_rd1 = S::left_read(wm, lj, lg, 1);
-    const int b_rd = S::right_read_base(lg) + lj * (int)sizeof(T);
+    const int b_rd = S::right_read_base(lg) - S::kLeftBytes + lj * (int)sizeof(T);   // relative to the right tile
     const int b_rc0 = (wn * 16 * WT + 16 * lg) * (int)sizeof(T);
 
-    auto multiply = [&](const unsigned char *cur) __attribute__((always_inline)) {
+    auto multiply = [&](const unsigned char *left, const unsigned char *right) __attribute__((always_inline)) {
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
             V af[WT];
 #pragma unroll
-            for (int ti = 0; ti < WT; ++ti) af[ti] = *reinterpret_cast<const V *>(cur + (h ? a_rd1 : a_rd0) + ti * 16 * APitch);
+            for (int ti = 0; ti < WT; ++ti) af[ti] = *reinterpret_cast<const V *>(left + (h ? a_rd1 : a_rd0) + ti * 16 * APitch);
 #pragma unroll
             for (int q = 0; q < VN; ++q) {
                 const int kk = h * VN + q;
                 T bf[WT];
 #pragma unroll
                 for (int tj = 0; tj < WT; ++tj)
-                    bf[tj] = *reinterpret_cast<const T *>(cur + b_rd + kk * BPitch + ((b_rc0 + tj * kRot) & (BPitch - 1)));
+                    bf[tj] = *reinterpret_cast<const T *>(right + b_rd + kk * BPitch + ((b_rc0 + tj * kRot) & (BPitch - 1)));
 #pragma unroll
                 for (int ti = 0; ti < WT; ++ti) {
                     const T a = reinterpret_cast<const T *>(&af[ti])[q];
@@ -243,11 +254,12 @@ __global__ __launch_bounds__(kRectThreads, WT == 4 ? 2 : 4) void rect_gemm_kerne
         }
         if constexpr (DMA) {
             if (more) dma(nxt);
-            multiply(cur);
+            if constexpr (RES) multiply(left_panel + c_kb * S::kLeftBytes, cur);
+            else multiply(cur, cur + kRightAt);
             dma_done();
         } else {
             if (more) fetch();
-            multiply(cur);
+            multiply(cur, cur + kRightAt);
             if (more) stash(nxt);
         }
         __syncthreads();
@@ -288,6 +300,11 @@ hipError_t launch_rect_v(const RectParams &p, dim3 grid, hipStream_t stream)
     if constexpr (MODE == kRectDma) {
         // the direct-to-LDS variant holds its two stages in static LDS
         static_assert(2 * stage_bytes<T, WT>(true) <= 65536, "static LDS of the direct-to-LDS variant");
+        // a short inner dimension walked over several column tiles: the left panel stays in LDS
+        if (p.slices == 1 && p.K <= kResBlocks * Tile<T>::BK && p.ctiles > 1) {
+            hipLaunchKernelGGL((rect_gemm_kernel<T, WT, MODE, true>), grid, dim3(kRectThreads), 0, stream, p);
+            return hipGetLastError();
+        }
         hipLaunchKernelGGL((rect_gemm_kernel<T, WT, MODE>), grid, dim3(kRectThreads), 0, stream, p);
         return hipGetLastError();
     }

@@ -102,6 +102,17 @@ template <typename T, int WT, bool DMA> struct TileStaging {
             to_lds(gb, stage + kLeftBytes + slot(i));
         }
     }
+    // The same for one side only: the left tile to `dst`, or the right tile to `dst`.
+    __device__ __forceinline__ void fetch_left_to_lds(const T *L, size_t ldl, int lrow0, int k0, unsigned char *dst) const
+    {
+#pragma unroll
+        for (int i = 0; i < WT; ++i) to_lds(L + (size_t)(lrow0 + left_row(i)) * ldl + k0 + a_kv, dst + slot(i));
+    }
+    __device__ __forceinline__ void fetch_right_to_lds(const T *R, size_t ldr, int col0, int k0, unsigned char *dst) const
+    {
+#pragma unroll
+        for (int i = 0; i < WT; ++i) to_lds(R + (size_t)(k0 + right_row(i)) * ldr + col0 + right_col(i), dst + slot(i));
+    }
     static __device__ __forceinline__ void to_lds(const T *g, unsigned char *lds)
     {
         __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)g,
@@ -117,6 +128,7 @@ template <typename T, int WT, bool DMA> struct TileStaging {
         return row + (DMA ? ((2 * lg + h) ^ ((lj >> 1) & 7)) * 16 : lg * 32 + 16 * h);
     }
     static __device__ __forceinline__ int right_read_base(int lg) { return kLeftBytes + (lg * KQ) * BPitch; }
+    static constexpr int kRightBytes = BK * BPitch;
 };
 
 }  // namespace expmk
